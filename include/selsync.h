@@ -1,0 +1,257 @@
+/*
+ * selsync.h -- C ABI of the MI355X-native SelSync per-step hot path.
+ *
+ * SelSync ("Accelerating Distributed ML Training via Selective Synchronization")
+ * decides every training step between a purely local SGD update and a
+ * synchronisation of all workers, by tracking how much the squared gradient norm
+ * has changed (Sec. III-A/B, Alg. 1).  This library runs that per-step path for K
+ * worker replicas resident in the HBM of ONE gpu (gfx950):
+ *
+ *   a1  ||g_k||^2 for every worker k, one fused multi-tensor reduction   (Alg. 1 line 8)
+ *   a2  windowed-EWMA smoothing, Delta(g_i) of Eq. 2, flag_k = Delta_k >= delta,
+ *       sync = OR_k flag_k                                               (Sec. III-A/B, Alg. 1 lines 8, 10-13)
+ *   a3  fused SGD(momentum, weight decay) local update                   (Alg. 1 line 9, Sec. IV-A recipes)
+ *   a4  parameter aggregation: mean over the K replicas written to the
+ *       global model and back into every replica                         (Alg. 1 lines 14-15)
+ *
+ * Conventions
+ *   - Every function returns an int32_t status (SELSYNC_OK == 0).  No exception
+ *     crosses the boundary.  selsync_last_error() gives a message for the last
+ *     failure on that context.
+ *   - "device pointer" = HIP device memory on the GPU that was current when the
+ *     context was created.  "host pointer" = ordinary host memory.
+ *   - The CALLER owns every tensor buffer; the library never frees or reallocates
+ *     them.  Descriptors are copied at plan time; the data pointers must stay valid
+ *     (and the memory allocated) until all work enqueued with that plan has finished.
+ *   - Tensors are contiguous.  Pointers need only element alignment; tensors whose
+ *     pointers are all 16-byte aligned take the 128-bit vector path.
+ *   - Buffers that are written (params, momenta, masters, global) must not overlap
+ *     each other or the gradients; this is checked at plan time.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work
+ *     is ordered on that stream.  Per-step calls never allocate memory and never
+ *     synchronise the host unless `blocking` is non-zero.
+ *   - One context may be used by one host thread at a time.
+ */
+#ifndef SELSYNC_H
+#define SELSYNC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ---------------------------------------------------------- */
+#define SELSYNC_OK                  0
+#define SELSYNC_ERR_INVALID_ARG     1   /* null pointer, bad count, bad config value, overlapping buffers */
+#define SELSYNC_ERR_SHAPE_MISMATCH  2   /* lists differ in tensor count or numel */
+#define SELSYNC_ERR_DTYPE           3   /* unsupported dtype or dtype combination */
+#define SELSYNC_ERR_OOM             4   /* host or device allocation failed */
+#define SELSYNC_ERR_HIP             5   /* a HIP runtime call failed (see selsync_last_error) */
+#define SELSYNC_ERR_NOT_DEVICE_MEM  6   /* a tensor pointer is not device memory of the context's GPU */
+#define SELSYNC_ERR_STATE           7   /* call not valid for this plan/context (e.g. no gradients bound) */
+#define SELSYNC_WARN_NONFINITE    100   /* blocking read saw a non-finite ||g||^2; results are still written */
+
+/* ---- element types --------------------------------------------------------- */
+#define SELSYNC_F32   0   /* IEEE binary32 */
+#define SELSYNC_BF16  1   /* bfloat16: upper 16 bits of binary32 */
+
+/* ---- plain-data descriptors -------------------------------------------------- */
+
+/* One contiguous tensor.  data: device pointer (may be NULL only if numel == 0). */
+typedef struct selsync_tensor {
+    void   *data;
+    int64_t numel;
+    int32_t dtype;      /* SELSYNC_F32 or SELSYNC_BF16 */
+    int32_t reserved;   /* must be 0 */
+} selsync_tensor;
+
+/* A list of tensors (one model replica's gradients, parameters, ...).  `tensors`
+ * is a HOST pointer to `count` descriptors; it is read during the call only. */
+typedef struct selsync_tensor_list {
+    const selsync_tensor *tensors;
+    int32_t count;
+    int32_t reserved;   /* must be 0 */
+} selsync_tensor_list;
+
+/* Inputs of Alg. 1 that concern the tracker, plus the smoothing constants of Sec. III-A. */
+typedef struct selsync_config {
+    int32_t num_workers;   /* K >= 1: replicas held on this GPU (the cluster size N of Alg. 1)        */
+    int32_t window;        /* EWMA window in iterations, >= 1 (the paper uses 25); 0 selects 25        */
+    double  delta;         /* threshold on the relative gradient change, >= 0 (+inf allowed)          */
+    double  alpha;         /* smoothing factor in (0,1]; <= 0 selects num_workers/100 (Sec. III-A)     */
+} selsync_config;
+
+/* Hyper-parameters of the local update (Alg. 1 line 9 with the Sec. IV-A recipes):
+ *   gh = grad_scale*g;  d = gh + weight_decay*w;  m = first ? d : momentum*m + d;  w = w - lr*m
+ * evaluated in fp32 with one rounding per operation (no fused multiply-add). */
+typedef struct selsync_sgd {
+    float   lr;
+    float   momentum;
+    float   weight_decay;
+    float   grad_scale;    /* multiplies every gradient element before use (also in the norm); 1 = none */
+    int32_t first_step;    /* 1: momentum buffers are uninitialised (m = d); 0: they are valid;
+                              -1: decide automatically (first local update since create/reset)        */
+} selsync_sgd;
+
+/* Cumulative counters (LSSR is Eq. 4; max_delta is the extremum M of Sec. III-B over finite values). */
+typedef struct selsync_stats {
+    int64_t steps_local;
+    int64_t steps_sync;
+    double  lssr;          /* steps_local / (steps_local + steps_sync); NaN before the first step */
+    double  max_delta;
+    int64_t nonfinite_steps;   /* steps on which some worker's ||g||^2 was not finite */
+} selsync_stats;
+
+/* Launch-shape knobs (all kernels are bandwidth bound; these exist for measurement).
+ * A value <= 0 keeps the built-in default. */
+typedef struct selsync_tuning {
+    int32_t chunk_elems;       /* elements per chunk of the multi-tensor chunk table (multiple of 8192) */
+    int32_t blocks_per_cu;     /* persistent workgroups per compute unit for the streaming kernels      */
+    int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
+    int32_t reserved;
+} selsync_tuning;
+
+typedef struct selsync_ctx  selsync_ctx;    /* opaque: tracker state, counters, workspace owner */
+typedef struct selsync_plan selsync_plan;   /* opaque: chunk tables for one binding of tensor lists */
+
+/* ---- lifecycle --------------------------------------------------------------- */
+
+/* Create a context on the current HIP device: allocates the device-side tracker
+ * state (K windows, counters) and a pinned host mirror.  *out is set on success. */
+int32_t selsync_create(const selsync_config *cfg, selsync_ctx **out);
+
+/* Waits for the device, frees everything the context owns.  Plans made from it must be
+ * destroyed first.  NULL is accepted. */
+int32_t selsync_destroy(selsync_ctx *ctx);
+
+/* Clear windows, previous smoothed values, counters and the automatic first-step
+ * marker, ordered on `stream`. */
+int32_t selsync_reset(selsync_ctx *ctx, void *stream);
+
+/* Change delta (the slider of Sec. III-B) for subsequent steps, ordered on `stream`. */
+int32_t selsync_set_delta(selsync_ctx *ctx, double delta, void *stream);
+
+/* Set launch-shape knobs used by plans created afterwards. */
+int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t);
+
+/* Message for the last error on this context (never NULL; valid until the next call). */
+const char *selsync_last_error(const selsync_ctx *ctx);
+
+/* Static name of a status code. */
+const char *selsync_status_string(int32_t status);
+
+/* ---- plan -------------------------------------------------------------------- */
+
+/*
+ * Bind tensor lists and build the chunk tables (host) and upload them (device);
+ * allocates the per-chunk partial-sum workspace.  All arrays of lists are HOST
+ * pointers to K = num_workers lists.
+ *
+ *   grads   [K] gradients g_k.           F32, or BF16 in mixed mode.  May be NULL: then only
+ *                                         selsync_aggregate_params is valid on the plan.
+ *   params  [K] worker replicas w_k.     F32; in mixed mode the BF16 working copies.
+ *   momenta [K] momentum buffers m_k.    F32.  NULL together with grads.
+ *   master  [K] fp32 master parameters.  NULL in fp32 mode; required in mixed mode.
+ *   global      the global model.        F32 (the fp32 master in mixed mode).
+ *   global_lowp BF16 copy of the global model; NULL in fp32 mode, required in mixed mode.
+ *
+ * Every list must have the same tensor count and per-tensor numel.  Mixed mode is
+ * selected by master != NULL.  Errors: INVALID_ARG, SHAPE_MISMATCH, DTYPE,
+ * NOT_DEVICE_MEM, OOM, HIP.  On error *out is NULL and nothing is leaked.
+ */
+int32_t selsync_plan_create(selsync_ctx *ctx,
+                            const selsync_tensor_list *grads,
+                            const selsync_tensor_list *params,
+                            const selsync_tensor_list *momenta,
+                            const selsync_tensor_list *master,
+                            const selsync_tensor_list *global,
+                            const selsync_tensor_list *global_lowp,
+                            selsync_plan **out);
+
+/* Waits for the device and frees the plan.  NULL is accepted. */
+int32_t selsync_plan_destroy(selsync_plan *plan);
+
+/* Sizes of a plan: tensors per replica, parameters per replica, chunks of the
+ * update table (all replicas) and of the aggregation table.  Any output may be NULL. */
+int32_t selsync_plan_info(const selsync_plan *plan, int32_t *num_tensors, int64_t *num_params,
+                          int32_t *update_chunks, int32_t *aggregate_chunks);
+
+/*
+ * Pure host helper (no GPU needed): the chunking rule of the multi-tensor chunk table
+ * for ONE replica.  Every tensor is cut from element 0 into pieces of chunk_elems
+ * (<= 0: the default) with one shorter last piece; empty tensors produce no chunk.
+ * Writes up to `capacity` entries of (tensor index, first element, element count) to
+ * the HOST arrays (each may be NULL) and the total number of chunks to *num_chunks.
+ */
+int32_t selsync_chunk_table_preview(const int64_t *numel, int32_t num_tensors, int32_t chunk_elems,
+                                    int32_t capacity, int32_t *tensor_out, int64_t *offset_out,
+                                    int32_t *count_out, int32_t *num_chunks);
+
+/* ---- the per-step path ---------------------------------------------------------- */
+
+/*
+ * RelativeGradChange for all K workers (Alg. 1 lines 8, 10-13; Eq. 2; Sec. III-A/B):
+ * x_k = ||grad_scale*g_k||^2 over every tensor of worker k (fp64 accumulation,
+ * deterministic), pushed into worker k's window; S_k = weight-normalised EWMA over the
+ * window; Delta_k = |S_k - S_k_prev| / S_k_prev; flag_k = Delta_k >= delta;
+ * sync = OR_k flag_k; the local/sync counters advance.  The decision stays on the
+ * device for selsync_aggregate_params.  If `blocking` != 0 the call waits for the
+ * stream and fills the HOST outputs (each may be NULL): norm_sq_out[K], delta_out[K],
+ * flags_out[K], sync_out[1]; it then returns SELSYNC_WARN_NONFINITE if some x_k was
+ * not finite (that worker's Delta is +inf and its flag is set).
+ */
+int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *plan, float grad_scale, void *stream,
+                                  int32_t blocking, double *norm_sq_out, double *delta_out,
+                                  int32_t *flags_out, int32_t *sync_out);
+
+/*
+ * Local update of all K replicas in place (Alg. 1 line 9; unconditional).  Mixed mode
+ * updates the fp32 masters and rewrites the BF16 copies by round-to-nearest-even.
+ * lr == 0 leaves every parameter bit-unchanged.
+ */
+int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream);
+
+/*
+ * Parameter aggregation (Alg. 1 lines 14-15): wbar = (sum_k w_k)/K in fp64, rounded
+ * once to fp32, written to the global model and to all K replicas (mixed mode: masters
+ * averaged, every BF16 copy refreshed).  Momentum buffers are not touched.
+ *   mode 0: only if the device-side decision of the last tracking call is "sync"
+ *           (the kernel is launched and exits at once otherwise);
+ *   mode 1: always.
+ */
+int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan, int32_t mode, void *stream);
+
+/*
+ * One whole iteration of Alg. 1 for all K workers: tracking and local update fused
+ * into ONE pass over the gradients (g is read once), then the predicated aggregation.
+ * Results are identical to selsync_track_grad_change + selsync_local_step +
+ * selsync_aggregate_params(mode 0) in that order.  Outputs as for tracking.
+ */
+int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
+                     int32_t blocking, double *norm_sq_out, double *delta_out,
+                     int32_t *flags_out, int32_t *sync_out);
+
+/* ---- observability ---------------------------------------------------------------- */
+
+/* Blocking fetch of the last step's device-side results (same outputs as tracking). */
+int32_t selsync_read_decision(selsync_ctx *ctx, void *stream, double *norm_sq_out, double *delta_out,
+                              int32_t *flags_out, int32_t *sync_out);
+
+/* Blocking fetch of the cumulative counters (Eq. 4). */
+int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_stats *out);
+
+/*
+ * Per-kernel timing with HIP events recorded on the caller's stream around every
+ * launch.  enable != 0 starts collecting (up to max_launches launches per kernel kind,
+ * further launches are not timed); enable == 0 stops.  kind: 0 = streaming
+ * update/norm kernel, 1 = tracker kernel, 2 = aggregation kernel.  The summary waits
+ * for the recorded events, returns count and summed milliseconds, and clears them.
+ */
+int32_t selsync_profile_enable(selsync_ctx *ctx, int32_t enable, int32_t max_launches);
+int32_t selsync_profile_summary(selsync_ctx *ctx, int32_t kind, int64_t *count, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SELSYNC_H */

@@ -1,0 +1,886 @@
+// Host side of the SelSync C ABI: contexts, plans (validation + chunk tables),
+// per-step entry points and observability.  Every step of the path runs in the
+// kernels of selsync_kernels.hip; this file only validates, builds tables once at
+// plan time, and enqueues launches on the caller's stream.
+#include "../../include/selsync.h"
+#include "selsync_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <climits>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace selsync;
+
+namespace {
+
+constexpr int kDefaultChunkElems = 65536;
+constexpr int kDefaultBlocksPerCu = 8;
+constexpr int kMaxWorkers = 1024;
+constexpr int kMaxWindow = 65536;
+
+struct ProfRec {
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct selsync_ctx {
+    selsync_config cfg;
+    int device = 0;
+    int num_cus = 256;
+    selsync_tuning tuning{0, 0, -1, 0};
+    // device state: one allocation, sub-pointers in td
+    void *d_state = nullptr;
+    size_t out_bytes = 0;          // bytes of the DecisionHeader block incl. the K-arrays
+    TrackerDev td{};
+    void *h_out = nullptr;         // pinned mirror of the decision block
+    int64_t local_steps = 0;       // local updates enqueued since create/reset (automatic first-step)
+    int live_plans = 0;
+    std::string err;
+    // profiling
+    bool prof_on = false;
+    int prof_cap = 0;
+    std::vector<ProfRec> prof_pool[3];
+    int prof_used[3] = {0, 0, 0};
+};
+
+struct selsync_plan {
+    selsync_ctx *ctx = nullptr;
+    int K = 0, T = 0;
+    int64_t P = 0;
+    bool mixed = false;
+    bool has_grads = false;
+    int n_upd_chunks = 0, n_agg_chunks = 0;
+    void *d_blob = nullptr;        // all tables in one allocation
+    TensorRec *d_recs = nullptr;
+    ChunkRec *d_chunks = nullptr;
+    int32_t *d_chunk_begin = nullptr;
+    double *d_partials = nullptr;
+    AggChunkRec *d_agg_chunks = nullptr;
+    AggTables agg{};
+    LaunchCfg upd_cfg{1, 1};
+    LaunchCfg agg_cfg{1, 1};
+};
+
+namespace {
+
+int32_t fail(selsync_ctx *ctx, int32_t code, const char *fmt, ...)
+{
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return fail((ctx), e_ == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP,     \
+                        "%s failed: %s", #expr, hipGetErrorString(e_));                           \
+    } while (0)
+
+int32_t check_device(selsync_ctx *ctx)
+{
+    int dev = -1;
+    HIP_TRY(ctx, hipGetDevice(&dev));
+    if (dev != ctx->device)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "current HIP device %d is not the context's device %d", dev,
+                    ctx->device);
+    return SELSYNC_OK;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+size_t dtype_size(int32_t dt) { return dt == SELSYNC_BF16 ? 2 : 4; }
+
+// Profiling brackets around one launch.
+struct ProfScope {
+    selsync_ctx *ctx;
+    int kind;
+    hipStream_t s;
+    ProfRec *rec = nullptr;
+    ProfScope(selsync_ctx *c, int k, hipStream_t st) : ctx(c), kind(k), s(st)
+    {
+        if (ctx->prof_on && ctx->prof_used[kind] < ctx->prof_cap) {
+            rec = &ctx->prof_pool[kind][ctx->prof_used[kind]++];
+            (void)hipEventRecord(rec->start, s);
+        }
+    }
+    ~ProfScope()
+    {
+        if (rec)
+            (void)hipEventRecord(rec->stop, s);
+    }
+};
+
+struct Interval {
+    uintptr_t lo, hi;
+    bool written;
+};
+
+// Validate one [K] array of lists against the reference shape; collect intervals.
+int32_t check_lists(selsync_ctx *ctx, const char *what, const selsync_tensor_list *lists, int K, int T,
+                    const std::vector<int64_t> &numel, int32_t want_dtype, bool written,
+                    std::vector<Interval> &ivals)
+{
+    for (int k = 0; k < K; ++k) {
+        const selsync_tensor_list &L = lists[k];
+        if (L.count != T)
+            return fail(ctx, SELSYNC_ERR_SHAPE_MISMATCH, "%s[%d] has %d tensors, expected %d", what, k, L.count, T);
+        if (T > 0 && L.tensors == nullptr)
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "%s[%d].tensors is NULL", what, k);
+        for (int t = 0; t < T; ++t) {
+            const selsync_tensor &x = L.tensors[t];
+            if (x.numel != numel[t])
+                return fail(ctx, SELSYNC_ERR_SHAPE_MISMATCH, "%s[%d] tensor %d has %lld elements, expected %lld",
+                            what, k, t, (long long)x.numel, (long long)numel[t]);
+            if (x.dtype != SELSYNC_F32 && x.dtype != SELSYNC_BF16)
+                return fail(ctx, SELSYNC_ERR_DTYPE, "%s[%d] tensor %d has unknown dtype %d", what, k, t, x.dtype);
+            if (x.dtype != want_dtype)
+                return fail(ctx, SELSYNC_ERR_DTYPE, "%s[%d] tensor %d has dtype %d, expected %d", what, k, t,
+                            x.dtype, want_dtype);
+            if (x.numel == 0)
+                continue;
+            if (x.data == nullptr)
+                return fail(ctx, SELSYNC_ERR_INVALID_ARG, "%s[%d] tensor %d has NULL data", what, k, t);
+            const size_t es = dtype_size(x.dtype);
+            if (reinterpret_cast<uintptr_t>(x.data) % es != 0)
+                return fail(ctx, SELSYNC_ERR_INVALID_ARG, "%s[%d] tensor %d is not aligned to its element size",
+                            what, k, t);
+            hipPointerAttribute_t attr;
+            hipError_t e = hipPointerGetAttributes(&attr, x.data);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(ctx, SELSYNC_ERR_NOT_DEVICE_MEM, "%s[%d] tensor %d: pointer %p is not known to HIP",
+                            what, k, t, x.data);
+            }
+            if (attr.type != hipMemoryTypeDevice || attr.device != ctx->device)
+                return fail(ctx, SELSYNC_ERR_NOT_DEVICE_MEM,
+                            "%s[%d] tensor %d: pointer %p is not device memory of GPU %d", what, k, t, x.data,
+                            ctx->device);
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(x.data);
+            ivals.push_back({lo, lo + (uintptr_t)x.numel * es, written});
+        }
+    }
+    return SELSYNC_OK;
+}
+
+int32_t check_overlap(selsync_ctx *ctx, std::vector<Interval> &iv)
+{
+    // Sorted sweep.  Read-only buffers may overlap each other (the same gradient may be
+    // bound to several workers); a written buffer may overlap nothing.
+    std::sort(iv.begin(), iv.end(), [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
+    uintptr_t max_hi = 0;     // furthest end of any interval seen so far
+    uintptr_t max_hi_w = 0;   // furthest end of any written interval seen so far
+    for (size_t i = 0; i < iv.size(); ++i) {
+        if (iv[i].lo < max_hi_w)
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "a tensor buffer overlaps a written buffer near %p",
+                        (void *)iv[i].lo);
+        if (iv[i].written && iv[i].lo < max_hi)
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "a written tensor buffer overlaps another buffer near %p",
+                        (void *)iv[i].lo);
+        max_hi = std::max(max_hi, iv[i].hi);
+        if (iv[i].written)
+            max_hi_w = std::max(max_hi_w, iv[i].hi);
+    }
+    return SELSYNC_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// The chunking rule of the multi-tensor tables: every tensor is cut, from element 0,
+// into pieces of `chunk` elements with one shorter last piece; empty tensors give none.
+template <typename Emit>
+void split_tensor(int64_t numel, int chunk, Emit emit)
+{
+    for (int64_t off = 0; off < numel; off += chunk)
+        emit(off, std::min<int64_t>(chunk, numel - off));
+}
+
+int effective_chunk(const selsync_ctx *ctx)
+{
+    return ctx->tuning.chunk_elems > 0 ? ctx->tuning.chunk_elems : kDefaultChunkElems;
+}
+
+int32_t fetch_decision(selsync_ctx *ctx, hipStream_t s, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                       int32_t *sync_out, DecisionHeader *hdr_out)
+{
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->h_out, ctx->td.out, ctx->out_bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    const int K = ctx->cfg.num_workers;
+    const char *base = static_cast<const char *>(ctx->h_out);
+    const DecisionHeader *hdr = reinterpret_cast<const DecisionHeader *>(base);
+    const double *nrm = reinterpret_cast<const double *>(base + sizeof(DecisionHeader));
+    const double *dlt = nrm + K;
+    const int32_t *flg = reinterpret_cast<const int32_t *>(dlt + 2 * K);
+    if (norm_sq_out)
+        std::memcpy(norm_sq_out, nrm, sizeof(double) * K);
+    if (delta_out)
+        std::memcpy(delta_out, dlt, sizeof(double) * K);
+    if (flags_out)
+        std::memcpy(flags_out, flg, sizeof(int32_t) * K);
+    if (sync_out)
+        *sync_out = hdr->sync;
+    if (hdr_out)
+        *hdr_out = *hdr;
+    return hdr->nonfinite_now ? SELSYNC_WARN_NONFINITE : SELSYNC_OK;
+}
+
+int32_t resolve_sgd(selsync_ctx *ctx, const selsync_sgd *sgd, SgdArgs *out)
+{
+    if (!sgd)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "sgd is NULL");
+    if (sgd->first_step < -1 || sgd->first_step > 1)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "sgd.first_step must be -1, 0 or 1");
+    out->lr = sgd->lr;
+    out->mu = sgd->momentum;
+    out->wd = sgd->weight_decay;
+    out->gs = sgd->grad_scale;
+    out->first = sgd->first_step < 0 ? (ctx->local_steps == 0 ? 1 : 0) : sgd->first_step;
+    return SELSYNC_OK;
+}
+
+int32_t check_plan(selsync_ctx *ctx, selsync_plan *plan, bool need_grads)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!plan)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->ctx != ctx)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "plan belongs to a different context");
+    if (need_grads && !plan->has_grads)
+        return fail(ctx, SELSYNC_ERR_STATE, "plan was created without gradients/momenta");
+    return check_device(ctx);
+}
+
+}  // namespace
+
+// =============================================================================== lifecycle
+
+extern "C" const char *selsync_status_string(int32_t status)
+{
+    switch (status) {
+    case SELSYNC_OK: return "SELSYNC_OK";
+    case SELSYNC_ERR_INVALID_ARG: return "SELSYNC_ERR_INVALID_ARG";
+    case SELSYNC_ERR_SHAPE_MISMATCH: return "SELSYNC_ERR_SHAPE_MISMATCH";
+    case SELSYNC_ERR_DTYPE: return "SELSYNC_ERR_DTYPE";
+    case SELSYNC_ERR_OOM: return "SELSYNC_ERR_OOM";
+    case SELSYNC_ERR_HIP: return "SELSYNC_ERR_HIP";
+    case SELSYNC_ERR_NOT_DEVICE_MEM: return "SELSYNC_ERR_NOT_DEVICE_MEM";
+    case SELSYNC_ERR_STATE: return "SELSYNC_ERR_STATE";
+    case SELSYNC_WARN_NONFINITE: return "SELSYNC_WARN_NONFINITE";
+    default: return "SELSYNC_UNKNOWN_STATUS";
+    }
+}
+
+extern "C" const char *selsync_last_error(const selsync_ctx *ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+extern "C" int32_t selsync_create(const selsync_config *cfg, selsync_ctx **out)
+{
+    if (!out)
+        return SELSYNC_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!cfg)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (cfg->num_workers < 1 || cfg->num_workers > kMaxWorkers)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (cfg->window < 0 || cfg->window > kMaxWindow)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!(cfg->delta >= 0.0))   // rejects negatives and NaN, accepts +inf
+        return SELSYNC_ERR_INVALID_ARG;
+    if (cfg->alpha > 1.0 || cfg->alpha != cfg->alpha)
+        return SELSYNC_ERR_INVALID_ARG;
+
+    selsync_ctx *ctx = new (std::nothrow) selsync_ctx();
+    if (!ctx)
+        return SELSYNC_ERR_OOM;
+    ctx->cfg = *cfg;
+    if (ctx->cfg.window == 0)
+        ctx->cfg.window = 25;
+    if (ctx->cfg.alpha <= 0.0)
+        ctx->cfg.alpha = (double)ctx->cfg.num_workers / 100.0;
+    if (ctx->cfg.alpha > 1.0)
+        ctx->cfg.alpha = 1.0;
+    const int K = ctx->cfg.num_workers, W = ctx->cfg.window;
+
+    auto bail = [&](int32_t code) {
+        if (ctx->d_state)
+            (void)hipFree(ctx->d_state);
+        if (ctx->h_out)
+            (void)hipHostFree(ctx->h_out);
+        delete ctx;
+        return code;
+    };
+
+    if (hipGetDevice(&ctx->device) != hipSuccess)
+        return bail(SELSYNC_ERR_HIP);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess)
+        return bail(SELSYNC_ERR_HIP);
+    ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    // layout of the single state allocation
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    ctx->out_bytes = sizeof(DecisionHeader) + sizeof(double) * 3 * K + sizeof(int32_t) * K;
+    const size_t o_out = take(ctx->out_bytes);
+    const size_t o_hist = take(sizeof(double) * (size_t)K * W);
+    const size_t o_len = take(sizeof(int32_t) * K);
+    const size_t o_head = take(sizeof(int32_t) * K);
+    const size_t o_sprev = take(sizeof(double) * K);
+    const size_t o_hasprev = take(sizeof(int32_t) * K);
+    const size_t o_weights = take(sizeof(double) * W);
+    const size_t o_thr = take(sizeof(double));
+    hipError_t e = hipMalloc(&ctx->d_state, off);
+    if (e != hipSuccess)
+        return bail(e == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP);
+    e = hipHostMalloc(&ctx->h_out, ctx->out_bytes, hipHostMallocDefault);
+    if (e != hipSuccess)
+        return bail(e == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP);
+
+    char *b = static_cast<char *>(ctx->d_state);
+    TrackerDev &td = ctx->td;
+    td.out = reinterpret_cast<DecisionHeader *>(b + o_out);
+    td.out_norm_sq = reinterpret_cast<double *>(b + o_out + sizeof(DecisionHeader));
+    td.out_delta = td.out_norm_sq + K;
+    td.out_smoothed = td.out_delta + K;
+    td.out_flags = reinterpret_cast<int32_t *>(td.out_smoothed + K);
+    td.hist = reinterpret_cast<double *>(b + o_hist);
+    td.len = reinterpret_cast<int32_t *>(b + o_len);
+    td.head = reinterpret_cast<int32_t *>(b + o_head);
+    td.s_prev = reinterpret_cast<double *>(b + o_sprev);
+    td.has_prev = reinterpret_cast<int32_t *>(b + o_hasprev);
+    td.weights = reinterpret_cast<const double *>(b + o_weights);
+    td.delta_thr = reinterpret_cast<double *>(b + o_thr);
+    td.K = K;
+    td.window = W;
+
+    // EWMA weights: a sample of age j weighs (1-alpha)^j (Sec. III-A smoothing)
+    std::vector<double> wts(W);
+    for (int j = 0; j < W; ++j)
+        wts[j] = std::pow(1.0 - ctx->cfg.alpha, (double)j);
+    if (hipMemcpy(b + o_weights, wts.data(), sizeof(double) * W, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(b + o_thr, &ctx->cfg.delta, sizeof(double), hipMemcpyHostToDevice) != hipSuccess ||
+        launch_reset(td, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess)
+        return bail(SELSYNC_ERR_HIP);
+
+    *out = ctx;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_destroy(selsync_ctx *ctx)
+{
+    if (!ctx)
+        return SELSYNC_OK;
+    if (ctx->live_plans != 0)
+        return fail(ctx, SELSYNC_ERR_STATE, "%d plan(s) still alive", ctx->live_plans);
+    (void)hipDeviceSynchronize();
+    for (int k = 0; k < 3; ++k)
+        for (auto &r : ctx->prof_pool[k]) {
+            (void)hipEventDestroy(r.start);
+            (void)hipEventDestroy(r.stop);
+        }
+    if (ctx->d_state)
+        (void)hipFree(ctx->d_state);
+    if (ctx->h_out)
+        (void)hipHostFree(ctx->h_out);
+    delete ctx;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_reset(selsync_ctx *ctx, void *stream)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    HIP_TRY(ctx, launch_reset(ctx->td, static_cast<hipStream_t>(stream)));
+    ctx->local_steps = 0;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_set_delta(selsync_ctx *ctx, double delta, void *stream)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!(delta >= 0.0))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "delta must be >= 0");
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    HIP_TRY(ctx, launch_set_delta(ctx->td, delta, static_cast<hipStream_t>(stream)));
+    ctx->cfg.delta = delta;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
+{
+    if (!ctx || !t)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (t->chunk_elems > 0 && (t->chunk_elems % kTileElems != 0 || t->chunk_elems > (1 << 24)))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kTileElems);
+    if (t->blocks_per_cu > 64)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "blocks_per_cu must be <= 64");
+    ctx->tuning = *t;
+    return SELSYNC_OK;
+}
+
+// =============================================================================== plan
+
+extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_list *grads,
+                                       const selsync_tensor_list *params, const selsync_tensor_list *momenta,
+                                       const selsync_tensor_list *master, const selsync_tensor_list *global,
+                                       const selsync_tensor_list *global_lowp, selsync_plan **out)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!out)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    if (!params || !global)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "params and global are required");
+    if ((grads == nullptr) != (momenta == nullptr))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "grads and momenta must be given together");
+    const bool mixed = master != nullptr;
+    if (mixed != (global_lowp != nullptr))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "master and global_lowp must be given together (mixed mode)");
+
+    const int K = ctx->cfg.num_workers;
+    const int T = params[0].count;
+    if (T < 0)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "negative tensor count");
+    if (T > 0 && params[0].tensors == nullptr)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "params[0].tensors is NULL");
+    std::vector<int64_t> numel(T);
+    int64_t P = 0;
+    for (int t = 0; t < T; ++t) {
+        numel[t] = params[0].tensors[t].numel;
+        if (numel[t] < 0)
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "tensor %d has negative numel", t);
+        P += numel[t];
+    }
+
+    std::vector<Interval> ivals;
+    ivals.reserve((size_t)T * (4 * K + 2));
+    const int32_t lowp = SELSYNC_BF16;
+    if ((rc = check_lists(ctx, "params", params, K, T, numel, mixed ? lowp : SELSYNC_F32, true, ivals)))
+        return rc;
+    if (grads) {
+        if ((rc = check_lists(ctx, "grads", grads, K, T, numel, mixed ? lowp : SELSYNC_F32, false, ivals)))
+            return rc;
+        if ((rc = check_lists(ctx, "momenta", momenta, K, T, numel, SELSYNC_F32, true, ivals)))
+            return rc;
+    }
+    if (mixed) {
+        if ((rc = check_lists(ctx, "master", master, K, T, numel, SELSYNC_F32, true, ivals)))
+            return rc;
+        if ((rc = check_lists(ctx, "global_lowp", global_lowp, 1, T, numel, lowp, true, ivals)))
+            return rc;
+    }
+    if ((rc = check_lists(ctx, "global", global, 1, T, numel, SELSYNC_F32, true, ivals)))
+        return rc;
+    if ((rc = check_overlap(ctx, ivals)))
+        return rc;
+
+    const int chunk = effective_chunk(ctx);
+    const int bpc = ctx->tuning.blocks_per_cu > 0 ? ctx->tuning.blocks_per_cu : kDefaultBlocksPerCu;
+    const int nt = ctx->tuning.nontemporal >= 0 ? ctx->tuning.nontemporal : 1;
+
+    // ---- host tables
+    std::vector<TensorRec> recs;
+    std::vector<ChunkRec> chunks;
+    std::vector<int32_t> chunk_begin(K + 1, 0);
+    if (grads) {
+        recs.resize((size_t)K * T);
+        for (int k = 0; k < K; ++k) {
+            chunk_begin[k] = (int32_t)chunks.size();
+            for (int t = 0; t < T; ++t) {
+                TensorRec r{};
+                r.g = grads[k].tensors[t].data;
+                r.m = static_cast<float *>(momenta[k].tensors[t].data);
+                if (mixed) {
+                    r.w = static_cast<float *>(master[k].tensors[t].data);
+                    r.lowp = static_cast<uint16_t *>(params[k].tensors[t].data);
+                } else {
+                    r.w = static_cast<float *>(params[k].tensors[t].data);
+                    r.lowp = nullptr;
+                }
+                recs[(size_t)k * T + t] = r;
+                const bool al = aligned16(r.g) && aligned16(r.w) && aligned16(r.m) && (!mixed || aligned16(r.lowp));
+                split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
+                    ChunkRec c;
+                    c.rec = (uint32_t)((size_t)k * T + t);
+                    c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u);
+                    c.off = (uint64_t)off;
+                    chunks.push_back(c);
+                });
+            }
+        }
+        chunk_begin[K] = (int32_t)chunks.size();
+    }
+
+    std::vector<AggChunkRec> agg_chunks;
+    std::vector<float *> agg_w((size_t)T * K);
+    std::vector<uint16_t *> agg_c(mixed ? (size_t)T * K : 0);
+    std::vector<float *> agg_g(T);
+    std::vector<uint16_t *> agg_gc(mixed ? T : 0);
+    for (int t = 0; t < T; ++t) {
+        bool al = true;
+        for (int k = 0; k < K; ++k) {
+            if (mixed) {
+                agg_w[(size_t)t * K + k] = static_cast<float *>(master[k].tensors[t].data);
+                agg_c[(size_t)t * K + k] = static_cast<uint16_t *>(params[k].tensors[t].data);
+                al = al && aligned16(agg_c[(size_t)t * K + k]);
+            } else {
+                agg_w[(size_t)t * K + k] = static_cast<float *>(params[k].tensors[t].data);
+            }
+            al = al && aligned16(agg_w[(size_t)t * K + k]);
+        }
+        agg_g[t] = static_cast<float *>(global[0].tensors[t].data);
+        al = al && aligned16(agg_g[t]);
+        if (mixed) {
+            agg_gc[t] = static_cast<uint16_t *>(global_lowp[0].tensors[t].data);
+            al = al && aligned16(agg_gc[t]);
+        }
+        split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
+            AggChunkRec c;
+            c.t = (uint32_t)t;
+            c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u);
+            c.off = (uint64_t)off;
+            agg_chunks.push_back(c);
+        });
+    }
+
+    selsync_plan *plan = new (std::nothrow) selsync_plan();
+    if (!plan)
+        return fail(ctx, SELSYNC_ERR_OOM, "out of host memory");
+    plan->ctx = ctx;
+    plan->K = K;
+    plan->T = T;
+    plan->P = P;
+    plan->mixed = mixed;
+    plan->has_grads = grads != nullptr;
+    plan->n_upd_chunks = (int)chunks.size();
+    plan->n_agg_chunks = (int)agg_chunks.size();
+
+    // ---- one device allocation for every table
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + std::max<size_t>(bytes, 8), 256);
+        return o;
+    };
+    const size_t o_recs = take(recs.size() * sizeof(TensorRec));
+    const size_t o_chunks = take(chunks.size() * sizeof(ChunkRec));
+    const size_t o_begin = take(chunk_begin.size() * sizeof(int32_t));
+    const size_t o_part = take(chunks.size() * sizeof(double));
+    const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
+    const size_t o_aw = take(agg_w.size() * sizeof(float *));
+    const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
+    const size_t o_ag = take(agg_g.size() * sizeof(float *));
+    const size_t o_agc = take(agg_gc.size() * sizeof(uint16_t *));
+
+    std::vector<char> blob(off, 0);
+    auto put = [&](size_t o, const void *src, size_t bytes) {
+        if (bytes)
+            std::memcpy(blob.data() + o, src, bytes);
+    };
+    put(o_recs, recs.data(), recs.size() * sizeof(TensorRec));
+    put(o_chunks, chunks.data(), chunks.size() * sizeof(ChunkRec));
+    put(o_begin, chunk_begin.data(), chunk_begin.size() * sizeof(int32_t));
+    put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
+    put(o_aw, agg_w.data(), agg_w.size() * sizeof(float *));
+    put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
+    put(o_ag, agg_g.data(), agg_g.size() * sizeof(float *));
+    put(o_agc, agg_gc.data(), agg_gc.size() * sizeof(uint16_t *));
+
+    hipError_t e = hipMalloc(&plan->d_blob, off);
+    if (e == hipSuccess)
+        e = hipMemcpy(plan->d_blob, blob.data(), off, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (plan->d_blob)
+            (void)hipFree(plan->d_blob);
+        delete plan;
+        return fail(ctx, e == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP, "plan tables: %s",
+                    hipGetErrorString(e));
+    }
+    char *b = static_cast<char *>(plan->d_blob);
+    plan->d_recs = reinterpret_cast<TensorRec *>(b + o_recs);
+    plan->d_chunks = reinterpret_cast<ChunkRec *>(b + o_chunks);
+    plan->d_chunk_begin = reinterpret_cast<int32_t *>(b + o_begin);
+    plan->d_partials = reinterpret_cast<double *>(b + o_part);
+    plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
+    plan->agg.w = reinterpret_cast<float *const *>(b + o_aw);
+    plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
+    plan->agg.global = reinterpret_cast<float *const *>(b + o_ag);
+    plan->agg.glowp = reinterpret_cast<uint16_t *const *>(b + o_agc);
+
+    plan->upd_cfg.grid = std::max(1, ctx->num_cus * bpc);
+    plan->upd_cfg.nontemporal = nt;
+    plan->agg_cfg = plan->upd_cfg;
+
+    ctx->live_plans += 1;
+    *out = plan;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_plan_destroy(selsync_plan *plan)
+{
+    if (!plan)
+        return SELSYNC_OK;
+    (void)hipDeviceSynchronize();
+    if (plan->d_blob)
+        (void)hipFree(plan->d_blob);
+    if (plan->ctx)
+        plan->ctx->live_plans -= 1;
+    delete plan;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_plan_info(const selsync_plan *plan, int32_t *num_tensors, int64_t *num_params,
+                                     int32_t *update_chunks, int32_t *aggregate_chunks)
+{
+    if (!plan)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (num_tensors)
+        *num_tensors = plan->T;
+    if (num_params)
+        *num_params = plan->P;
+    if (update_chunks)
+        *update_chunks = plan->n_upd_chunks;
+    if (aggregate_chunks)
+        *aggregate_chunks = plan->n_agg_chunks;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_chunk_table_preview(const int64_t *numel, int32_t num_tensors, int32_t chunk_elems,
+                                               int32_t capacity, int32_t *tensor_out, int64_t *offset_out,
+                                               int32_t *count_out, int32_t *num_chunks)
+{
+    if (!num_chunks || num_tensors < 0 || (num_tensors > 0 && !numel))
+        return SELSYNC_ERR_INVALID_ARG;
+    const int chunk = chunk_elems > 0 ? chunk_elems : kDefaultChunkElems;
+    if (chunk % kTileElems != 0 || chunk > (1 << 24))
+        return SELSYNC_ERR_INVALID_ARG;
+    int64_t total = 0;
+    for (int t = 0; t < num_tensors; ++t) {
+        if (numel[t] < 0)
+            return SELSYNC_ERR_INVALID_ARG;
+        split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
+            if (total < capacity) {
+                if (tensor_out)
+                    tensor_out[total] = t;
+                if (offset_out)
+                    offset_out[total] = off;
+                if (count_out)
+                    count_out[total] = (int32_t)n;
+            }
+            ++total;
+        });
+    }
+    if (total > INT32_MAX)
+        return SELSYNC_ERR_INVALID_ARG;
+    *num_chunks = (int32_t)total;
+    return SELSYNC_OK;
+}
+
+// =============================================================================== per-step path
+
+extern "C" int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *plan, float grad_scale, void *stream,
+                                             int32_t blocking, double *norm_sq_out, double *delta_out,
+                                             int32_t *flags_out, int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SgdArgs a{0.f, 0.f, 0.f, grad_scale, 0};
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
+                                   plan->d_partials, a, plan->upd_cfg, s));
+    }
+    {
+        ProfScope p(ctx, 1, s);
+        HIP_TRY(ctx, launch_track(ctx->td, plan->d_partials, plan->d_chunk_begin, s));
+    }
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    SgdArgs a;
+    if ((rc = resolve_sgd(ctx, sgd, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
+                                   plan->d_partials, a, plan->upd_cfg, s));
+    }
+    ctx->local_steps += 1;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan, int32_t mode, void *stream)
+{
+    int32_t rc = check_plan(ctx, plan, false);
+    if (rc)
+        return rc;
+    if (mode != 0 && mode != 1)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "mode must be 0 (if flagged) or 1 (always)");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 2, s);
+        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+                                      &ctx->td.out->sync, mode, plan->agg_cfg, s));
+    }
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
+                                int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                                int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    SgdArgs a;
+    if ((rc = resolve_sgd(ctx, sgd, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
+                                   plan->d_partials, a, plan->upd_cfg, s));
+    }
+    ctx->local_steps += 1;
+    {
+        ProfScope p(ctx, 1, s);
+        HIP_TRY(ctx, launch_track(ctx->td, plan->d_partials, plan->d_chunk_begin, s));
+    }
+    {
+        ProfScope p(ctx, 2, s);
+        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+                                      &ctx->td.out->sync, 0, plan->agg_cfg, s));
+    }
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
+// =============================================================================== observability
+
+extern "C" int32_t selsync_read_decision(selsync_ctx *ctx, void *stream, double *norm_sq_out, double *delta_out,
+                                         int32_t *flags_out, int32_t *sync_out)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    return fetch_decision(ctx, static_cast<hipStream_t>(stream), norm_sq_out, delta_out, flags_out, sync_out,
+                          nullptr);
+}
+
+extern "C" int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_stats *out)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!out)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "out is NULL");
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    DecisionHeader h;
+    rc = fetch_decision(ctx, static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, nullptr, &h);
+    if (rc != SELSYNC_OK && rc != SELSYNC_WARN_NONFINITE)
+        return rc;
+    out->steps_local = h.steps_local;
+    out->steps_sync = h.steps_sync;
+    const int64_t tot = h.steps_local + h.steps_sync;
+    out->lssr = tot ? (double)h.steps_local / (double)tot : std::nan("");
+    out->max_delta = h.max_delta;
+    out->nonfinite_steps = h.nonfinite_steps;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_profile_enable(selsync_ctx *ctx, int32_t enable, int32_t max_launches)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    if (!enable) {
+        ctx->prof_on = false;
+        return SELSYNC_OK;
+    }
+    if (max_launches < 1 || max_launches > (1 << 20))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "max_launches out of range");
+    for (int k = 0; k < 3; ++k) {
+        while ((int)ctx->prof_pool[k].size() < max_launches) {
+            ProfRec r;
+            HIP_TRY(ctx, hipEventCreate(&r.start));
+            hipError_t e = hipEventCreate(&r.stop);
+            if (e != hipSuccess) {
+                (void)hipEventDestroy(r.start);
+                return fail(ctx, SELSYNC_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+            }
+            ctx->prof_pool[k].push_back(r);
+        }
+        ctx->prof_used[k] = 0;
+    }
+    ctx->prof_cap = max_launches;
+    ctx->prof_on = true;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_profile_summary(selsync_ctx *ctx, int32_t kind, int64_t *count, double *total_ms)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (kind < 0 || kind > 2 || !count || !total_ms)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "bad kind or NULL output");
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    double tot = 0.0;
+    const int n = ctx->prof_used[kind];
+    for (int i = 0; i < n; ++i) {
+        ProfRec &r = ctx->prof_pool[kind][i];
+        HIP_TRY(ctx, hipEventSynchronize(r.stop));
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, r.start, r.stop));
+        tot += ms;
+    }
+    *count = n;
+    *total_ms = tot;
+    ctx->prof_used[kind] = 0;
+    return SELSYNC_OK;
+}

@@ -1,0 +1,107 @@
+// Internal declarations shared by the host side (context, plans, validation) and
+// the device side (kernels and their launchers) of the SelSync library.  Nothing in
+// here is part of the public C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace selsync {
+
+// ---- device-visible tables --------------------------------------------------
+
+// Pointers of one (worker k, tensor t) pair; index k*T + t.
+struct TensorRec {
+    const void *g;   // gradient (fp32, or bf16 in mixed mode)
+    float *w;        // fp32 parameter (mixed mode: fp32 master)
+    float *m;        // fp32 momentum buffer
+    uint16_t *lowp;  // bf16 working copy (mixed mode only)
+};
+
+// One unit of work of the multi-tensor streaming kernel: `n` consecutive elements
+// of one tensor of one worker, starting at element `off`.
+struct ChunkRec {
+    uint32_t rec;      // index into the TensorRec table
+    uint32_t n_flags;  // bits 0..27: element count; bit 31: all pointers 16-byte aligned
+    uint64_t off;      // first element
+};
+
+// One unit of work of the aggregation kernel: `n` consecutive elements of tensor t
+// across all K replicas.
+struct AggChunkRec {
+    uint32_t t;
+    uint32_t n_flags;
+    uint64_t off;
+};
+
+constexpr uint32_t kChunkAligned = 0x80000000u;
+constexpr uint32_t kChunkCountMask = 0x0fffffffu;
+
+// Aggregation pointer tables (device arrays).
+struct AggTables {
+    float *const *w;           // [T*K]  replica parameters (mixed: masters), index t*K + k
+    uint16_t *const *lowp;     // [T*K]  bf16 copies (mixed only)
+    float *const *global;      // [T]
+    uint16_t *const *glowp;    // [T]    (mixed only)
+};
+
+// Results of the last step plus the cumulative counters; one contiguous block so a
+// blocking read is a single device-to-host copy.  Followed in memory by
+//   double norm_sq[K]; double delta[K]; double smoothed[K]; int32_t flags[K];
+struct DecisionHeader {
+    int64_t steps_local;
+    int64_t steps_sync;
+    int64_t nonfinite_steps;
+    double max_delta;
+    int32_t sync;            // OR over the K flags of the last step
+    int32_t nonfinite_now;   // some ||g||^2 of the last step was not finite
+};
+
+// Device-side state of the K significance trackers.
+struct TrackerDev {
+    double *hist;            // [K][window] ring buffers of raw ||g||^2
+    int32_t *len;            // [K] samples stored (<= window)
+    int32_t *head;           // [K] slot the next sample is written to
+    double *s_prev;          // [K] previous smoothed value
+    int32_t *has_prev;       // [K]
+    const double *weights;   // [window] (1-alpha)^j
+    double *delta_thr;       // [1] threshold delta
+    DecisionHeader *out;
+    double *out_norm_sq;     // [K]
+    double *out_delta;       // [K]
+    double *out_smoothed;    // [K]
+    int32_t *out_flags;      // [K]
+    int32_t K;
+    int32_t window;
+};
+
+struct SgdArgs {
+    float lr, mu, wd, gs;
+    int32_t first;
+};
+
+// Launch shape for the streaming kernels.
+struct LaunchCfg {
+    int grid;
+    int nontemporal;
+};
+
+enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };
+
+// ---- launchers (selsync_kernels.hip) --------------------------------------------
+
+// Elements one workgroup iteration covers; chunk sizes are multiples of this.
+constexpr int kTileElems = 8192;
+
+hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
+                         double *partials, const SgdArgs &sgd, const LaunchCfg &cfg, hipStream_t s);
+
+hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s);
+
+hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
+                            const int32_t *sync_flag, int mode, const LaunchCfg &cfg, hipStream_t s);
+
+hipError_t launch_reset(const TrackerDev &td, hipStream_t s);
+hipError_t launch_set_delta(const TrackerDev &td, double delta, hipStream_t s);
+
+}  // namespace selsync

@@ -1,0 +1,684 @@
+// CDNA4 (gfx950) kernels of the SelSync per-step path and their launchers.
+//
+//   k_stream     multi-tensor-apply over a chunk table: fused local SGD update
+//                (Alg. 1 line 9) and/or per-chunk sum of squared gradients
+//                (the ||g_i||^2 of Alg. 1 line 8).  One read of g serves both.
+//   k_track      deterministic final pass over the per-chunk partials, then the
+//                windowed EWMA, Eq. 2, the delta rule and the any-worker OR
+//                (Sec. III-A/B, Alg. 1 lines 8, 10-13), all K workers in one block.
+//   k_aggregate  K-way replica mean written to the global model and back to every
+//                replica (Alg. 1 lines 14-15), predicated on the device-side decision.
+//
+// All three are HBM-bandwidth bound (<= 0.4 flop/byte), so there is no MFMA use:
+// the design is 128-bit coalesced accesses, many independent loads in flight per
+// lane, a persistent grid sized to the CU count, and no atomics (every partial has
+// a fixed slot and every sum a fixed order, so results are run-to-run identical).
+//
+// fp32 arithmetic of the update is written to round once per operation; the file
+// is compiled with -ffp-contract=off and the pragma below so no multiply-add is fused.
+#include "selsync_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace selsync {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T *p)
+{
+    if (NT)
+        return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T *p, T v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// bf16 <-> fp32.  Widening is exact; narrowing rounds to nearest, ties to even, and
+// keeps NaN a quiet NaN.
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ uint32_t bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+
+// Sum over the 64 lanes of a wavefront in a fixed butterfly order; result in lane 0.
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v += __shfl_down(v, o, 64);
+    return v;
+}
+
+// One element of the fused pass.  gh = fl(gs*g); x += gh^2 in fp64 (the product of two
+// fp32 values is exact in fp64); d = fl(gh + fl(wd*w)); m = first ? d : fl(fl(mu*m) + d);
+// w = fl(w - fl(lr*m)).
+template <bool UPD, bool NORM>
+__device__ __forceinline__ void elem(float g, float &w, float &m, const SgdArgs &a, double &acc)
+{
+    const float gh = a.gs * g;
+    if (NORM)
+        acc = __builtin_fma((double)gh, (double)gh, acc);
+    if (UPD) {
+        const float dec = a.wd * w;
+        const float d = gh + dec;
+        float mom = d;
+        if (!a.first) {
+            const float mm = a.mu * m;
+            mom = mm + d;
+        }
+        const float stepv = a.lr * mom;
+        m = mom;
+        w = w - stepv;
+    }
+}
+
+// Four consecutive elements held in 128-bit registers.
+template <bool UPD, bool NORM>
+__device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, const SgdArgs &a, double &acc)
+{
+    float w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
+    float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
+    elem<UPD, NORM>(g.x, w0, m0, a, acc);
+    elem<UPD, NORM>(g.y, w1, m1, a, acc);
+    elem<UPD, NORM>(g.z, w2, m2, a, acc);
+    elem<UPD, NORM>(g.w, w3, m3, a, acc);
+    w.x = w0; w.y = w1; w.z = w2; w.w = w3;
+    m.x = m0; m.y = m1; m.z = m2; m.w = m3;
+}
+
+// ---------------------------------------------------------------- k_stream
+
+// One tile of BLOCK*U vectors of an aligned fp32 chunk.
+template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
+__device__ __forceinline__ void tile_f32(const f32x4 *__restrict__ g4, f32x4 *__restrict__ w4, f32x4 *__restrict__ m4,
+                                         uint32_t base, uint32_t nvec, const SgdArgs &a, double &acc)
+{
+    f32x4 gv[U], wv[U], mv[U];
+    const uint32_t tid = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = base + u * BLOCK + tid;
+        gv[u] = 0.f;
+        wv[u] = 0.f;
+        mv[u] = 0.f;
+        if (!GUARD || i < nvec) {
+            gv[u] = ld<NT>(g4 + i);
+            if (UPD) {
+                wv[u] = ld<NT>(w4 + i);
+                if (!a.first)
+                    mv[u] = ld<NT>(m4 + i);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = base + u * BLOCK + tid;
+        if (!GUARD || i < nvec) {
+            elem4<UPD, NORM>(gv[u], wv[u], mv[u], a, acc);
+            if (UPD) {
+                st<NT>(w4 + i, wv[u]);
+                st<NT>(m4 + i, mv[u]);
+            }
+        }
+    }
+}
+
+// One tile of BLOCK*U groups of 8 elements of an aligned mixed-precision chunk:
+// 8 bf16 gradients (16 B), 2x4 fp32 masters, 2x4 fp32 momenta, 8 bf16 copies out.
+template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
+__device__ __forceinline__ void tile_mixed(const u32x4 *__restrict__ g8, f32x4 *__restrict__ w4, f32x4 *__restrict__ m4,
+                                           u32x4 *__restrict__ c8, uint32_t base, uint32_t nvec, const SgdArgs &a,
+                                           double &acc)
+{
+    u32x4 gv[U];
+    f32x4 wv[U][2], mv[U][2];
+    const uint32_t tid = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = base + u * BLOCK + tid;
+        gv[u] = 0u;
+        wv[u][0] = wv[u][1] = 0.f;
+        mv[u][0] = mv[u][1] = 0.f;
+        if (!GUARD || i < nvec) {
+            gv[u] = ld<NT>(g8 + i);
+            if (UPD) {
+                wv[u][0] = ld<NT>(w4 + 2 * i);
+                wv[u][1] = ld<NT>(w4 + 2 * i + 1);
+                if (!a.first) {
+                    mv[u][0] = ld<NT>(m4 + 2 * i);
+                    mv[u][1] = ld<NT>(m4 + 2 * i + 1);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = base + u * BLOCK + tid;
+        if (!GUARD || i < nvec) {
+            f32x4 ga, gb;
+            ga.x = bf16_lo(gv[u].x); ga.y = bf16_hi(gv[u].x); ga.z = bf16_lo(gv[u].y); ga.w = bf16_hi(gv[u].y);
+            gb.x = bf16_lo(gv[u].z); gb.y = bf16_hi(gv[u].z); gb.z = bf16_lo(gv[u].w); gb.w = bf16_hi(gv[u].w);
+            elem4<UPD, NORM>(ga, wv[u][0], mv[u][0], a, acc);
+            elem4<UPD, NORM>(gb, wv[u][1], mv[u][1], a, acc);
+            if (UPD) {
+                st<NT>(w4 + 2 * i, wv[u][0]);
+                st<NT>(w4 + 2 * i + 1, wv[u][1]);
+                st<NT>(m4 + 2 * i, mv[u][0]);
+                st<NT>(m4 + 2 * i + 1, mv[u][1]);
+                u32x4 cv;
+                cv.x = bf16_pack(wv[u][0].x, wv[u][0].y);
+                cv.y = bf16_pack(wv[u][0].z, wv[u][0].w);
+                cv.z = bf16_pack(wv[u][1].x, wv[u][1].y);
+                cv.w = bf16_pack(wv[u][1].z, wv[u][1].w);
+                st<NT>(c8 + i, cv);
+            }
+        }
+    }
+}
+
+// Element-at-a-time processing of elements [begin, n) of a chunk (unaligned tensors
+// and the ragged tail of aligned ones).  Still coalesced: lane i takes element i.
+template <int BLOCK, bool MIXED, bool UPD, bool NORM>
+__device__ __forceinline__ void scalar_range(const TensorRec &r, uint64_t off, uint32_t begin, uint32_t n,
+                                             const SgdArgs &a, double &acc)
+{
+    for (uint32_t i = begin + threadIdx.x; i < n; i += BLOCK) {
+        const uint64_t e = off + i;
+        float g;
+        if (MIXED)
+            g = __uint_as_float(((uint32_t) reinterpret_cast<const uint16_t *>(r.g)[e]) << 16);
+        else
+            g = reinterpret_cast<const float *>(r.g)[e];
+        float w = 0.f, m = 0.f;
+        if (UPD) {
+            w = r.w[e];
+            if (!a.first)
+                m = r.m[e];
+        }
+        elem<UPD, NORM>(g, w, m, a, acc);
+        if (UPD) {
+            r.w[e] = w;
+            r.m[e] = m;
+            if (MIXED)
+                r.lowp[e] = (uint16_t)bf16_bits(w);
+        }
+    }
+}
+
+template <int BLOCK, int U, bool MIXED, int MODE, bool NT>
+__global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ recs,
+                                                  const ChunkRec *__restrict__ chunks, int nchunks,
+                                                  double *__restrict__ partials, SgdArgs a)
+{
+    constexpr bool UPD = MODE != kNormOnly;
+    constexpr bool NORM = MODE != kUpdateOnly;
+    constexpr uint32_t VEC = MIXED ? 8 : 4;
+    __shared__ double red[BLOCK / 64];
+
+    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const ChunkRec ch = chunks[c];
+        const TensorRec r = recs[ch.rec];
+        const uint32_t n = ch.n_flags & kChunkCountMask;
+        double acc = 0.0;
+
+        if (ch.n_flags & kChunkAligned) {
+            const uint32_t nvec = n / VEC;
+            f32x4 *w4 = reinterpret_cast<f32x4 *>(r.w + ch.off);
+            f32x4 *m4 = reinterpret_cast<f32x4 *>(r.m + ch.off);
+            if (MIXED) {
+                const u32x4 *g8 = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
+                u32x4 *c8 = reinterpret_cast<u32x4 *>(r.lowp + ch.off);
+                uint32_t base = 0;
+                for (; base + BLOCK * U <= nvec; base += BLOCK * U)
+                    tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g8, w4, m4, c8, base, nvec, a, acc);
+                if (base < nvec)
+                    tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g8, w4, m4, c8, base, nvec, a, acc);
+            } else {
+                const f32x4 *g4 = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(r.g) + ch.off);
+                uint32_t base = 0;
+                for (; base + BLOCK * U <= nvec; base += BLOCK * U)
+                    tile_f32<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, base, nvec, a, acc);
+                if (base < nvec)
+                    tile_f32<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, base, nvec, a, acc);
+            }
+            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, nvec * VEC, n, a, acc);
+        } else {
+            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, n, a, acc);
+        }
+
+        if (NORM) {
+            // level 1: wavefront shuffle; level 2: LDS across the block's wavefronts,
+            // summed by one thread in wave order -> one fixed slot per chunk.
+            const double s = wave_sum(acc);
+            if ((threadIdx.x & 63) == 0)
+                red[threadIdx.x >> 6] = s;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double t = 0.0;
+#pragma unroll
+                for (int w = 0; w < BLOCK / 64; ++w)
+                    t += red[w];
+                partials[c] = t;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---------------------------------------------------------------- k_track
+
+constexpr int kTrackBlock = 1024;
+
+// Wave v owns workers v, v+16, ...: it sums that worker's per-chunk partials in a
+// fixed order (lane-strided, then butterfly), evaluates the windowed EWMA with one
+// window sample per lane, and lane 0 applies Eq. 2 and the delta rule.
+__global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const double *__restrict__ partials,
+                                                       const int32_t *__restrict__ chunk_begin)
+{
+    __shared__ int32_t s_flag[kTrackBlock / 64];
+    __shared__ int32_t s_nonfinite[kTrackBlock / 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nwaves = kTrackBlock / 64;
+    const int W = td.window;
+    const double thr = *td.delta_thr;
+    int32_t my_flag = 0, my_nonfinite = 0;
+    double my_max = 0.0;
+
+    for (int k = wave; k < td.K; k += nwaves) {
+        // a1, final pass
+        double acc = 0.0;
+        if (partials != nullptr) {
+            const int b = chunk_begin[k], e = chunk_begin[k + 1];
+            for (int i = b + lane; i < e; i += 64)
+                acc += partials[i];
+        }
+        double x = wave_sum(acc);
+        x = __shfl(x, 0, 64);
+
+        // a2: window holds the previous `len` samples; the new one is age 0
+        double *h = td.hist + (size_t)k * W;
+        const int len = td.len[k];
+        const int head = td.head[k];
+        const int len_new = len < W ? len + 1 : W;
+        double num = 0.0, den = 0.0;
+        for (int j = lane; j < len_new; j += 64) {
+            const double wgt = td.weights[j];
+            int pos = head - j;
+            if (pos < 0)
+                pos += W;
+            const double v = (j == 0) ? x : h[pos];
+            num += wgt * v;
+            den += wgt;
+        }
+        num = wave_sum(num);
+        den = wave_sum(den);
+        if (lane == 0) {
+            const double s = num / den;
+            double d;
+            if (!td.has_prev[k]) {
+                d = 0.0;
+            } else {
+                const double sp = td.s_prev[k];
+                if (sp == 0.0 && s == 0.0) {
+                    d = 0.0;
+                } else {
+                    d = fabs(s - sp) / sp;
+                    if (d != d)
+                        d = __builtin_inf();
+                }
+            }
+            const bool finite_x = (x - x) == 0.0;
+            if (!finite_x) {
+                d = __builtin_inf();
+                my_nonfinite = 1;
+            }
+            const int32_t f = (d >= thr) ? 1 : 0;
+            my_flag |= f;
+            if (d < __builtin_inf() && d > my_max)
+                my_max = d;
+            h[head] = x;
+            td.head[k] = (head + 1 == W) ? 0 : head + 1;
+            td.len[k] = len_new;
+            td.s_prev[k] = s;
+            td.has_prev[k] = 1;
+            td.out_norm_sq[k] = x;
+            td.out_delta[k] = d;
+            td.out_smoothed[k] = s;
+            td.out_flags[k] = f;
+        }
+    }
+
+    __shared__ double s_max[kTrackBlock / 64];
+    if (lane == 0) {
+        s_flag[wave] = my_flag;
+        s_nonfinite[wave] = my_nonfinite;
+        s_max[wave] = my_max;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int32_t any = 0, nf = 0;
+        double mx = td.out->max_delta;
+        for (int w = 0; w < nwaves; ++w) {
+            any |= s_flag[w];
+            nf |= s_nonfinite[w];
+            if (s_max[w] > mx)
+                mx = s_max[w];
+        }
+        td.out->sync = any;
+        td.out->nonfinite_now = nf;
+        td.out->max_delta = mx;
+        td.out->nonfinite_steps += nf;
+        if (any)
+            td.out->steps_sync += 1;
+        else
+            td.out->steps_local += 1;
+    }
+}
+
+__global__ void k_reset(TrackerDev td)
+{
+    const int n = td.K * td.window;
+    for (int i = threadIdx.x; i < n; i += blockDim.x)
+        td.hist[i] = 0.0;
+    for (int k = threadIdx.x; k < td.K; k += blockDim.x) {
+        td.len[k] = 0;
+        td.head[k] = 0;
+        td.s_prev[k] = 0.0;
+        td.has_prev[k] = 0;
+        td.out_norm_sq[k] = 0.0;
+        td.out_delta[k] = 0.0;
+        td.out_smoothed[k] = 0.0;
+        td.out_flags[k] = 0;
+    }
+    if (threadIdx.x == 0) {
+        td.out->steps_local = 0;
+        td.out->steps_sync = 0;
+        td.out->nonfinite_steps = 0;
+        td.out->max_delta = 0.0;
+        td.out->sync = 0;
+        td.out->nonfinite_now = 0;
+    }
+}
+
+__global__ void k_set_delta(TrackerDev td, double delta) { *td.delta_thr = delta; }
+
+// ---------------------------------------------------------------- k_aggregate
+
+// Mean of K fp32 values in fp64, summed k = 0..K-1, divided by K, rounded once to fp32.
+// For K a power of two the division is a multiplication by the exact reciprocal.
+__device__ __forceinline__ float finish_mean(double s, int K, double invK, int pow2)
+{
+    const double mean = pow2 ? s * invK : s / (double)K;
+    return (float)mean;
+}
+
+template <int BLOCK, int U, int KC, bool MIXED, bool NT>
+__global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restrict__ chunks, int nchunks,
+                                                     AggTables tabs, int K, double invK, int pow2,
+                                                     const int32_t *__restrict__ sync_flag, int mode)
+{
+    if (mode == 0 && *sync_flag == 0)
+        return;
+    const uint32_t tid = threadIdx.x;
+
+    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const AggChunkRec ch = chunks[c];
+        const uint32_t n = ch.n_flags & kChunkCountMask;
+        float *const *wtab = tabs.w + (size_t)ch.t * K;
+        uint16_t *const *ctab = MIXED ? tabs.lowp + (size_t)ch.t * K : nullptr;
+        float *gp = tabs.global[ch.t] + ch.off;
+        uint16_t *gcp = MIXED ? tabs.glowp[ch.t] + ch.off : nullptr;
+        uint32_t done = 0;
+
+        if constexpr (KC > 0) {
+            // K known at compile time: replica pointers live in registers, all K*U loads
+            // of a tile are issued before the first use.
+            float *wp[KC];
+            uint16_t *cp[KC];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                wp[k] = wtab[k] + ch.off;
+                cp[k] = MIXED ? ctab[k] + ch.off : nullptr;
+            }
+            if (ch.n_flags & kChunkAligned) {
+                const uint32_t nvec = n / 4;
+                for (uint32_t base = 0; base < nvec; base += BLOCK * U) {
+                    f32x4 v[U][KC];
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const uint32_t i = base + u * BLOCK + tid;
+                            v[u][k] = 0.f;
+                            if (i < nvec)
+                                v[u][k] = ld<NT>(reinterpret_cast<const f32x4 *>(wp[k]) + i);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t i = base + u * BLOCK + tid;
+                        if (i < nvec) {
+                            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+                            for (int k = 0; k < KC; ++k) {
+                                s0 += (double)v[u][k].x;
+                                s1 += (double)v[u][k].y;
+                                s2 += (double)v[u][k].z;
+                                s3 += (double)v[u][k].w;
+                            }
+                            f32x4 r;
+                            r.x = finish_mean(s0, KC, invK, pow2);
+                            r.y = finish_mean(s1, KC, invK, pow2);
+                            r.z = finish_mean(s2, KC, invK, pow2);
+                            r.w = finish_mean(s3, KC, invK, pow2);
+                            st<NT>(reinterpret_cast<f32x4 *>(gp) + i, r);
+                            u32x2 h;
+                            if (MIXED) {
+                                h.x = bf16_pack(r.x, r.y);
+                                h.y = bf16_pack(r.z, r.w);
+                                st<NT>(reinterpret_cast<u32x2 *>(gcp) + i, h);
+                            }
+#pragma unroll
+                            for (int k = 0; k < KC; ++k) {
+                                st<NT>(reinterpret_cast<f32x4 *>(wp[k]) + i, r);
+                                if (MIXED)
+                                    st<NT>(reinterpret_cast<u32x2 *>(cp[k]) + i, h);
+                            }
+                        }
+                    }
+                }
+                done = nvec * 4;
+            }
+            for (uint32_t i = done + tid; i < n; i += BLOCK) {
+                double s = 0.0;
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    s += (double)wp[k][i];
+                const float r = finish_mean(s, KC, invK, pow2);
+                gp[i] = r;
+                const uint16_t h = MIXED ? (uint16_t)bf16_bits(r) : (uint16_t)0;
+                if (MIXED)
+                    gcp[i] = h;
+#pragma unroll
+                for (int k = 0; k < KC; ++k) {
+                    wp[k][i] = r;
+                    if (MIXED)
+                        cp[k][i] = h;
+                }
+            }
+        } else {
+            // Any other K: same arithmetic, replica pointers re-read from the table.
+            if (ch.n_flags & kChunkAligned) {
+                const uint32_t nvec = n / 4;
+                for (uint32_t i = tid; i < nvec; i += BLOCK) {
+                    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+                    for (int k = 0; k < K; ++k) {
+                        const f32x4 v = ld<NT>(reinterpret_cast<const f32x4 *>(wtab[k] + ch.off) + i);
+                        s0 += (double)v.x;
+                        s1 += (double)v.y;
+                        s2 += (double)v.z;
+                        s3 += (double)v.w;
+                    }
+                    f32x4 r;
+                    r.x = finish_mean(s0, K, invK, pow2);
+                    r.y = finish_mean(s1, K, invK, pow2);
+                    r.z = finish_mean(s2, K, invK, pow2);
+                    r.w = finish_mean(s3, K, invK, pow2);
+                    st<NT>(reinterpret_cast<f32x4 *>(gp) + i, r);
+                    u32x2 h;
+                    if (MIXED) {
+                        h.x = bf16_pack(r.x, r.y);
+                        h.y = bf16_pack(r.z, r.w);
+                        st<NT>(reinterpret_cast<u32x2 *>(gcp) + i, h);
+                    }
+                    for (int k = 0; k < K; ++k) {
+                        st<NT>(reinterpret_cast<f32x4 *>(wtab[k] + ch.off) + i, r);
+                        if (MIXED)
+                            st<NT>(reinterpret_cast<u32x2 *>(ctab[k] + ch.off) + i, h);
+                    }
+                }
+                done = nvec * 4;
+            }
+            for (uint32_t i = done + tid; i < n; i += BLOCK) {
+                double s = 0.0;
+                for (int k = 0; k < K; ++k)
+                    s += (double)wtab[k][ch.off + i];
+                const float r = finish_mean(s, K, invK, pow2);
+                gp[i] = r;
+                const uint16_t h = MIXED ? (uint16_t)bf16_bits(r) : (uint16_t)0;
+                if (MIXED)
+                    gcp[i] = h;
+                for (int k = 0; k < K; ++k) {
+                    wtab[k][ch.off + i] = r;
+                    if (MIXED)
+                        ctab[k][ch.off + i] = h;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- dispatch helpers
+
+constexpr int kBlock = 256;
+
+template <bool MIXED, int MODE, bool NT>
+hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
+                           const SgdArgs &sgd, int grid, hipStream_t s)
+{
+    constexpr int U = MIXED ? 2 : 4;
+    hipLaunchKernelGGL((k_stream<kBlock, U, MIXED, MODE, NT>), dim3(grid), dim3(kBlock), 0, s, recs, chunks, nchunks,
+                       partials, sgd);
+    return hipGetLastError();
+}
+
+template <bool MIXED, bool NT>
+hipError_t launch_stream_m(StreamMode mode, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
+                           double *partials, const SgdArgs &sgd, int grid, hipStream_t s)
+{
+    switch (mode) {
+    case kNormOnly:
+        return launch_stream_t<MIXED, kNormOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, s);
+    case kUpdateOnly:
+        return launch_stream_t<MIXED, kUpdateOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, s);
+    default:
+        return launch_stream_t<MIXED, kUpdateAndNorm, NT>(recs, chunks, nchunks, partials, sgd, grid, s);
+    }
+}
+
+template <int KC, bool MIXED, bool NT>
+hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
+                        int mode, int grid, hipStream_t s)
+{
+    constexpr int U = (KC == 0 || KC > 4) ? 1 : 2;
+    const int pow2 = (K & (K - 1)) == 0;
+    hipLaunchKernelGGL((k_aggregate<kBlock, U, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs,
+                       K, 1.0 / (double)K, pow2, flag, mode);
+    return hipGetLastError();
+}
+
+template <bool MIXED, bool NT>
+hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
+                        int mode, int grid, hipStream_t s)
+{
+    switch (K) {
+    case 1:
+        return launch_agg_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+    case 2:
+        return launch_agg_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+    case 4:
+        return launch_agg_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+    case 8:
+        return launch_agg_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+    default:
+        return launch_agg_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- launchers
+
+hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
+                         double *partials, const SgdArgs &sgd, const LaunchCfg &cfg, hipStream_t s)
+{
+    if (nchunks <= 0)
+        return hipSuccess;
+    const int grid = cfg.grid < nchunks ? cfg.grid : nchunks;
+    if (mixed)
+        return cfg.nontemporal ? launch_stream_m<true, true>(mode, recs, chunks, nchunks, partials, sgd, grid, s)
+                               : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, s);
+    return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, s)
+                           : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, s);
+}
+
+hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_track, dim3(1), dim3(kTrackBlock), 0, s, td, partials, chunk_begin);
+    return hipGetLastError();
+}
+
+hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
+                            const int32_t *sync_flag, int mode, const LaunchCfg &cfg, hipStream_t s)
+{
+    if (nchunks <= 0)
+        return hipSuccess;
+    const int grid = cfg.grid < nchunks ? cfg.grid : nchunks;
+    if (mixed)
+        return cfg.nontemporal ? launch_agg_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s)
+                               : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s);
+    return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s)
+                           : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s);
+}
+
+hipError_t launch_reset(const TrackerDev &td, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, td);
+    return hipGetLastError();
+}
+
+hipError_t launch_set_delta(const TrackerDev &td, double delta, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_set_delta, dim3(1), dim3(1), 0, s, td, delta);
+    return hipGetLastError();
+}
+
+}  // namespace selsync

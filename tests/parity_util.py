@@ -1,0 +1,238 @@
+"""Helpers shared by the GPU parity tests: host<->device plumbing, ulp distances and a
+lock-step runner that feeds bit-identical seeded inputs to the CPU oracle and to the
+HIP library and compares them after every step."""
+from __future__ import annotations
+
+import math
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import selsync_oracle as O
+from paper_2307_07950_amd import workloads as W
+
+NORM_RTOL = 1e-5        # squared gradient norm, relative
+DELTA_ATOL = 1e-5       # decisions may differ only if |Delta - delta| <= this
+AVG_RTOL = 1e-6         # averaged parameters, relative to max(|mean|, max_k |w_k|)
+UPDATE_ULP = 1          # updated parameters / momenta, fp32 ulps
+
+
+def to_dev(a: np.ndarray, misalign: int = 0) -> torch.Tensor:
+    """Upload a host array.  uint16 arrays are bf16 bit patterns.  `misalign` > 0
+    places the tensor that many ELEMENTS past a 256-byte aligned address."""
+    if a.dtype == np.uint16:
+        t = torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16)
+    else:
+        t = torch.from_numpy(a.copy())
+    if misalign == 0:
+        return t.cuda()
+    buf = torch.empty(t.numel() + misalign + 64, dtype=t.dtype, device="cuda")
+    view = buf[misalign:misalign + t.numel()]
+    view.copy_(t)
+    return view
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    c = t.detach().cpu().contiguous()
+    if c.dtype == torch.bfloat16:
+        return c.view(torch.int16).numpy().view(np.uint16).copy()
+    return c.numpy().copy()
+
+
+def ulp_distance(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Distance in units in the last place between two fp32 arrays (ordered-integer trick)."""
+    def key(x):
+        i = np.ascontiguousarray(x, dtype=np.float32).view(np.int32).astype(np.int64)
+        return np.where(i < 0, np.int64(-(2 ** 31)) - i, i)
+    return np.abs(key(a) - key(b))
+
+
+def assert_update_close(got: np.ndarray, want: np.ndarray, what: str):
+    if got.tobytes() == want.tobytes():
+        return 0
+    d = ulp_distance(got, want)
+    both_nan = np.isnan(got) & np.isnan(want)
+    d = np.where(both_nan, 0, d)
+    worst = int(d.max()) if d.size else 0
+    assert worst <= UPDATE_ULP, "%s: %d ulp apart at index %d (got %r want %r)" % (
+        what, worst, int(d.argmax()), got.ravel()[d.argmax()], want.ravel()[d.argmax()])
+    return worst
+
+
+def assert_average_close(got: np.ndarray, want: np.ndarray, scale: np.ndarray, what: str):
+    if got.tobytes() == want.tobytes():
+        return
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    bound = AVG_RTOL * np.maximum(np.abs(want.astype(np.float64)), scale)
+    bad = err > bound
+    assert not bad.any(), "%s: %d elements off by more than 1e-6 relative (worst %g)" % (
+        what, int(bad.sum()), float((err / np.maximum(bound, 1e-300)).max()))
+
+
+class LockStep:
+    """K replicas of one tensor list on the host (oracle) and on the GPU (library)."""
+
+    def __init__(self, B, shapes_numel: Sequence[int], K: int, delta: float, window: int = 25, alpha: float = -1.0,
+                 mixed: bool = False, init_params: Optional[List[np.ndarray]] = None, misalign: int = 0,
+                 tuning: Optional[dict] = None, seed: int = 0):
+        self.B, self.K, self.mixed = B, K, mixed
+        self.numel = list(shapes_numel)
+        if init_params is None:
+            r = np.random.default_rng(seed)
+            init_params = [(r.standard_normal(n) * 0.05).astype(np.float32) for n in self.numel]
+        # host state (oracle side)
+        self.h_w = [[a.copy() for a in init_params] for _ in range(K)]          # fp32 params / masters
+        self.h_m = [[np.zeros_like(a) for a in init_params] for _ in range(K)]
+        self.h_glob = [np.zeros_like(a) for a in init_params]
+        if mixed:
+            self.h_c = [[W.round_to_bf16_bits(a) for a in init_params] for _ in range(K)]
+            self.h_gc = [np.zeros(a.size, np.uint16) for a in init_params]
+        else:
+            self.h_c, self.h_gc = None, None
+        self.oracle = O.OracleSelSync(K, delta, window, alpha)
+        # device state
+        self.d_w = [[to_dev(a, misalign) for a in self.h_w[k]] for k in range(K)]
+        self.d_m = [[to_dev(a, misalign) for a in self.h_m[k]] for k in range(K)]
+        self.d_glob = [to_dev(a, misalign) for a in self.h_glob]
+        if mixed:
+            self.d_c = [[to_dev(a, misalign) for a in self.h_c[k]] for k in range(K)]
+            self.d_gc = [to_dev(a, misalign) for a in self.h_gc]
+        self.misalign = misalign
+        self.ctx = B.SelSync(K, delta, window, alpha)
+        if tuning:
+            self.ctx.set_tuning(**tuning)
+        self.plans = {}
+        self.d_grads = {}
+        self.steps_done = 0
+        self.min_margin = math.inf
+        self.worst_norm_rel = 0.0
+        self.worst_ulp = 0
+        self.forced = 0
+
+    # ---- gradient slots
+    def bind_grads(self, slot: int, grads: List[List[np.ndarray]]):
+        """grads[k][t]: host arrays (fp32, or bf16 bits in mixed mode)."""
+        self.h_grads = getattr(self, "h_grads", {})
+        self.h_grads[slot] = grads
+        dg = [[to_dev(a, self.misalign) for a in grads[k]] for k in range(self.K)]
+        self.d_grads[slot] = dg
+        if self.mixed:
+            self.plans[slot] = self.ctx.plan(dg, self.d_c, self.d_m, self.d_glob, master=self.d_w,
+                                             global_lowp=self.d_gc)
+        else:
+            self.plans[slot] = self.ctx.plan(dg, self.d_w, self.d_m, self.d_glob)
+
+    # ---- one step on both sides
+    def step(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True,
+             compare_tensors: bool = True):
+        B = self.B
+        plan = self.plans[slot]
+        first = self.steps_done == 0
+        if fused:
+            dec = self.ctx.step(plan, lr, mu, wd, gs, first_step=int(first), blocking=True)
+        else:
+            dec = self.ctx.track_grad_change(plan, gs, blocking=True)
+            self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first))
+            self.ctx.aggregate_params(plan, always=False)
+        g = self.h_grads[slot]
+        rec = self.oracle.track(g, gs)
+        for k in range(self.K):
+            O.sgd_update(self.h_w[k], self.h_m[k], g[k], lr, mu, wd, gs, first,
+                         None if not self.mixed else self.h_c[k])
+        # --- a1 / a2 parity
+        for k in range(self.K):
+            x, y = dec.norm_sq[k], rec.norm_sq[k]
+            if math.isfinite(y):
+                rel = abs(x - y) / y if y != 0 else abs(x)
+                self.worst_norm_rel = max(self.worst_norm_rel, rel)
+                assert rel <= NORM_RTOL, "step %d worker %d: norm %r vs oracle %r" % (self.steps_done, k, x, y)
+            else:
+                assert not math.isfinite(x)
+            if math.isfinite(rec.delta[k]):
+                assert abs(dec.delta[k] - rec.delta[k]) <= 1e-9 + 1e-6 * abs(rec.delta[k]), (
+                    "step %d worker %d: Delta %r vs oracle %r" % (self.steps_done, k, dec.delta[k], rec.delta[k]))
+                self.min_margin = min(self.min_margin, abs(rec.delta[k] - self.oracle.delta))
+            else:
+                assert dec.delta[k] == rec.delta[k]
+        sync = rec.sync
+        if dec.sync != rec.sync or list(dec.flags) != list(rec.flags):
+            near = [abs(rec.delta[k] - self.oracle.delta) <= DELTA_ATOL for k in range(self.K)
+                    if dec.flags[k] != rec.flags[k]]
+            assert near and all(near), "step %d: decisions differ away from the threshold: gpu %s oracle %s" % (
+                self.steps_done, dec.flags, rec.flags)
+            sync = dec.sync          # tolerated: the oracle follows the GPU's decision
+            self.forced += 1
+            self.oracle.steps_sync += dec.sync - rec.sync
+            self.oracle.steps_local -= dec.sync - rec.sync
+        if sync:
+            pre = [np.max(np.abs(np.stack([self.h_w[k][t] for k in range(self.K)])), axis=0).astype(np.float64)
+                   for t in range(len(self.numel))]
+            O.average_params(self.h_w, self.h_glob, self.h_c, self.h_gc)
+            self._pre_scale = pre
+        self.steps_done += 1
+        if compare_tensors or sync:          # every aggregation is checked, local steps on request
+            self.compare(after_sync=bool(sync))
+        return dec, rec
+
+    def compare(self, after_sync: bool = False):
+        torch.cuda.synchronize()
+        for k in range(self.K):
+            for t in range(len(self.numel)):
+                gw, gm = to_host(self.d_w[k][t]), to_host(self.d_m[k][t])
+                self.worst_ulp = max(self.worst_ulp, assert_update_close(gm, self.h_m[k][t], "momentum[%d][%d]" % (k, t)))
+                if after_sync:
+                    assert_average_close(gw, self.h_w[k][t], self._pre_scale[t], "averaged params[%d][%d]" % (k, t))
+                else:
+                    self.worst_ulp = max(self.worst_ulp,
+                                         assert_update_close(gw, self.h_w[k][t], "params[%d][%d]" % (k, t)))
+                if self.mixed:
+                    gc = to_host(self.d_c[k][t])
+                    if gw.tobytes() == self.h_w[k][t].tobytes():
+                        assert np.array_equal(gc, self.h_c[k][t]), "bf16 copy[%d][%d]" % (k, t)
+                    else:   # master within tolerance: the copy must be the rounding of the GPU's own master
+                        assert np.array_equal(gc, W.round_to_bf16_bits(gw)), "bf16 copy[%d][%d]" % (k, t)
+        if after_sync:
+            for t in range(len(self.numel)):
+                gg = to_host(self.d_glob[t])
+                assert_average_close(gg, self.h_glob[t], self._pre_scale[t], "global[%d]" % t)
+                for k in range(self.K):     # every replica holds exactly the global model
+                    assert to_host(self.d_w[k][t]).tobytes() == gg.tobytes()
+                if self.mixed:
+                    ggc = to_host(self.d_gc[t])
+                    assert np.array_equal(ggc, W.round_to_bf16_bits(gg))
+                    for k in range(self.K):
+                        assert np.array_equal(to_host(self.d_c[k][t]), ggc)
+
+    def adopt_gpu_state(self):
+        """After a tolerated sub-ulp difference keep both sides in lock step by
+        copying the GPU tensors into the oracle's state."""
+        for k in range(self.K):
+            for t in range(len(self.numel)):
+                self.h_w[k][t][...] = to_host(self.d_w[k][t])
+                self.h_m[k][t][...] = to_host(self.d_m[k][t])
+                if self.mixed:
+                    self.h_c[k][t][...] = to_host(self.d_c[k][t])
+
+    def close(self):
+        self.ctx.close()
+
+
+def run_workload(B, wl: W.Workload, steps: Optional[int] = None, compare_every: int = 1, fused: bool = True,
+                 tuning: Optional[dict] = None, pool: Optional[int] = None) -> LockStep:
+    """Run a whole seeded workload in lock step and return the runner (with counters)."""
+    steps = wl.steps if steps is None else steps
+    pool = min(wl.pool if pool is None else pool, steps)
+    ls = LockStep(B, wl.numels, wl.num_workers, wl.delta, wl.window, -1.0, wl.mixed_bf16,
+                  init_params=W.initial_params(wl), tuning=tuning)
+    for b in range(pool):
+        ls.bind_grads(b, [W.unit_grads(wl, k, b) for k in range(wl.num_workers)])
+    sig = wl.sigmas(steps)
+    for t in range(steps):
+        cmp_now = (t % compare_every == 0) or t == steps - 1
+        dec, rec = ls.step(t % pool, wl.lr, wl.momentum, wl.weight_decay, sig[t], fused=fused,
+                           compare_tensors=cmp_now)
+    st = ls.ctx.stats()
+    assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
+    assert st["lssr"] == ls.oracle.lssr
+    return ls

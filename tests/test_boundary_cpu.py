@@ -1,0 +1,183 @@
+"""CPU-only checks of the boundary: the C-ABI library loads, exports every symbol the
+header declares, the binding prototypes cover them, argument validation that needs no
+GPU works, and the chunking rule covers every element exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "selsync.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2307_07950_amd import build
+    if build.needs_build():
+        build.build()
+    from paper_2307_07950_amd import binding
+    return binding
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(selsync_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = declared_functions()
+    assert len(names) >= 18
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "libselsync.so does not export %s" % n
+
+
+def test_binding_prototypes_match_header(B):
+    assert sorted(B.PROTOTYPES) == declared_functions()
+    for n in B.PROTOTYPES:
+        assert callable(getattr(B, n))
+
+
+def test_struct_layouts_are_plain_c(B):
+    assert ctypes.sizeof(B.selsync_tensor) == 24
+    assert ctypes.sizeof(B.selsync_tensor_list) == 16
+    assert ctypes.sizeof(B.selsync_config) == 24
+    assert ctypes.sizeof(B.selsync_sgd) == 20
+    assert ctypes.sizeof(B.selsync_stats) == 40
+    assert ctypes.sizeof(B.selsync_tuning) == 16
+
+
+def test_status_strings(B):
+    assert B.selsync_status_string(0) == b"SELSYNC_OK"
+    assert B.selsync_status_string(B.SELSYNC_ERR_DTYPE) == b"SELSYNC_ERR_DTYPE"
+    assert B.selsync_status_string(B.SELSYNC_WARN_NONFINITE) == b"SELSYNC_WARN_NONFINITE"
+    assert B.selsync_status_string(12345) == b"SELSYNC_UNKNOWN_STATUS"
+    assert B.selsync_last_error(None) == b"context is NULL"
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(num_workers=0, window=25, delta=0.3, alpha=-1.0),
+    dict(num_workers=-3, window=25, delta=0.3, alpha=-1.0),
+    dict(num_workers=4, window=-1, delta=0.3, alpha=-1.0),
+    dict(num_workers=4, window=25, delta=-0.1, alpha=-1.0),
+    dict(num_workers=4, window=25, delta=float("nan"), alpha=-1.0),
+    dict(num_workers=4, window=25, delta=0.3, alpha=1.5),
+    dict(num_workers=4, window=25, delta=0.3, alpha=float("nan")),
+])
+def test_create_rejects_bad_config_before_touching_the_gpu(B, cfg):
+    c = B.selsync_config(**cfg)
+    h = ctypes.c_void_p(1234)
+    assert B.selsync_create(ctypes.byref(c), ctypes.byref(h)) == B.SELSYNC_ERR_INVALID_ARG
+    assert h.value is None
+
+
+def test_null_arguments_are_errors_not_crashes(B):
+    h = ctypes.c_void_p()
+    assert B.selsync_create(None, ctypes.byref(h)) == B.SELSYNC_ERR_INVALID_ARG
+    c = B.selsync_config(4, 25, 0.3, -1.0)
+    assert B.selsync_create(ctypes.byref(c), None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_destroy(None) == B.SELSYNC_OK
+    assert B.selsync_plan_destroy(None) == B.SELSYNC_OK
+    assert B.selsync_reset(None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_set_delta(None, 0.1, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_plan_info(None, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_step(None, None, None, None, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_track_grad_change(None, None, 1.0, None, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_local_step(None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_aggregate_params(None, None, 0, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_get_stats(None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_read_decision(None, None, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_profile_enable(None, 1, 10) == B.SELSYNC_ERR_INVALID_ARG
+
+
+def chunk_preview(B, numel, chunk):
+    arr = (ctypes.c_int64 * max(1, len(numel)))(*numel)
+    n = ctypes.c_int32()
+    assert B.selsync_chunk_table_preview(arr, len(numel), chunk, 0, None, None, None, ctypes.byref(n)) == 0
+    cap = n.value
+    t = (ctypes.c_int32 * max(1, cap))()
+    o = (ctypes.c_int64 * max(1, cap))()
+    c = (ctypes.c_int32 * max(1, cap))()
+    assert B.selsync_chunk_table_preview(arr, len(numel), chunk, cap, t, o, c, ctypes.byref(n)) == 0
+    assert n.value == cap
+    return list(t)[:cap], list(o)[:cap], list(c)[:cap]
+
+
+@pytest.mark.parametrize("chunk", [8192, 65536, 1 << 20])
+def test_chunk_table_covers_every_element_exactly_once(B, chunk):
+    from paper_2307_07950_amd import workloads as W
+    for name in ("c1", "c2", "c3", "c4", "c5"):
+        wl = W.get(name)
+        numel = wl.numels + [0, 1, chunk, chunk + 1, chunk - 1]
+        t, o, c = chunk_preview(B, numel, chunk)
+        seen = {}
+        for ti, oi, ci in zip(t, o, c):
+            assert 0 < ci <= chunk
+            assert oi % chunk == 0                         # chunk starts keep 16-byte alignment of the tensor base
+            seen.setdefault(ti, []).append((oi, ci))
+        for ti, n in enumerate(numel):
+            pieces = sorted(seen.get(ti, []))
+            pos = 0
+            for oi, ci in pieces:
+                assert oi == pos                           # no gap, no overlap
+                pos += ci
+            assert pos == n
+            assert len(pieces) == -(-n // chunk)
+            if n == 0:
+                assert ti not in seen
+        # table order is tensor-major, offsets ascending
+        assert t == sorted(t)
+
+
+def test_chunk_table_preview_rejects_bad_arguments(B):
+    n = ctypes.c_int32()
+    arr = (ctypes.c_int64 * 2)(10, -1)
+    assert B.selsync_chunk_table_preview(arr, 2, 8192, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
+    arr = (ctypes.c_int64 * 2)(10, 5)
+    assert B.selsync_chunk_table_preview(arr, 2, 1000, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(arr, 2, 8192, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(None, 2, 8192, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(arr, 2, 0, 0, None, None, None, ctypes.byref(n)) == 0 and n.value == 2
+
+
+def test_product_path_has_no_cpu_fallback_and_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2307_07950_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.lower() or f == "workloads.py", f
+    src = open(os.path.join(pkg, "workloads.py")).read()
+    assert "import oracle" not in src and "from oracle" not in src
+    # and the oracle does not import the product
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            assert "paper_2307_07950_amd" not in open(os.path.join(ROOT, "oracle", f)).read()
+
+
+def test_workload_shapes_match_the_stated_models():
+    from paper_2307_07950_amd import workloads as W
+    for name in ("c1", "c2", "c3", "c4", "c5"):
+        wl = W.get(name)
+        assert (wl.num_tensors, wl.num_params) == W.FULL_SIZE_PARAMS[wl.name]
+    # 507 MB fp32 model size quoted for VGG11 (Sec. II-A)
+    assert round(W.get("c4").num_params * 4 / 2 ** 20) == 507
+
+
+def test_workload_generators_are_seeded_and_order_independent():
+    from paper_2307_07950_amd import workloads as W
+    wl = W.get("c1")
+    a = W.unit_grads(wl, 2, 3)
+    _ = W.unit_grads(wl, 0, 0)
+    b = W.unit_grads(wl, 2, 3)
+    for x, y in zip(a, b):
+        assert x.tobytes() == y.tobytes()
+    assert a[0].tobytes() != W.unit_grads(wl, 1, 3)[0].tobytes()
+    wl5 = W.get("c5", shrink=8)
+    g = W.unit_grads(wl5, 0, 0)
+    assert g[0].dtype == np.uint16
+    f = W.tensor_factors(wl5)
+    assert 50 < max(f) / min(f) <= 100.0 + 1e-9

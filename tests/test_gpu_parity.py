@@ -1,0 +1,429 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Bars: ||g||^2 within 1e-5 relative; updated
+parameters / momenta within 1 fp32 ulp; averaged parameters within 1e-6 relative;
+decisions identical unless |Delta - delta| <= 1e-5."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import selsync_oracle as O                          # noqa: E402
+from paper_2307_07950_amd import workloads as W                 # noqa: E402
+from tests import parity_util as PU                             # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2307_07950_amd import binding
+    return binding
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2)     # many chunks per tensor even for small tensors
+
+# tensor-size sets: tiny / ragged tails / several tiles / empty tensors / exactly one chunk
+SIZE_SETS = {
+    "tiny": [1, 2, 3, 5, 10],
+    "ragged": [4097, 8191, 8193, 65537, 7, 1023],
+    "tiles": [3 * 65536 + 13, 65536, 2 * 8192],
+    "with_empty": [0, 100, 0, 70000, 0],
+    "one": [123457],
+}
+
+
+# ================================================================= a1: squared norm
+
+@pytest.mark.parametrize("sizes", list(SIZE_SETS))
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 1, 3])
+def test_norm_matches_oracle(B, sizes, mixed, misalign):
+    numel = SIZE_SETS[sizes]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, misalign=misalign, tuning=SMALL_CHUNK, seed=1)
+    r = rng(10)
+    grads = []
+    for k in range(K):
+        gk = [(r.standard_normal(n) * 10.0 ** r.uniform(-4, 1)).astype(np.float32) for n in numel]
+        grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+    ls.bind_grads(0, grads)
+    for gs in (1.0, 0.37):
+        dec = ls.ctx.track_grad_change(ls.plans[0], gs, blocking=True)
+        for k in range(K):
+            want = O.norm_sq(grads[k], gs)
+            assert dec.norm_sq[k] == pytest.approx(want, rel=PU.NORM_RTOL)
+            assert dec.norm_sq[k] == pytest.approx(want, rel=1e-12)      # fp64 accumulation: far inside the bar
+    ls.close()
+
+
+def test_norm_invariants_zero_constant_and_determinism(B):
+    numel = [100000, 33, 70001]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=0.3, tuning=SMALL_CHUNK)
+    c = 0.5
+    ls.bind_grads(0, [[np.zeros(n, np.float32) for n in numel], [np.full(n, c, np.float32) for n in numel]])
+    dec = ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True)
+    assert dec.norm_sq[0] == 0.0
+    assert dec.norm_sq[1] == sum(numel) * c * c
+    # run-to-run bitwise determinism on random data (no atomics, fixed slots, fixed order)
+    r = rng(3)
+    g = [[r.standard_normal(n).astype(np.float32) for n in numel] for _ in range(K)]
+    ls.bind_grads(1, g)
+    first = ls.ctx.track_grad_change(ls.plans[1], 1.0, blocking=True).norm_sq
+    for _ in range(5):
+        again = ls.ctx.track_grad_change(ls.plans[1], 1.0, blocking=True).norm_sq
+        assert [x.hex() for x in again] == [x.hex() for x in first]
+    ls.close()
+
+
+def test_norm_nonfinite_gradient_sets_flag_and_warns(B):
+    numel = [5000, 9000]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=float("inf"))
+    r = rng(4)
+    g = [[r.standard_normal(n).astype(np.float32) for n in numel] for _ in range(K)]
+    g[1][1][77] = np.inf
+    ls.bind_grads(0, g)
+    dec = ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True)
+    rec = ls.oracle.track(g, 1.0)
+    assert dec.nonfinite and dec.flags == [0, 1, 0] == rec.flags and dec.sync == 1 == rec.sync
+    assert math.isinf(dec.delta[1]) and math.isinf(rec.delta[1])
+    assert ls.ctx.stats()["nonfinite_steps"] == 1
+    ls.close()
+
+
+# ================================================================= a3: local update
+
+@pytest.mark.parametrize("sizes", list(SIZE_SETS))
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_local_step_matches_oracle_over_steps(B, sizes, mixed, misalign):
+    numel = SIZE_SETS[sizes]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=float("inf"), mixed=mixed, misalign=misalign, tuning=SMALL_CHUNK, seed=2)
+    r = rng(20)
+    for slot in range(2):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    for t in range(6):
+        ls.step(t % 2, lr=0.1, mu=0.9, wd=5e-4, gs=[1.0, 0.5, 1.7][t % 3], fused=(t % 2 == 0))
+    assert ls.worst_ulp == 0          # same rounding sequence on both sides: bit-identical in practice
+    ls.close()
+
+
+def test_local_step_lr_zero_is_noop_and_plain_sgd_special_case(B):
+    numel = [40000, 17]
+    ls = PU.LockStep(B, numel, 1, delta=float("inf"), seed=5)
+    r = rng(21)
+    g = [[r.standard_normal(n).astype(np.float32) for n in numel]]
+    ls.bind_grads(0, g)
+    w0 = [PU.to_host(t) for t in ls.d_w[0]]
+    ls.ctx.local_step(ls.plans[0], lr=0.0, momentum=0.9, weight_decay=5e-4, first_step=1)
+    for t in range(len(numel)):
+        assert PU.to_host(ls.d_w[0][t]).tobytes() == w0[t].tobytes()
+    # momentum 0, weight decay 0: w - lr*g exactly (Alg. 1 line 9)
+    ls.ctx.local_step(ls.plans[0], lr=0.25, momentum=0.0, weight_decay=0.0, first_step=0)
+    for t in range(len(numel)):
+        want = (w0[t].astype(np.float64) - (np.float32(0.25) * g[0][t]).astype(np.float64)).astype(np.float32)
+        assert PU.to_host(ls.d_w[0][t]).tobytes() == want.tobytes()
+    ls.close()
+
+
+def test_local_step_automatic_first_step(B):
+    numel = [1000]
+    ls = PU.LockStep(B, numel, 1, delta=float("inf"), seed=6)
+    g = [[rng(22).standard_normal(1000).astype(np.float32)]]
+    ls.bind_grads(0, g)
+    ls.d_m[0][0].fill_(1e6)                      # garbage momentum must be ignored on the first step
+    ls.ctx.local_step(ls.plans[0], lr=0.1, momentum=0.9, weight_decay=0.0, first_step=-1)
+    assert PU.to_host(ls.d_m[0][0]).tobytes() == g[0][0].tobytes()
+    ls.ctx.local_step(ls.plans[0], lr=0.1, momentum=0.9, weight_decay=0.0, first_step=-1)
+    want = (np.float32(0.9) * g[0][0]) + g[0][0]
+    assert PU.to_host(ls.d_m[0][0]).tobytes() == want.tobytes()
+    ls.ctx.reset()
+    ls.ctx.local_step(ls.plans[0], lr=0.1, momentum=0.9, weight_decay=0.0, first_step=-1)
+    assert PU.to_host(ls.d_m[0][0]).tobytes() == g[0][0].tobytes()
+    ls.close()
+
+
+# ================================================================= a4: aggregation
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 16])
+@pytest.mark.parametrize("mixed", [False, True])
+def test_aggregate_matches_oracle(B, K, mixed):
+    numel = [70001, 5, 8192, 0, 33333]
+    ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, tuning=SMALL_CHUNK, seed=7)
+    r = rng(30 + K)
+    # make the replicas differ
+    for k in range(K):
+        for t, n in enumerate(numel):
+            pert = (r.standard_normal(n) * 1e-3).astype(np.float32)
+            ls.h_w[k][t] += pert
+            ls.d_w[k][t].copy_(torch.from_numpy(ls.h_w[k][t]))
+    m_before = [[PU.to_host(x) for x in ls.d_m[k]] for k in range(K)]
+    ls.bind_grads(0, [[W.round_to_bf16_bits(np.zeros(n, np.float32)) if mixed else np.zeros(n, np.float32)
+                       for n in numel] for _ in range(K)])
+    pre = [np.max(np.abs(np.stack([ls.h_w[k][t] for k in range(K)])), axis=0).astype(np.float64)
+           for t in range(len(numel))]
+    ls.ctx.aggregate_params(ls.plans[0], always=True)
+    O.average_params(ls.h_w, ls.h_glob, ls.h_c, ls.h_gc)
+    ls._pre_scale = pre
+    ls.compare(after_sync=True)
+    for t in range(len(numel)):      # fp64 sum in the same order on both sides: expect identical bits
+        assert PU.to_host(ls.d_glob[t]).tobytes() == ls.h_glob[t].tobytes()
+    for k in range(K):               # momentum untouched
+        for t in range(len(numel)):
+            assert PU.to_host(ls.d_m[k][t]).tobytes() == m_before[k][t].tobytes()
+    ls.close()
+
+
+def test_aggregate_identical_replicas_is_identity_and_misaligned(B):
+    numel = [10001, 64, 3]
+    K = 4
+    ls = PU.LockStep(B, numel, K, delta=0.0, misalign=1, seed=8)
+    ls.bind_grads(0, [[np.zeros(n, np.float32) for n in numel] for _ in range(K)])
+    ls.ctx.aggregate_params(ls.plans[0], always=True)
+    for t in range(len(numel)):
+        assert PU.to_host(ls.d_glob[t]).tobytes() == ls.h_w[0][t].tobytes()
+        for k in range(K):
+            assert PU.to_host(ls.d_w[k][t]).tobytes() == ls.h_w[0][t].tobytes()
+    ls.close()
+
+
+def test_aggregate_mode0_follows_device_decision(B):
+    numel = [50000]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=float("inf"), seed=9)
+    ls.d_w[1][0].add_(1.0)
+    before = [PU.to_host(ls.d_w[k][0]) for k in range(K)]
+    g = [[rng(40 + k).standard_normal(50000).astype(np.float32)] for k in range(K)]
+    ls.bind_grads(0, g)
+    dec = ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True)
+    assert dec.sync == 0
+    ls.ctx.aggregate_params(ls.plans[0], always=False)          # decision is "local": nothing may change
+    for k in range(K):
+        assert PU.to_host(ls.d_w[k][0]).tobytes() == before[k].tobytes()
+    assert not PU.to_host(ls.d_glob[0]).any()
+    ls.ctx.set_delta(0.0)
+    dec = ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True)
+    assert dec.sync == 1
+    ls.ctx.aggregate_params(ls.plans[0], always=False)
+    want = ((before[0].astype(np.float64) + before[1].astype(np.float64)) / 2).astype(np.float32)
+    assert PU.to_host(ls.d_glob[0]).tobytes() == want.tobytes()
+    ls.close()
+
+
+# ================================================================= a2 + whole steps
+
+def test_fused_step_is_bit_identical_to_three_calls(B):
+    numel = [100003, 257, 65536]
+    K = 4
+    r = rng(50)
+    runs = []
+    for fused in (True, False):
+        ls = PU.LockStep(B, numel, K, delta=0.05, alpha=0.5, window=5, tuning=SMALL_CHUNK, seed=11)
+        rr = rng(51)
+        for slot in range(3):
+            ls.bind_grads(slot, [[(rr.standard_normal(n) * (1 + slot)).astype(np.float32) for n in numel]
+                                 for _ in range(K)])
+        decs = []
+        for t in range(9):
+            dec, _ = ls.step(t % 3, 0.05, 0.9, 1e-4, 1.0, fused=fused)
+            decs.append(dec)
+        state = [[PU.to_host(x).tobytes() for x in ls.d_w[k]] + [PU.to_host(x).tobytes() for x in ls.d_m[k]]
+                 for k in range(K)]
+        runs.append((decs, state, [PU.to_host(x).tobytes() for x in ls.d_glob]))
+        assert ls.oracle.steps_sync > 0 and ls.oracle.steps_local > 0
+        ls.close()
+    (d1, s1, g1), (d2, s2, g2) = runs
+    assert s1 == s2 and g1 == g2
+    for a, b in zip(d1, d2):
+        assert a.flags == b.flags and a.sync == b.sync
+        assert [x.hex() for x in a.norm_sq] == [x.hex() for x in b.norm_sq]
+        assert [x.hex() for x in a.delta] == [x.hex() for x in b.delta]
+
+
+@pytest.mark.parametrize("window,alpha", [(1, 0.16), (25, 0.04), (25, 1.0), (200, 0.16), (3, 0.5)])
+def test_tracker_matches_oracle_for_windows_and_alphas(B, window, alpha):
+    numel = [3000]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=0.2, window=window, alpha=alpha, seed=12)
+    g = [[rng(60 + k).standard_normal(3000).astype(np.float32)] for k in range(K)]
+    ls.bind_grads(0, g)
+    r = rng(61)
+    nsteps = 2 * window + 10 if window <= 25 else window + 30
+    scales = np.exp(np.cumsum(r.standard_normal(nsteps) * 0.15))
+    for t in range(nsteps):
+        ls.step(0, 0.0, 0.0, 0.0, float(np.float32(scales[t])), compare_tensors=False)
+    assert ls.oracle.steps_sync > 0 and ls.oracle.steps_local > 0
+    st = ls.ctx.stats()
+    assert st["max_delta"] == pytest.approx(ls.oracle.max_delta, rel=1e-9)
+    ls.close()
+
+
+def test_delta_zero_is_bsp_and_huge_delta_is_local_only_on_gpu(B):
+    numel = [20000, 31]
+    K = 3
+    for delta, lssr in ((0.0, 0.0), (float("inf"), 1.0)):
+        ls = PU.LockStep(B, numel, K, delta=delta, seed=13)
+        for slot in range(2):
+            ls.bind_grads(slot, [[rng(70 + 10 * slot + k).standard_normal(n).astype(np.float32) for n in numel]
+                                 for k in range(K)])
+        for t in range(8):
+            dec, _ = ls.step(t % 2, 0.1, 0.9, 1e-4)
+            assert dec.sync == (1 if delta == 0.0 else 0)
+        assert ls.ctx.stats()["lssr"] == lssr
+        ls.close()
+
+
+def test_reset_clears_tracker_and_counters(B):
+    numel = [4096]
+    ls = PU.LockStep(B, numel, 2, delta=0.0, seed=14)
+    ls.bind_grads(0, [[rng(80 + k).standard_normal(4096).astype(np.float32)] for k in range(2)])
+    for _ in range(3):
+        ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True)
+    assert ls.ctx.stats()["steps_sync"] == 3
+    ls.ctx.reset()
+    st = ls.ctx.stats()
+    assert st["steps_sync"] == 0 and st["steps_local"] == 0 and math.isnan(st["lssr"])
+    dec = ls.ctx.track_grad_change(ls.plans[0], 3.0, blocking=True)
+    assert dec.delta == [0.0, 0.0]               # no previous smoothed value again
+    ls.close()
+
+
+# ================================================================= the five workloads, lock step
+
+@pytest.mark.parametrize("name,shrink,steps,compare_every", [
+    ("c1", 1, None, 1),
+    ("c2", 8, 60, 10),
+    ("c3", 8, 30, 10),
+    ("c4", 8, 60, 10),
+    ("c5", 8, 40, 10),
+])
+def test_workload_lockstep(B, name, shrink, steps, compare_every):
+    wl = W.get(name, shrink=shrink)
+    ls = PU.run_workload(B, wl, steps=steps, compare_every=compare_every)
+    print("%s: steps=%d sync=%d lssr=%.3f min|Delta-delta|=%.3g worst norm rel=%.2g worst ulp=%d forced=%d" % (
+        wl.name, ls.steps_done, ls.oracle.steps_sync, ls.oracle.lssr, ls.min_margin, ls.worst_norm_rel,
+        ls.worst_ulp, ls.forced))
+    assert ls.min_margin > 1e-3, "seed puts a decision too close to the threshold for a meaningful run"
+    assert ls.forced == 0
+    if name in ("c1", "c2", "c4"):
+        assert ls.oracle.steps_sync > 0          # the schedule contains real synchronisations
+    ls.close()
+
+
+def test_mixed_precision_workload_with_sync_steps(B):
+    # the stated C5 schedule is constant (never syncs); add spikes so the bf16 aggregation path runs in a workload
+    wl = W.get("c5", shrink=8)
+    wl.sigma = lambda t: 4.0 if t in (5, 12) else 1.0
+    ls = PU.run_workload(B, wl, steps=16, compare_every=1)
+    assert ls.oracle.steps_sync >= 2
+    ls.close()
+
+
+# ================================================================= error paths through the C ABI
+
+def _lists(B, tensors_per_worker):
+    arr, keep = B._marshal_lists(tensors_per_worker)
+    return arr, keep
+
+
+def test_plan_validation_errors(B):
+    K = 2
+    ctx = B.SelSync(K, 0.3)
+    mk = lambda n, dt=torch.float32: torch.zeros(n, dtype=dt, device="cuda")
+    good = lambda: [[mk(100), mk(7)] for _ in range(K)]
+    g, p, m, glob = good(), good(), good(), [mk(100), mk(7)]
+    ctx.plan(g, p, m, glob).destroy()
+
+    def status(fn):
+        with pytest.raises(B.SelSyncError) as e:
+            fn()
+        return e.value.status
+
+    # shape mismatch: numel and tensor count
+    bad = good(); bad[1][1] = mk(8)
+    assert status(lambda: ctx.plan(bad, p, m, glob)) == B.SELSYNC_ERR_SHAPE_MISMATCH
+    bad = good(); bad[1] = bad[1][:1]
+    assert status(lambda: ctx.plan(g, p, bad, glob)) == B.SELSYNC_ERR_SHAPE_MISMATCH
+    # dtype: bf16 grads without master, fp32 momenta required
+    bad = [[mk(100, torch.bfloat16), mk(7, torch.bfloat16)] for _ in range(K)]
+    assert status(lambda: ctx.plan(bad, p, m, glob)) == B.SELSYNC_ERR_DTYPE
+    assert status(lambda: ctx.plan(g, p, bad, glob)) == B.SELSYNC_ERR_DTYPE
+    # mixed mode needs both master and global_lowp
+    assert status(lambda: ctx.plan(bad, bad, m, glob, master=p)) == B.SELSYNC_ERR_INVALID_ARG
+    # overlapping written buffers
+    assert status(lambda: ctx.plan(g, [p[0], p[0]], m, glob)) == B.SELSYNC_ERR_INVALID_ARG
+    assert status(lambda: ctx.plan(g, p, p, glob)) == B.SELSYNC_ERR_INVALID_ARG
+    assert status(lambda: ctx.plan(p, p, m, glob)) == B.SELSYNC_ERR_INVALID_ARG
+    # the same read-only gradient for every worker is allowed
+    ctx.plan([g[0], g[0]], p, m, glob).destroy()
+    # host memory is rejected
+    host = torch.zeros(100)
+    descs = (B.selsync_tensor * 2)()
+    descs[0].data, descs[0].numel, descs[0].dtype = host.data_ptr(), 100, B.SELSYNC_F32
+    descs[1].data, descs[1].numel, descs[1].dtype = g[0][1].data_ptr(), 7, B.SELSYNC_F32
+    ga, keep1 = B._marshal_lists(g)
+    pa, keep2 = B._marshal_lists(p)
+    ma, keep3 = B._marshal_lists(m)
+    gl, keep4 = B._marshal_lists([glob])
+    ga[0].tensors = descs
+    h = ctypes.c_void_p()
+    rc = B.selsync_plan_create(ctx._h, ga, pa, ma, None, gl, None, ctypes.byref(h))
+    assert rc == B.SELSYNC_ERR_NOT_DEVICE_MEM and h.value is None
+    assert b"not" in B.selsync_last_error(ctx._h)
+    # NULL data with numel > 0
+    descs[0].data = None
+    rc = B.selsync_plan_create(ctx._h, ga, pa, ma, None, gl, None, ctypes.byref(h))
+    assert rc == B.SELSYNC_ERR_INVALID_ARG
+    # aggregate-only plan: tracking / update are state errors
+    plan = ctx.plan(None, p, None, glob)
+    assert status(lambda: ctx.track_grad_change(plan)) == B.SELSYNC_ERR_STATE
+    assert status(lambda: ctx.local_step(plan, 0.1)) == B.SELSYNC_ERR_STATE
+    ctx.aggregate_params(plan, always=True)
+    assert B.selsync_aggregate_params(ctx._h, plan._h, 5, None) == B.SELSYNC_ERR_INVALID_ARG
+    # destroying a context with live plans is refused
+    assert B.selsync_destroy(ctx._h) == B.SELSYNC_ERR_STATE
+    ctx.close()
+
+
+def test_empty_model_and_single_worker(B):
+    ctx = B.SelSync(1, 0.3)
+    plan = ctx.plan([[]], [[]], [[]], [])
+    dec = ctx.step(plan, 0.1, 0.9, 0.0, blocking=True)
+    assert dec.norm_sq == [0.0] and dec.sync == 0
+    assert plan.info() == {"num_tensors": 0, "num_params": 0, "update_chunks": 0, "aggregate_chunks": 0}
+    ctx.close()
+    # K = 1: aggregation copies the single replica into the global model
+    ls = PU.LockStep(B, [5000, 3], 1, delta=0.0, seed=15)
+    ls.bind_grads(0, [[rng(90).standard_normal(n).astype(np.float32) for n in [5000, 3]]])
+    ls.step(0, 0.1, 0.9, 1e-4)
+    for t in range(2):
+        assert PU.to_host(ls.d_glob[t]).tobytes() == PU.to_host(ls.d_w[0][t]).tobytes()
+    ls.close()
+
+
+def test_profile_counters_report_launches(B):
+    ls = PU.LockStep(B, [300000], 2, delta=0.0, seed=16)
+    ls.bind_grads(0, [[rng(95 + k).standard_normal(300000).astype(np.float32)] for k in range(2)])
+    ls.ctx.profile_enable(True, 16)
+    for _ in range(4):
+        ls.ctx.step(ls.plans[0], 0.1, 0.9, 0.0)
+    for kind in range(3):
+        count, ms = ls.ctx.profile_summary(kind)
+        assert count == 4 and ms > 0.0
+    ls.ctx.profile_enable(False)
+    ls.close()
