@@ -68,7 +68,7 @@ class selsync_stats(ctypes.Structure):
 
 class selsync_tuning(ctypes.Structure):
     _fields_ = [("chunk_elems", ctypes.c_int32), ("blocks_per_cu", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("agg_chunk_elems", ctypes.c_int32)]
 
 
 _vp = ctypes.c_void_p
@@ -222,8 +222,9 @@ class SelSync:
         return Decision(list(n), list(d), list(f), s.value, rc == SELSYNC_WARN_NONFINITE)
 
     # -- lifecycle
-    def set_tuning(self, chunk_elems: int = 0, blocks_per_cu: int = 0, nontemporal: int = -1):
-        t = selsync_tuning(chunk_elems, blocks_per_cu, nontemporal, 0)
+    def set_tuning(self, chunk_elems: int = 0, blocks_per_cu: int = 0, nontemporal: int = -1,
+                   agg_chunk_elems: int = 0):
+        t = selsync_tuning(chunk_elems, blocks_per_cu, nontemporal, agg_chunk_elems)
         self._check(selsync_set_tuning(self._h, ctypes.byref(t)))
 
     def reset(self, stream=None):

@@ -19,8 +19,7 @@ using namespace selsync;
 
 namespace {
 
-constexpr int kDefaultChunkElems = 65536;
-constexpr int kDefaultBlocksPerCu = 8;
+constexpr int kDefaultChunkElems = kTileElems;   // one workgroup pass per chunk: a one-shot grid
 constexpr int kMaxWorkers = 1024;
 constexpr int kMaxWindow = 65536;
 
@@ -208,6 +207,10 @@ void split_tensor(int64_t numel, int chunk, Emit emit)
     for (int64_t off = 0; off < numel; off += chunk)
         emit(off, std::min<int64_t>(chunk, numel - off));
 }
+
+// Elements per aggregation chunk: each thread keeps K*U 128-bit loads in flight, so the
+// smallest tile (one 128-bit vector per thread and replica) measured best for K = 4 and 8.
+int default_agg_chunk(int) { return kAggTileElems; }
 
 int effective_chunk(const selsync_ctx *ctx)
 {
@@ -436,6 +439,9 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
         return SELSYNC_ERR_INVALID_ARG;
     if (t->chunk_elems > 0 && (t->chunk_elems % kTileElems != 0 || t->chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kTileElems);
+    if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kAggTileElems != 0 || t->agg_chunk_elems > (1 << 24)))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_chunk_elems must be a multiple of %d and <= 2^24",
+                    kAggTileElems);
     if (t->blocks_per_cu > 64)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "blocks_per_cu must be <= 64");
     ctx->tuning = *t;
@@ -503,7 +509,9 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
         return rc;
 
     const int chunk = effective_chunk(ctx);
-    const int bpc = ctx->tuning.blocks_per_cu > 0 ? ctx->tuning.blocks_per_cu : kDefaultBlocksPerCu;
+    const int agg_chunk = ctx->tuning.agg_chunk_elems > 0 ? ctx->tuning.agg_chunk_elems : default_agg_chunk(K);
+    // blocks_per_cu <= 0: one workgroup per chunk (one-shot grid); > 0: a persistent grid of that many per CU
+    const int grid_cap = ctx->tuning.blocks_per_cu > 0 ? ctx->num_cus * ctx->tuning.blocks_per_cu : INT_MAX;
     const int nt = ctx->tuning.nontemporal >= 0 ? ctx->tuning.nontemporal : 1;
 
     // ---- host tables
@@ -562,7 +570,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
             agg_gc[t] = static_cast<uint16_t *>(global_lowp[0].tensors[t].data);
             al = al && aligned16(agg_gc[t]);
         }
-        split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
+        split_tensor(numel[t], agg_chunk, [&](int64_t off, int64_t n) {
             AggChunkRec c;
             c.t = (uint32_t)t;
             c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u);
@@ -635,7 +643,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->agg.global = reinterpret_cast<float *const *>(b + o_ag);
     plan->agg.glowp = reinterpret_cast<uint16_t *const *>(b + o_agc);
 
-    plan->upd_cfg.grid = std::max(1, ctx->num_cus * bpc);
+    plan->upd_cfg.grid = std::max(1, grid_cap);
     plan->upd_cfg.nontemporal = nt;
     plan->agg_cfg = plan->upd_cfg;
 

@@ -90,8 +90,11 @@ enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };
 
 // ---- launchers (selsync_kernels.hip) --------------------------------------------
 
-// Elements one workgroup iteration covers; chunk sizes are multiples of this.
-constexpr int kTileElems = 8192;
+// Elements one workgroup pass of the streaming kernel covers (256 threads x 16 elements,
+// fp32: 4 x 128-bit per stream per thread; mixed: 2 x 8 bf16).  Chunk sizes are multiples.
+constexpr int kTileElems = 4096;
+// Smallest aggregation tile: 256 threads x one 128-bit vector.
+constexpr int kAggTileElems = 1024;
 
 hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
                          double *partials, const SgdArgs &sgd, const LaunchCfg &cfg, hipStream_t s);

@@ -27,8 +27,20 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Tensor pointers come out of tables in memory, so the compiler only knows them as
+// generic (flat) addresses.  They are device-memory addresses by construction (checked
+// at plan time); casting them to the global address space yields global_load/global_store
+// instead of the slower flat forms.
+#define SELSYNC_GLOBAL __attribute__((address_space(1)))
+
+template <typename T>
+__device__ __forceinline__ SELSYNC_GLOBAL T *as_global(const void *p)
+{
+    return (SELSYNC_GLOBAL T *)(p);
+}
+
 template <bool NT, typename T>
-__device__ __forceinline__ T ld(const T *p)
+__device__ __forceinline__ T ld(const SELSYNC_GLOBAL T *p)
 {
     if (NT)
         return __builtin_nontemporal_load(p);
@@ -36,7 +48,7 @@ __device__ __forceinline__ T ld(const T *p)
 }
 
 template <bool NT, typename T>
-__device__ __forceinline__ void st(T *p, T v)
+__device__ __forceinline__ void st(SELSYNC_GLOBAL T *p, T v)
 {
     if (NT)
         __builtin_nontemporal_store(v, p);
@@ -107,8 +119,10 @@ __device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, const 
 
 // One tile of BLOCK*U vectors of an aligned fp32 chunk.
 template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
-__device__ __forceinline__ void tile_f32(const f32x4 *__restrict__ g4, f32x4 *__restrict__ w4, f32x4 *__restrict__ m4,
-                                         uint32_t base, uint32_t nvec, const SgdArgs &a, double &acc)
+__device__ __forceinline__ void tile_f32(const SELSYNC_GLOBAL f32x4 *__restrict__ g4,
+                                         SELSYNC_GLOBAL f32x4 *__restrict__ w4,
+                                         SELSYNC_GLOBAL f32x4 *__restrict__ m4, uint32_t base, uint32_t nvec,
+                                         const SgdArgs &a, double &acc)
 {
     f32x4 gv[U], wv[U], mv[U];
     const uint32_t tid = threadIdx.x;
@@ -143,9 +157,11 @@ __device__ __forceinline__ void tile_f32(const f32x4 *__restrict__ g4, f32x4 *__
 // One tile of BLOCK*U groups of 8 elements of an aligned mixed-precision chunk:
 // 8 bf16 gradients (16 B), 2x4 fp32 masters, 2x4 fp32 momenta, 8 bf16 copies out.
 template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
-__device__ __forceinline__ void tile_mixed(const u32x4 *__restrict__ g8, f32x4 *__restrict__ w4, f32x4 *__restrict__ m4,
-                                           u32x4 *__restrict__ c8, uint32_t base, uint32_t nvec, const SgdArgs &a,
-                                           double &acc)
+__device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x4 *__restrict__ g8,
+                                           SELSYNC_GLOBAL f32x4 *__restrict__ w4,
+                                           SELSYNC_GLOBAL f32x4 *__restrict__ m4,
+                                           SELSYNC_GLOBAL u32x4 *__restrict__ c8, uint32_t base, uint32_t nvec,
+                                           const SgdArgs &a, double &acc)
 {
     u32x4 gv[U];
     f32x4 wv[U][2], mv[U][2];
@@ -199,25 +215,30 @@ template <int BLOCK, bool MIXED, bool UPD, bool NORM>
 __device__ __forceinline__ void scalar_range(const TensorRec &r, uint64_t off, uint32_t begin, uint32_t n,
                                              const SgdArgs &a, double &acc)
 {
+    const SELSYNC_GLOBAL float *gf = as_global<const float>(r.g);
+    const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(r.g);
+    SELSYNC_GLOBAL float *wp = as_global<float>(r.w);
+    SELSYNC_GLOBAL float *mp = as_global<float>(r.m);
+    SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(r.lowp);
     for (uint32_t i = begin + threadIdx.x; i < n; i += BLOCK) {
         const uint64_t e = off + i;
         float g;
         if (MIXED)
-            g = __uint_as_float(((uint32_t) reinterpret_cast<const uint16_t *>(r.g)[e]) << 16);
+            g = __uint_as_float(((uint32_t)gh[e]) << 16);
         else
-            g = reinterpret_cast<const float *>(r.g)[e];
+            g = gf[e];
         float w = 0.f, m = 0.f;
         if (UPD) {
-            w = r.w[e];
+            w = wp[e];
             if (!a.first)
-                m = r.m[e];
+                m = mp[e];
         }
         elem<UPD, NORM>(g, w, m, a, acc);
         if (UPD) {
-            r.w[e] = w;
-            r.m[e] = m;
+            wp[e] = w;
+            mp[e] = m;
             if (MIXED)
-                r.lowp[e] = (uint16_t)bf16_bits(w);
+                cp[e] = (uint16_t)bf16_bits(w);
         }
     }
 }
@@ -240,18 +261,20 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
 
         if (ch.n_flags & kChunkAligned) {
             const uint32_t nvec = n / VEC;
-            f32x4 *w4 = reinterpret_cast<f32x4 *>(r.w + ch.off);
-            f32x4 *m4 = reinterpret_cast<f32x4 *>(r.m + ch.off);
+            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + ch.off);
+            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + ch.off);
             if (MIXED) {
-                const u32x4 *g8 = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
-                u32x4 *c8 = reinterpret_cast<u32x4 *>(r.lowp + ch.off);
+                const SELSYNC_GLOBAL u32x4 *g8 =
+                    as_global<const u32x4>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
+                SELSYNC_GLOBAL u32x4 *c8 = as_global<u32x4>(r.lowp + ch.off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
                     tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g8, w4, m4, c8, base, nvec, a, acc);
                 if (base < nvec)
                     tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g8, w4, m4, c8, base, nvec, a, acc);
             } else {
-                const f32x4 *g4 = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(r.g) + ch.off);
+                const SELSYNC_GLOBAL f32x4 *g4 =
+                    as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + ch.off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
                     tile_f32<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, base, nvec, a, acc);
@@ -285,88 +308,118 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
 // ---------------------------------------------------------------- k_track
 
 constexpr int kTrackBlock = 1024;
+constexpr int kTrackWaves = kTrackBlock / 64;
 
-// Wave v owns workers v, v+16, ...: it sums that worker's per-chunk partials in a
-// fixed order (lane-strided, then butterfly), evaluates the windowed EWMA with one
-// window sample per lane, and lane 0 applies Eq. 2 and the delta rule.
+// One workgroup handles all K workers, kTrackWaves of them per round.
+//   phase 1 (a1, final pass): the whole block sums one worker's per-chunk partials in a
+//     fixed order (thread-strided, wave butterfly, then the wave results in wave order);
+//   phase 2 (a2): wave v owns worker (round*16 + v): one window sample per lane for the
+//     weighted sums, lane 0 applies Eq. 2 and the delta rule.
+// Afterwards thread 0 ORs the flags (the all-gather of Alg. 1 collapses to this on one
+// GPU) and advances the local/sync counters of Eq. 4.
 __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const double *__restrict__ partials,
                                                        const int32_t *__restrict__ chunk_begin)
 {
-    __shared__ int32_t s_flag[kTrackBlock / 64];
-    __shared__ int32_t s_nonfinite[kTrackBlock / 64];
+    __shared__ double s_part[kTrackWaves][kTrackWaves];   // [worker in round][wave]
+    __shared__ int32_t s_flag[kTrackWaves];
+    __shared__ int32_t s_nonfinite[kTrackWaves];
+    __shared__ double s_max[kTrackWaves];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int nwaves = kTrackBlock / 64;
     const int W = td.window;
     const double thr = *td.delta_thr;
     int32_t my_flag = 0, my_nonfinite = 0;
     double my_max = 0.0;
 
-    for (int k = wave; k < td.K; k += nwaves) {
-        // a1, final pass
-        double acc = 0.0;
-        if (partials != nullptr) {
-            const int b = chunk_begin[k], e = chunk_begin[k + 1];
-            for (int i = b + lane; i < e; i += 64)
-                acc += partials[i];
+    for (int k0 = 0; k0 < td.K; k0 += kTrackWaves) {
+        const int kn = (td.K - k0) < kTrackWaves ? (td.K - k0) : kTrackWaves;
+        for (int r = 0; r < kn; ++r) {
+            double acc = 0.0;
+            if (partials != nullptr) {
+                // 8 independent loads in flight per thread; fixed association order
+                const int b = chunk_begin[k0 + r], e = chunk_begin[k0 + r + 1];
+                double a8[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+                for (int i = b + (int)threadIdx.x; i < e; i += 8 * kTrackBlock) {
+                    double v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int idx = i + j * kTrackBlock;
+                        v[j] = idx < e ? partials[idx] : 0.0;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        a8[j] += v[j];
+                }
+                acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+            }
+            acc = wave_sum(acc);
+            if (lane == 0)
+                s_part[r][wave] = acc;
         }
-        double x = wave_sum(acc);
-        x = __shfl(x, 0, 64);
+        __syncthreads();
 
-        // a2: window holds the previous `len` samples; the new one is age 0
-        double *h = td.hist + (size_t)k * W;
-        const int len = td.len[k];
-        const int head = td.head[k];
-        const int len_new = len < W ? len + 1 : W;
-        double num = 0.0, den = 0.0;
-        for (int j = lane; j < len_new; j += 64) {
-            const double wgt = td.weights[j];
-            int pos = head - j;
-            if (pos < 0)
-                pos += W;
-            const double v = (j == 0) ? x : h[pos];
-            num += wgt * v;
-            den += wgt;
-        }
-        num = wave_sum(num);
-        den = wave_sum(den);
-        if (lane == 0) {
-            const double s = num / den;
-            double d;
-            if (!td.has_prev[k]) {
-                d = 0.0;
-            } else {
-                const double sp = td.s_prev[k];
-                if (sp == 0.0 && s == 0.0) {
+        if (wave < kn) {
+            const int k = k0 + wave;
+            double x = 0.0;
+#pragma unroll
+            for (int w = 0; w < kTrackWaves; ++w)
+                x += s_part[wave][w];
+
+            // the window holds the previous `len` samples; the new one has age 0
+            double *h = td.hist + (size_t)k * W;
+            const int len = td.len[k];
+            const int head = td.head[k];
+            const int len_new = len < W ? len + 1 : W;
+            double num = 0.0, den = 0.0;
+            for (int j = lane; j < len_new; j += 64) {
+                const double wgt = td.weights[j];
+                int pos = head - j;
+                if (pos < 0)
+                    pos += W;
+                const double v = (j == 0) ? x : h[pos];
+                num += wgt * v;
+                den += wgt;
+            }
+            num = wave_sum(num);
+            den = wave_sum(den);
+            if (lane == 0) {
+                const double s = num / den;
+                double d;
+                if (!td.has_prev[k]) {
                     d = 0.0;
                 } else {
-                    d = fabs(s - sp) / sp;
-                    if (d != d)
-                        d = __builtin_inf();
+                    const double sp = td.s_prev[k];
+                    if (sp == 0.0 && s == 0.0) {
+                        d = 0.0;
+                    } else {
+                        d = fabs(s - sp) / sp;
+                        if (d != d)
+                            d = __builtin_inf();
+                    }
                 }
+                const bool finite_x = (x - x) == 0.0;
+                if (!finite_x) {
+                    d = __builtin_inf();
+                    my_nonfinite = 1;
+                }
+                const int32_t f = (d >= thr) ? 1 : 0;
+                my_flag |= f;
+                if (d < __builtin_inf() && d > my_max)
+                    my_max = d;
+                h[head] = x;
+                td.head[k] = (head + 1 == W) ? 0 : head + 1;
+                td.len[k] = len_new;
+                td.s_prev[k] = s;
+                td.has_prev[k] = 1;
+                td.out_norm_sq[k] = x;
+                td.out_delta[k] = d;
+                td.out_smoothed[k] = s;
+                td.out_flags[k] = f;
             }
-            const bool finite_x = (x - x) == 0.0;
-            if (!finite_x) {
-                d = __builtin_inf();
-                my_nonfinite = 1;
-            }
-            const int32_t f = (d >= thr) ? 1 : 0;
-            my_flag |= f;
-            if (d < __builtin_inf() && d > my_max)
-                my_max = d;
-            h[head] = x;
-            td.head[k] = (head + 1 == W) ? 0 : head + 1;
-            td.len[k] = len_new;
-            td.s_prev[k] = s;
-            td.has_prev[k] = 1;
-            td.out_norm_sq[k] = x;
-            td.out_delta[k] = d;
-            td.out_smoothed[k] = s;
-            td.out_flags[k] = f;
         }
+        __syncthreads();   // s_part is reused by the next round
     }
 
-    __shared__ double s_max[kTrackBlock / 64];
     if (lane == 0) {
         s_flag[wave] = my_flag;
         s_nonfinite[wave] = my_nonfinite;
@@ -376,7 +429,7 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
     if (threadIdx.x == 0) {
         int32_t any = 0, nf = 0;
         double mx = td.out->max_delta;
-        for (int w = 0; w < nwaves; ++w) {
+        for (int w = 0; w < kTrackWaves; ++w) {
             any |= s_flag[w];
             nf |= s_nonfinite[w];
             if (s_max[w] > mx)
@@ -444,19 +497,19 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
         const uint32_t n = ch.n_flags & kChunkCountMask;
         float *const *wtab = tabs.w + (size_t)ch.t * K;
         uint16_t *const *ctab = MIXED ? tabs.lowp + (size_t)ch.t * K : nullptr;
-        float *gp = tabs.global[ch.t] + ch.off;
-        uint16_t *gcp = MIXED ? tabs.glowp[ch.t] + ch.off : nullptr;
+        SELSYNC_GLOBAL float *gp = as_global<float>(tabs.global[ch.t] + ch.off);
+        SELSYNC_GLOBAL uint16_t *gcp = MIXED ? as_global<uint16_t>(tabs.glowp[ch.t] + ch.off) : nullptr;
         uint32_t done = 0;
 
         if constexpr (KC > 0) {
             // K known at compile time: replica pointers live in registers, all K*U loads
             // of a tile are issued before the first use.
-            float *wp[KC];
-            uint16_t *cp[KC];
+            SELSYNC_GLOBAL float *wp[KC];
+            SELSYNC_GLOBAL uint16_t *cp[KC];
 #pragma unroll
             for (int k = 0; k < KC; ++k) {
-                wp[k] = wtab[k] + ch.off;
-                cp[k] = MIXED ? ctab[k] + ch.off : nullptr;
+                wp[k] = as_global<float>(wtab[k] + ch.off);
+                cp[k] = MIXED ? as_global<uint16_t>(ctab[k] + ch.off) : nullptr;
             }
             if (ch.n_flags & kChunkAligned) {
                 const uint32_t nvec = n / 4;
@@ -469,7 +522,7 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                             const uint32_t i = base + u * BLOCK + tid;
                             v[u][k] = 0.f;
                             if (i < nvec)
-                                v[u][k] = ld<NT>(reinterpret_cast<const f32x4 *>(wp[k]) + i);
+                                v[u][k] = ld<NT>((const SELSYNC_GLOBAL f32x4 *)(wp[k]) + i);
                         }
                     }
 #pragma unroll
@@ -489,18 +542,18 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                             r.y = finish_mean(s1, KC, invK, pow2);
                             r.z = finish_mean(s2, KC, invK, pow2);
                             r.w = finish_mean(s3, KC, invK, pow2);
-                            st<NT>(reinterpret_cast<f32x4 *>(gp) + i, r);
+                            st<NT>((SELSYNC_GLOBAL f32x4 *)(gp) + i, r);
                             u32x2 h;
                             if (MIXED) {
                                 h.x = bf16_pack(r.x, r.y);
                                 h.y = bf16_pack(r.z, r.w);
-                                st<NT>(reinterpret_cast<u32x2 *>(gcp) + i, h);
+                                st<NT>((SELSYNC_GLOBAL u32x2 *)(gcp) + i, h);
                             }
 #pragma unroll
                             for (int k = 0; k < KC; ++k) {
-                                st<NT>(reinterpret_cast<f32x4 *>(wp[k]) + i, r);
+                                st<NT>((SELSYNC_GLOBAL f32x4 *)(wp[k]) + i, r);
                                 if (MIXED)
-                                    st<NT>(reinterpret_cast<u32x2 *>(cp[k]) + i, h);
+                                    st<NT>((SELSYNC_GLOBAL u32x2 *)(cp[k]) + i, h);
                             }
                         }
                     }
@@ -531,7 +584,7 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                 for (uint32_t i = tid; i < nvec; i += BLOCK) {
                     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
                     for (int k = 0; k < K; ++k) {
-                        const f32x4 v = ld<NT>(reinterpret_cast<const f32x4 *>(wtab[k] + ch.off) + i);
+                        const f32x4 v = ld<NT>(as_global<const f32x4>(wtab[k] + ch.off) + i);
                         s0 += (double)v.x;
                         s1 += (double)v.y;
                         s2 += (double)v.z;
@@ -542,17 +595,17 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                     r.y = finish_mean(s1, K, invK, pow2);
                     r.z = finish_mean(s2, K, invK, pow2);
                     r.w = finish_mean(s3, K, invK, pow2);
-                    st<NT>(reinterpret_cast<f32x4 *>(gp) + i, r);
+                    st<NT>((SELSYNC_GLOBAL f32x4 *)(gp) + i, r);
                     u32x2 h;
                     if (MIXED) {
                         h.x = bf16_pack(r.x, r.y);
                         h.y = bf16_pack(r.z, r.w);
-                        st<NT>(reinterpret_cast<u32x2 *>(gcp) + i, h);
+                        st<NT>((SELSYNC_GLOBAL u32x2 *)(gcp) + i, h);
                     }
                     for (int k = 0; k < K; ++k) {
-                        st<NT>(reinterpret_cast<f32x4 *>(wtab[k] + ch.off) + i, r);
+                        st<NT>(as_global<f32x4>(wtab[k] + ch.off) + i, r);
                         if (MIXED)
-                            st<NT>(reinterpret_cast<u32x2 *>(ctab[k] + ch.off) + i, h);
+                            st<NT>(as_global<u32x2>(ctab[k] + ch.off) + i, h);
                     }
                 }
                 done = nvec * 4;
@@ -560,16 +613,16 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
             for (uint32_t i = done + tid; i < n; i += BLOCK) {
                 double s = 0.0;
                 for (int k = 0; k < K; ++k)
-                    s += (double)wtab[k][ch.off + i];
+                    s += (double)as_global<const float>(wtab[k])[ch.off + i];
                 const float r = finish_mean(s, K, invK, pow2);
                 gp[i] = r;
                 const uint16_t h = MIXED ? (uint16_t)bf16_bits(r) : (uint16_t)0;
                 if (MIXED)
                     gcp[i] = h;
                 for (int k = 0; k < K; ++k) {
-                    wtab[k][ch.off + i] = r;
+                    as_global<float>(wtab[k])[ch.off + i] = r;
                     if (MIXED)
-                        ctab[k][ch.off + i] = h;
+                        as_global<uint16_t>(ctab[k])[ch.off + i] = h;
                 }
             }
         }
@@ -608,7 +661,7 @@ template <int KC, bool MIXED, bool NT>
 hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
                         int mode, int grid, hipStream_t s)
 {
-    constexpr int U = (KC == 0 || KC > 4) ? 1 : 2;
+    constexpr int U = (KC == 0 || KC > 4) ? 1 : 4;
     const int pow2 = (K & (K - 1)) == 0;
     hipLaunchKernelGGL((k_aggregate<kBlock, U, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs,
                        K, 1.0 / (double)K, pow2, flag, mode);

@@ -162,7 +162,7 @@ def _rng(seed: int, *stream: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, *[int(s) for s in stream]])))
 
 
-def _lognormal_decay_schedule(seed: int, steps: int, tau: float = 100.0, jitter: float = 0.1,
+def _lognormal_decay_schedule(seed: int, steps: int, tau: float = 100.0, jitter: float = 0.25,
                               base: float = 1e-2) -> List[float]:
     xi = _rng(seed, 7777).standard_normal(steps)
     return [base * math.exp(-t / tau + jitter * float(xi[t])) for t in range(steps)]

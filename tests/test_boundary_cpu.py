@@ -106,7 +106,7 @@ def chunk_preview(B, numel, chunk):
     return list(t)[:cap], list(o)[:cap], list(c)[:cap]
 
 
-@pytest.mark.parametrize("chunk", [8192, 65536, 1 << 20])
+@pytest.mark.parametrize("chunk", [4096, 8192, 65536, 1 << 20])
 def test_chunk_table_covers_every_element_exactly_once(B, chunk):
     from paper_2307_07950_amd import workloads as W
     for name in ("c1", "c2", "c3", "c4", "c5"):

@@ -259,7 +259,7 @@ def test_fused_step_is_bit_identical_to_three_calls(B):
 def test_tracker_matches_oracle_for_windows_and_alphas(B, window, alpha):
     numel = [3000]
     K = 2
-    ls = PU.LockStep(B, numel, K, delta=0.2, window=window, alpha=alpha, seed=12)
+    ls = PU.LockStep(B, numel, K, delta=0.05, window=window, alpha=alpha, seed=12)
     g = [[rng(60 + k).standard_normal(3000).astype(np.float32)] for k in range(K)]
     ls.bind_grads(0, g)
     r = rng(61)
