@@ -106,11 +106,13 @@ typedef struct selsync_stats {
 /* Launch-shape knobs (all kernels are bandwidth bound; these exist for measurement).
  * A value <= 0 keeps the built-in default. */
 typedef struct selsync_tuning {
-    int32_t chunk_elems;       /* elements per chunk of the update/norm chunk table (multiple of 4096)  */
+    int32_t chunk_elems;       /* elements per chunk of the update/norm chunk table (multiple of 256)   */
     int32_t blocks_per_cu;     /* > 0: persistent grid of this many workgroups per compute unit;
                                   <= 0 (default): one workgroup per chunk                               */
     int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
     int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 1024)        */
+    int32_t stream_variant;    /* workgroup shape of the update/norm kernel, 0 = default (see DESIGN)   */
+    int32_t reserved;          /* must be 0                                                              */
 } selsync_tuning;
 
 typedef struct selsync_ctx  selsync_ctx;    /* opaque: tracker state, counters, workspace owner */

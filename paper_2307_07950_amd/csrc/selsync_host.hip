@@ -21,6 +21,8 @@ namespace {
 
 constexpr int kDefaultChunkElems = kTileElems;   // one workgroup pass per chunk: a one-shot grid
 constexpr int kMaxWorkers = 1024;
+constexpr int kSegChunks = 2048;          // chunks per segment of the intermediate reduction
+constexpr int kDirectChunkLimit = 16384;  // up to this many chunks the tracker sums them directly
 constexpr int kMaxWindow = 65536;
 
 struct ProfRec {
@@ -33,7 +35,7 @@ struct selsync_ctx {
     selsync_config cfg;
     int device = 0;
     int num_cus = 256;
-    selsync_tuning tuning{0, 0, -1, 0};
+    selsync_tuning tuning{0, 0, -1, 0, 0, 0};
     // device state: one allocation, sub-pointers in td
     void *d_state = nullptr;
     size_t out_bytes = 0;          // bytes of the DecisionHeader block incl. the K-arrays
@@ -61,10 +63,15 @@ struct selsync_plan {
     ChunkRec *d_chunks = nullptr;
     int32_t *d_chunk_begin = nullptr;
     double *d_partials = nullptr;
+    // intermediate reduction level (used when there are many chunks)
+    int n_segs = 0;
+    int2 *d_segs = nullptr;
+    double *d_seg_sums = nullptr;
+    int32_t *d_seg_begin = nullptr;
     AggChunkRec *d_agg_chunks = nullptr;
     AggTables agg{};
-    LaunchCfg upd_cfg{1, 1};
-    LaunchCfg agg_cfg{1, 1};
+    LaunchCfg upd_cfg{1, 1, 0};
+    LaunchCfg agg_cfg{1, 1, 0};
 };
 
 namespace {
@@ -208,9 +215,11 @@ void split_tensor(int64_t numel, int chunk, Emit emit)
         emit(off, std::min<int64_t>(chunk, numel - off));
 }
 
-// Elements per aggregation chunk: each thread keeps K*U 128-bit loads in flight, so the
-// smallest tile (one 128-bit vector per thread and replica) measured best for K = 4 and 8.
-int default_agg_chunk(int) { return kAggTileElems; }
+// Elements per aggregation chunk.  Each thread keeps K*U 128-bit loads in flight; up to
+// K = 4 a 4096-element tile (U = 4) streams as fast as the smallest one and needs four
+// times fewer workgroups, which matters on local steps where the predicated launch only
+// reads the decision and exits.  From K = 8 the smallest tile (U = 1) is fastest.
+int default_agg_chunk(int K) { return K <= 4 ? 4 * kAggTileElems : kAggTileElems; }
 
 int effective_chunk(const selsync_ctx *ctx)
 {
@@ -252,6 +261,19 @@ int32_t resolve_sgd(selsync_ctx *ctx, const selsync_sgd *sgd, SgdArgs *out)
     out->wd = sgd->weight_decay;
     out->gs = sgd->grad_scale;
     out->first = sgd->first_step < 0 ? (ctx->local_steps == 0 ? 1 : 0) : sgd->first_step;
+    return SELSYNC_OK;
+}
+
+// a1 final passes + a2: (optional) segment reduction, then the single-workgroup tracker.
+int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
+{
+    ProfScope p(ctx, 1, s);
+    if (plan->n_segs > 0) {
+        HIP_TRY(ctx, launch_reduce(plan->d_partials, plan->d_segs, plan->n_segs, plan->d_seg_sums, s));
+        HIP_TRY(ctx, launch_track(ctx->td, plan->d_seg_sums, plan->d_seg_begin, s));
+    } else {
+        HIP_TRY(ctx, launch_track(ctx->td, plan->d_partials, plan->d_chunk_begin, s));
+    }
     return SELSYNC_OK;
 }
 
@@ -437,8 +459,10 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
 {
     if (!ctx || !t)
         return SELSYNC_ERR_INVALID_ARG;
-    if (t->chunk_elems > 0 && (t->chunk_elems % kTileElems != 0 || t->chunk_elems > (1 << 24)))
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kTileElems);
+    if (t->chunk_elems > 0 && (t->chunk_elems % kChunkGranule != 0 || t->chunk_elems > (1 << 24)))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
+    if (t->stream_variant < 0 || t->stream_variant > 9)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be in 0..9");
     if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kAggTileElems != 0 || t->agg_chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_chunk_elems must be a multiple of %d and <= 2^24",
                     kAggTileElems);
@@ -546,6 +570,22 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
         }
         chunk_begin[K] = (int32_t)chunks.size();
     }
+    if (chunks.size() > (size_t)INT32_MAX)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan (%zu chunks)", chunks.size());
+
+    // With many chunks the per-chunk partials first collapse into fixed segments of
+    // kSegChunks consecutive chunks (never crossing a worker boundary); the tracker kernel
+    // then sums segment results.  Small models skip this level.
+    std::vector<int2> segs;
+    std::vector<int32_t> seg_begin(K + 1, 0);
+    if (grads && chunks.size() > (size_t)kDirectChunkLimit) {
+        for (int k = 0; k < K; ++k) {
+            seg_begin[k] = (int32_t)segs.size();
+            for (int32_t b0 = chunk_begin[k]; b0 < chunk_begin[k + 1]; b0 += kSegChunks)
+                segs.push_back(make_int2(b0, std::min<int32_t>(b0 + kSegChunks, chunk_begin[k + 1])));
+        }
+        seg_begin[K] = (int32_t)segs.size();
+    }
 
     std::vector<AggChunkRec> agg_chunks;
     std::vector<float *> agg_w((size_t)T * K);
@@ -602,6 +642,9 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     const size_t o_chunks = take(chunks.size() * sizeof(ChunkRec));
     const size_t o_begin = take(chunk_begin.size() * sizeof(int32_t));
     const size_t o_part = take(chunks.size() * sizeof(double));
+    const size_t o_segs = take(segs.size() * sizeof(int2));
+    const size_t o_segsum = take(segs.size() * sizeof(double));
+    const size_t o_segbegin = take(seg_begin.size() * sizeof(int32_t));
     const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
     const size_t o_aw = take(agg_w.size() * sizeof(float *));
     const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
@@ -616,6 +659,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     put(o_recs, recs.data(), recs.size() * sizeof(TensorRec));
     put(o_chunks, chunks.data(), chunks.size() * sizeof(ChunkRec));
     put(o_begin, chunk_begin.data(), chunk_begin.size() * sizeof(int32_t));
+    put(o_segs, segs.data(), segs.size() * sizeof(int2));
+    put(o_segbegin, seg_begin.data(), seg_begin.size() * sizeof(int32_t));
     put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
     put(o_aw, agg_w.data(), agg_w.size() * sizeof(float *));
     put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
@@ -637,6 +682,10 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->d_chunks = reinterpret_cast<ChunkRec *>(b + o_chunks);
     plan->d_chunk_begin = reinterpret_cast<int32_t *>(b + o_begin);
     plan->d_partials = reinterpret_cast<double *>(b + o_part);
+    plan->n_segs = (int)segs.size();
+    plan->d_segs = reinterpret_cast<int2 *>(b + o_segs);
+    plan->d_seg_sums = reinterpret_cast<double *>(b + o_segsum);
+    plan->d_seg_begin = reinterpret_cast<int32_t *>(b + o_segbegin);
     plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
     plan->agg.w = reinterpret_cast<float *const *>(b + o_aw);
     plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
@@ -645,6 +694,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
 
     plan->upd_cfg.grid = std::max(1, grid_cap);
     plan->upd_cfg.nontemporal = nt;
+    plan->upd_cfg.variant = ctx->tuning.stream_variant;
     plan->agg_cfg = plan->upd_cfg;
 
     ctx->live_plans += 1;
@@ -688,7 +738,7 @@ extern "C" int32_t selsync_chunk_table_preview(const int64_t *numel, int32_t num
     if (!num_chunks || num_tensors < 0 || (num_tensors > 0 && !numel))
         return SELSYNC_ERR_INVALID_ARG;
     const int chunk = chunk_elems > 0 ? chunk_elems : kDefaultChunkElems;
-    if (chunk % kTileElems != 0 || chunk > (1 << 24))
+    if (chunk % kChunkGranule != 0 || chunk > (1 << 24))
         return SELSYNC_ERR_INVALID_ARG;
     int64_t total = 0;
     for (int t = 0; t < num_tensors; ++t) {
@@ -728,10 +778,8 @@ extern "C" int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *pla
         HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
                                    plan->d_partials, a, plan->upd_cfg, s));
     }
-    {
-        ProfScope p(ctx, 1, s);
-        HIP_TRY(ctx, launch_track(ctx->td, plan->d_partials, plan->d_chunk_begin, s));
-    }
+    if ((rc = enqueue_track(ctx, plan, s)))
+        return rc;
     if (blocking)
         return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
     return SELSYNC_OK;
@@ -788,10 +836,8 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
                                    plan->d_partials, a, plan->upd_cfg, s));
     }
     ctx->local_steps += 1;
-    {
-        ProfScope p(ctx, 1, s);
-        HIP_TRY(ctx, launch_track(ctx->td, plan->d_partials, plan->d_chunk_begin, s));
-    }
+    if ((rc = enqueue_track(ctx, plan, s)))
+        return rc;
     {
         ProfScope p(ctx, 2, s);
         HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,

@@ -84,20 +84,26 @@ struct SgdArgs {
 struct LaunchCfg {
     int grid;
     int nontemporal;
+    int variant = 0;   // workgroup shape of the streaming kernel
 };
 
 enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };
 
 // ---- launchers (selsync_kernels.hip) --------------------------------------------
 
-// Elements one workgroup pass of the streaming kernel covers (256 threads x 16 elements,
-// fp32: 4 x 128-bit per stream per thread; mixed: 2 x 8 bf16).  Chunk sizes are multiples.
-constexpr int kTileElems = 4096;
+// Elements one workgroup pass of the default streaming kernel shape covers: one
+// wavefront x 2 groups of 4 elements per lane (128-bit per fp32 stream, 64-bit per bf16 stream).
+constexpr int kTileElems = 512;
+// Chunk sizes must be a multiple of this (the smallest workgroup shape's tile).
+constexpr int kChunkGranule = 256;
 // Smallest aggregation tile: 256 threads x one 128-bit vector.
 constexpr int kAggTileElems = 1024;
 
 hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
                          double *partials, const SgdArgs &sgd, const LaunchCfg &cfg, hipStream_t s);
+
+// Sums partials[segs[j].x .. segs[j].y) into seg_sums[j], one workgroup per segment.
+hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s);
 
 hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s);
 

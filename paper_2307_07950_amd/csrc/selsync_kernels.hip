@@ -24,7 +24,6 @@ namespace selsync {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Tensor pointers come out of tables in memory, so the compiler only knows them as
@@ -154,33 +153,31 @@ __device__ __forceinline__ void tile_f32(const SELSYNC_GLOBAL f32x4 *__restrict_
     }
 }
 
-// One tile of BLOCK*U groups of 8 elements of an aligned mixed-precision chunk:
-// 8 bf16 gradients (16 B), 2x4 fp32 masters, 2x4 fp32 momenta, 8 bf16 copies out.
+// One tile of BLOCK*U groups of 4 elements of an aligned mixed-precision chunk: 4 bf16
+// gradients (8 B), 4 fp32 masters and 4 fp32 momenta (16 B each), 4 bf16 copies out (8 B).
+// Every stream is read and written with consecutive lanes on consecutive addresses.
 template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
-__device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x4 *__restrict__ g8,
+__device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x2 *__restrict__ g4,
                                            SELSYNC_GLOBAL f32x4 *__restrict__ w4,
                                            SELSYNC_GLOBAL f32x4 *__restrict__ m4,
-                                           SELSYNC_GLOBAL u32x4 *__restrict__ c8, uint32_t base, uint32_t nvec,
+                                           SELSYNC_GLOBAL u32x2 *__restrict__ c4, uint32_t base, uint32_t nvec,
                                            const SgdArgs &a, double &acc)
 {
-    u32x4 gv[U];
-    f32x4 wv[U][2], mv[U][2];
+    u32x2 gv[U];
+    f32x4 wv[U], mv[U];
     const uint32_t tid = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t i = base + u * BLOCK + tid;
         gv[u] = 0u;
-        wv[u][0] = wv[u][1] = 0.f;
-        mv[u][0] = mv[u][1] = 0.f;
+        wv[u] = 0.f;
+        mv[u] = 0.f;
         if (!GUARD || i < nvec) {
-            gv[u] = ld<NT>(g8 + i);
+            gv[u] = ld<NT>(g4 + i);
             if (UPD) {
-                wv[u][0] = ld<NT>(w4 + 2 * i);
-                wv[u][1] = ld<NT>(w4 + 2 * i + 1);
-                if (!a.first) {
-                    mv[u][0] = ld<NT>(m4 + 2 * i);
-                    mv[u][1] = ld<NT>(m4 + 2 * i + 1);
-                }
+                wv[u] = ld<NT>(w4 + i);
+                if (!a.first)
+                    mv[u] = ld<NT>(m4 + i);
             }
         }
     }
@@ -188,22 +185,19 @@ __device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x4 *__restric
     for (int u = 0; u < U; ++u) {
         const uint32_t i = base + u * BLOCK + tid;
         if (!GUARD || i < nvec) {
-            f32x4 ga, gb;
-            ga.x = bf16_lo(gv[u].x); ga.y = bf16_hi(gv[u].x); ga.z = bf16_lo(gv[u].y); ga.w = bf16_hi(gv[u].y);
-            gb.x = bf16_lo(gv[u].z); gb.y = bf16_hi(gv[u].z); gb.z = bf16_lo(gv[u].w); gb.w = bf16_hi(gv[u].w);
-            elem4<UPD, NORM>(ga, wv[u][0], mv[u][0], a, acc);
-            elem4<UPD, NORM>(gb, wv[u][1], mv[u][1], a, acc);
+            f32x4 g;
+            g.x = bf16_lo(gv[u].x);
+            g.y = bf16_hi(gv[u].x);
+            g.z = bf16_lo(gv[u].y);
+            g.w = bf16_hi(gv[u].y);
+            elem4<UPD, NORM>(g, wv[u], mv[u], a, acc);
             if (UPD) {
-                st<NT>(w4 + 2 * i, wv[u][0]);
-                st<NT>(w4 + 2 * i + 1, wv[u][1]);
-                st<NT>(m4 + 2 * i, mv[u][0]);
-                st<NT>(m4 + 2 * i + 1, mv[u][1]);
-                u32x4 cv;
-                cv.x = bf16_pack(wv[u][0].x, wv[u][0].y);
-                cv.y = bf16_pack(wv[u][0].z, wv[u][0].w);
-                cv.z = bf16_pack(wv[u][1].x, wv[u][1].y);
-                cv.w = bf16_pack(wv[u][1].z, wv[u][1].w);
-                st<NT>(c8 + i, cv);
+                st<NT>(w4 + i, wv[u]);
+                st<NT>(m4 + i, mv[u]);
+                u32x2 cv;
+                cv.x = bf16_pack(wv[u].x, wv[u].y);
+                cv.y = bf16_pack(wv[u].z, wv[u].w);
+                st<NT>(c4 + i, cv);
             }
         }
     }
@@ -250,7 +244,7 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
 {
     constexpr bool UPD = MODE != kNormOnly;
     constexpr bool NORM = MODE != kUpdateOnly;
-    constexpr uint32_t VEC = MIXED ? 8 : 4;
+    constexpr uint32_t VEC = 4;
     __shared__ double red[BLOCK / 64];
 
     for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
@@ -264,14 +258,14 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
             SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + ch.off);
             SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + ch.off);
             if (MIXED) {
-                const SELSYNC_GLOBAL u32x4 *g8 =
-                    as_global<const u32x4>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
-                SELSYNC_GLOBAL u32x4 *c8 = as_global<u32x4>(r.lowp + ch.off);
+                const SELSYNC_GLOBAL u32x2 *g4 =
+                    as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
+                SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + ch.off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
-                    tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g8, w4, m4, c8, base, nvec, a, acc);
+                    tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, c4, base, nvec, a, acc);
                 if (base < nvec)
-                    tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g8, w4, m4, c8, base, nvec, a, acc);
+                    tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, c4, base, nvec, a, acc);
             } else {
                 const SELSYNC_GLOBAL f32x4 *g4 =
                     as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + ch.off);
@@ -287,22 +281,62 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
         }
 
         if (NORM) {
-            // level 1: wavefront shuffle; level 2: LDS across the block's wavefronts,
-            // summed by one thread in wave order -> one fixed slot per chunk.
+            // wavefront shuffle first; a multi-wave workgroup then combines its waves
+            // through LDS in wave order.  Either way: one fixed slot per chunk.
             const double s = wave_sum(acc);
-            if ((threadIdx.x & 63) == 0)
-                red[threadIdx.x >> 6] = s;
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                double t = 0.0;
+            if constexpr (BLOCK == 64) {
+                if (threadIdx.x == 0)
+                    partials[c] = s;
+            } else {
+                if ((threadIdx.x & 63) == 0)
+                    red[threadIdx.x >> 6] = s;
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    double t = 0.0;
 #pragma unroll
-                for (int w = 0; w < BLOCK / 64; ++w)
-                    t += red[w];
-                partials[c] = t;
+                    for (int w = 0; w < BLOCK / 64; ++w)
+                        t += red[w];
+                    partials[c] = t;
+                }
+                __syncthreads();
             }
-            __syncthreads();
         }
     }
+}
+
+// ---------------------------------------------------------------- k_reduce
+
+constexpr int kReduceBlock = 256;
+
+// Intermediate level of the deterministic norm reduction: workgroup j sums the per-chunk
+// partials of segment j (a fixed range inside one worker's chunks) and writes one value.
+// Order: thread-strided accumulation (8 independent loads in flight), wavefront
+// shuffle, then the four wave results through LDS in wave order.
+__global__ __launch_bounds__(kReduceBlock) void k_reduce(const double *__restrict__ partials,
+                                                         const int2 *__restrict__ segs,
+                                                         double *__restrict__ seg_sums)
+{
+    __shared__ double red[kReduceBlock / 64];
+    const int2 sg = segs[blockIdx.x];
+    double a8[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int i = sg.x + (int)threadIdx.x; i < sg.y; i += 8 * kReduceBlock) {
+        double v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int idx = i + j * kReduceBlock;
+            v[j] = idx < sg.y ? partials[idx] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            a8[j] += v[j];
+    }
+    double acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0)
+        red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        seg_sums[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
 }
 
 // ---------------------------------------------------------------- k_track
@@ -633,27 +667,47 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
 
 constexpr int kBlock = 256;
 
-template <bool MIXED, int MODE, bool NT>
-hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
-                           const SgdArgs &sgd, int grid, hipStream_t s)
+template <int BLOCK, int U, bool MIXED, int MODE, bool NT>
+hipError_t launch_stream_bu(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
+                            const SgdArgs &sgd, int grid, hipStream_t s)
 {
-    constexpr int U = MIXED ? 2 : 4;
-    hipLaunchKernelGGL((k_stream<kBlock, U, MIXED, MODE, NT>), dim3(grid), dim3(kBlock), 0, s, recs, chunks, nchunks,
+    hipLaunchKernelGGL((k_stream<BLOCK, U, MIXED, MODE, NT>), dim3(grid), dim3(BLOCK), 0, s, recs, chunks, nchunks,
                        partials, sgd);
     return hipGetLastError();
 }
 
+template <bool MIXED, int MODE, bool NT>
+hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
+                           const SgdArgs &sgd, int grid, int variant, hipStream_t s)
+{
+    // (workgroup size, 4-element groups per thread)
+#define SELSYNC_V(B, UF) \
+    return launch_stream_bu<B, UF, MIXED, MODE, NT>(recs, chunks, nchunks, partials, sgd, grid, s)
+    switch (variant) {
+    case 1: SELSYNC_V(256, 2);
+    case 2: SELSYNC_V(256, 1);
+    case 3: SELSYNC_V(128, 4);
+    case 4: SELSYNC_V(128, 2);
+    case 5: SELSYNC_V(64, 4);
+    case 7: SELSYNC_V(64, 1);
+    case 8: SELSYNC_V(128, 1);
+    case 9: SELSYNC_V(256, 4);
+    default: SELSYNC_V(64, 2);   // 0 and 6: single-wave workgroups, 512 elements each (measured best)
+    }
+#undef SELSYNC_V
+}
+
 template <bool MIXED, bool NT>
 hipError_t launch_stream_m(StreamMode mode, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                           double *partials, const SgdArgs &sgd, int grid, hipStream_t s)
+                           double *partials, const SgdArgs &sgd, int grid, int variant, hipStream_t s)
 {
     switch (mode) {
     case kNormOnly:
-        return launch_stream_t<MIXED, kNormOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, s);
+        return launch_stream_t<MIXED, kNormOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, s);
     case kUpdateOnly:
-        return launch_stream_t<MIXED, kUpdateOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, s);
+        return launch_stream_t<MIXED, kUpdateOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, s);
     default:
-        return launch_stream_t<MIXED, kUpdateAndNorm, NT>(recs, chunks, nchunks, partials, sgd, grid, s);
+        return launch_stream_t<MIXED, kUpdateAndNorm, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, s);
     }
 }
 
@@ -697,10 +751,18 @@ hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, con
         return hipSuccess;
     const int grid = cfg.grid < nchunks ? cfg.grid : nchunks;
     if (mixed)
-        return cfg.nontemporal ? launch_stream_m<true, true>(mode, recs, chunks, nchunks, partials, sgd, grid, s)
-                               : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, s);
-    return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, s)
-                           : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, s);
+        return cfg.nontemporal ? launch_stream_m<true, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s)
+                               : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s);
+    return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s)
+                           : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s);
+}
+
+hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s)
+{
+    if (nsegs <= 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(k_reduce, dim3(nsegs), dim3(kReduceBlock), 0, s, partials, segs, seg_sums);
+    return hipGetLastError();
 }
 
 hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s)

@@ -29,7 +29,7 @@ def rng(seed):
     return np.random.default_rng(seed)
 
 
-SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2)     # many chunks per tensor even for small tensors
+SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2, stream_variant=9)   # persistent grid, multi-pass chunks
 
 # tensor-size sets: tiny / ragged tails / several tiles / empty tensors / exactly one chunk
 SIZE_SETS = {
@@ -156,6 +156,46 @@ def test_local_step_automatic_first_step(B):
     ls.ctx.local_step(ls.plans[0], lr=0.1, momentum=0.9, weight_decay=0.0, first_step=-1)
     assert PU.to_host(ls.d_m[0][0]).tobytes() == g[0][0].tobytes()
     ls.close()
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+def test_many_chunks_take_the_segment_reduction_level(B, mixed):
+    # more than 16384 chunks: per-chunk partials -> per-segment sums -> tracker
+    numel = [4_200_000 + 13, 77]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=float("inf"), mixed=mixed, seed=3)
+    r = rng(23)
+    grads = []
+    for k in range(K):
+        gk = [(r.standard_normal(n, dtype=np.float32) * np.float32(1e-2)) for n in numel]
+        grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+    ls.bind_grads(0, grads)
+    assert ls.plans[0].info()["update_chunks"] > 16384
+    for t in range(2):
+        ls.step(0, lr=0.1, mu=0.9, wd=5e-4, gs=1.0 + t, fused=(t == 0))
+    assert ls.worst_norm_rel < 1e-12 and ls.worst_ulp == 0
+    ls.close()
+
+
+@pytest.mark.parametrize("variant,chunk", [(0, 512), (0, 1024), (1, 2048), (2, 1024), (3, 2048), (4, 1024), (5, 1024),
+                                           (7, 256), (8, 512), (9, 4096), (9, 65536)])
+@pytest.mark.parametrize("persistent", [0, 2])
+def test_every_workgroup_shape_gives_the_same_results(B, variant, chunk, persistent):
+    numel = [100003, 513, 4096, 255]
+    K = 2
+    tuning = dict(chunk_elems=chunk, blocks_per_cu=persistent, stream_variant=variant)
+    for mixed in (False, True):
+        ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, tuning=tuning, seed=4)
+        r = rng(24)
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(0, grads)
+        for t in range(3):
+            ls.step(0, lr=0.1, mu=0.9, wd=5e-4, gs=1.0, fused=(t != 1))
+        assert ls.worst_ulp == 0
+        ls.close()
 
 
 # ================================================================= a4: aggregation
