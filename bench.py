@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
+# plain copy kernel of known size (profiles/pmc_hbm_traffic_vgg11like_k4.txt); not measurable from inside this
+# process, so it is quoted for the workload it was measured on and null otherwise.
+MEASURED_TRAFFIC_BYTES = {("vgg11_like", 1): 1.0795e10}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -38,6 +43,15 @@ def parse_args():
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernels with HIP events in the timed loop (roofline.achieved becomes null)")
+    ap.add_argument("--event-stride", type=int, default=4,
+                    help="bracket every n-th launch of the dominant kernel with HIP events inside the timed loop")
+    ap.add_argument("--all-kernel-events", action="store_true",
+                    help="bracket every launch of every kernel (costs ~1.4 %% of the step time)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy kernel (1 GiB read + 1 GiB written, 3 times) so "
+                         "that FETCH_SIZE / WRITE_SIZE counters can be scaled by a kernel of known traffic")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for the CPU baseline")
     return ap.parse_args()
 
@@ -162,10 +176,23 @@ def main():
         for t in range(t0, t0 + n):
             ctx.step(plans[t % wl.pool], wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)          # one vectorised elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     run(0, args.warmup)
     torch.cuda.synchronize()
     s0 = ctx.stats()
-    ctx.profile_enable(True, args.steps)
+    if not args.no_kernel_events:
+        if args.all_kernel_events:
+            ctx.profile_config(7, 1)
+        else:
+            ctx.profile_config(1, max(1, args.event_stride))     # dominant kernel only, sparse
+        ctx.profile_enable(True, args.steps)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     run(args.warmup, args.steps)
@@ -187,7 +214,7 @@ def main():
     upd_ms = kern[0][1] / max(1, kern[0][0])
     trk_ms = kern[1][1] / max(1, kern[1][0])
     agg_ms_all = kern[2][1] / max(1, kern[2][0])          # includes the early-exit launches of local steps
-    achieved = b_local / (upd_ms * 1e-3) / 1e9
+    achieved = b_local / (upd_ms * 1e-3) / 1e9 if kern[0][0] else None
     result = {
         "metric": "SelSync steps/s (one GPU, K replicas in HBM)",
         "value": args.steps / elapsed,
@@ -216,16 +243,18 @@ def main():
         "extra_bytes_per_sync_step": b_sync,
         "roofline": {
             "bound": "hbm", "kernel": "k_stream (fused update + norm partials)",
-            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None, "avg_ms": upd_ms, "launches": kern[0][0],
+            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": (achieved / HBM_PEAK_GBPS) if achieved else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, args.shrink)), "avg_ms": upd_ms, "timed_launches": kern[0][0],
         },
-        "other_kernels": {
-            "k_track_avg_ms": trk_ms,
-            "k_aggregate_avg_ms_over_all_launches": agg_ms_all,
-            "k_aggregate_est_ms_per_sync": (kern[2][1] / n_sync) if n_sync else None,
-            "k_aggregate_est_gbps_per_sync": (b_sync / (kern[2][1] / n_sync * 1e-3) / 1e9) if n_sync else None,
-        },
+        "other_kernels": None,
     }
+    if args.all_kernel_events and not args.no_kernel_events:
+        result["other_kernels"] = {
+            "k_reduce_plus_k_track_avg_ms": trk_ms,
+            "k_aggregate_avg_ms_over_all_launches": agg_ms_all,      # local steps launch it too (it exits at once)
+            "k_aggregate_est_ms_per_sync": (kern[2][1] / n_sync) if n_sync else None,
+        }
     if not args.no_cpu_baseline:
         # release the GPU-side working set first: the oracle needs host memory only
         result["cpu_baseline"] = cpu_baseline(wl, lssr_run, args.cpu_steps)

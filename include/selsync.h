@@ -112,7 +112,7 @@ typedef struct selsync_tuning {
     int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
     int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 1024)        */
     int32_t stream_variant;    /* workgroup shape of the update/norm kernel, 0 = default (see DESIGN)   */
-    int32_t reserved;          /* must be 0                                                              */
+    int32_t xcd_swizzle;       /* 1: each XCD walks a contiguous eighth of the chunk table; 0: off; <0 default */
 } selsync_tuning;
 
 typedef struct selsync_ctx  selsync_ctx;    /* opaque: tracker state, counters, workspace owner */
@@ -252,6 +252,10 @@ int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_stats *out);
  * for the recorded events, returns count and summed milliseconds, and clears them.
  */
 int32_t selsync_profile_enable(selsync_ctx *ctx, int32_t enable, int32_t max_launches);
+/* Which launches are timed: bit k of kind_mask selects kernel kind k (default 7 = all), and
+ * only every stride-th launch of a selected kind is bracketed (default 1).  Event records
+ * cost a few microseconds of stream time each, so a sparse setting keeps a timed loop honest. */
+int32_t selsync_profile_config(selsync_ctx *ctx, int32_t kind_mask, int32_t stride);
 int32_t selsync_profile_summary(selsync_ctx *ctx, int32_t kind, int64_t *count, double *total_ms);
 
 #ifdef __cplusplus

@@ -69,7 +69,7 @@ class selsync_stats(ctypes.Structure):
 class selsync_tuning(ctypes.Structure):
     _fields_ = [("chunk_elems", ctypes.c_int32), ("blocks_per_cu", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
                 ("agg_chunk_elems", ctypes.c_int32), ("stream_variant", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("xcd_swizzle", ctypes.c_int32)]
 
 
 _vp = ctypes.c_void_p
@@ -99,6 +99,7 @@ PROTOTYPES = {
     "selsync_read_decision": (_i32, [_vp, _vp, _dp, _dp, _ip, _ip]),
     "selsync_get_stats": (_i32, [_vp, _vp, ctypes.POINTER(selsync_stats)]),
     "selsync_profile_enable": (_i32, [_vp, _i32, _i32]),
+    "selsync_profile_config": (_i32, [_vp, _i32, _i32]),
     "selsync_profile_summary": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_int64), _dp]),
 }
 
@@ -224,8 +225,8 @@ class SelSync:
 
     # -- lifecycle
     def set_tuning(self, chunk_elems: int = 0, blocks_per_cu: int = 0, nontemporal: int = -1,
-                   agg_chunk_elems: int = 0, stream_variant: int = 0):
-        t = selsync_tuning(chunk_elems, blocks_per_cu, nontemporal, agg_chunk_elems, stream_variant, 0)
+                   agg_chunk_elems: int = 0, stream_variant: int = 0, xcd_swizzle: int = -1):
+        t = selsync_tuning(chunk_elems, blocks_per_cu, nontemporal, agg_chunk_elems, stream_variant, xcd_swizzle)
         self._check(selsync_set_tuning(self._h, ctypes.byref(t)))
 
     def reset(self, stream=None):
@@ -293,6 +294,9 @@ class SelSync:
 
     def profile_enable(self, enable: bool = True, max_launches: int = 4096):
         self._check(selsync_profile_enable(self._h, int(enable), max_launches))
+
+    def profile_config(self, kind_mask: int = 7, stride: int = 1):
+        self._check(selsync_profile_config(self._h, kind_mask, stride))
 
     def profile_summary(self, kind: int):
         c, ms = ctypes.c_int64(), ctypes.c_double()

@@ -20,6 +20,7 @@ using namespace selsync;
 namespace {
 
 constexpr int kDefaultChunkElems = kTileElems;   // one workgroup pass per chunk: a one-shot grid
+constexpr int kDefaultXcdSwizzle = 0;
 constexpr int kMaxWorkers = 1024;
 constexpr int kSegChunks = 2048;          // chunks per segment of the intermediate reduction
 constexpr int kDirectChunkLimit = 16384;  // up to this many chunks the tracker sums them directly
@@ -35,7 +36,7 @@ struct selsync_ctx {
     selsync_config cfg;
     int device = 0;
     int num_cus = 256;
-    selsync_tuning tuning{0, 0, -1, 0, 0, 0};
+    selsync_tuning tuning{0, 0, -1, 0, 0, -1};
     // device state: one allocation, sub-pointers in td
     void *d_state = nullptr;
     size_t out_bytes = 0;          // bytes of the DecisionHeader block incl. the K-arrays
@@ -49,6 +50,9 @@ struct selsync_ctx {
     int prof_cap = 0;
     std::vector<ProfRec> prof_pool[3];
     int prof_used[3] = {0, 0, 0};
+    int64_t prof_seen[3] = {0, 0, 0};   // launches seen per kind since enable
+    int prof_mask = 7;                  // bit k: time kernels of kind k
+    int prof_stride = 1;                // time every prof_stride-th launch of a kind
 };
 
 struct selsync_plan {
@@ -119,9 +123,12 @@ struct ProfScope {
     ProfRec *rec = nullptr;
     ProfScope(selsync_ctx *c, int k, hipStream_t st) : ctx(c), kind(k), s(st)
     {
-        if (ctx->prof_on && ctx->prof_used[kind] < ctx->prof_cap) {
-            rec = &ctx->prof_pool[kind][ctx->prof_used[kind]++];
-            (void)hipEventRecord(rec->start, s);
+        if (ctx->prof_on && ((ctx->prof_mask >> kind) & 1)) {
+            const bool pick = (ctx->prof_seen[kind]++ % ctx->prof_stride) == 0;
+            if (pick && ctx->prof_used[kind] < ctx->prof_cap) {
+                rec = &ctx->prof_pool[kind][ctx->prof_used[kind]++];
+                (void)hipEventRecord(rec->start, s);
+            }
         }
     }
     ~ProfScope()
@@ -695,6 +702,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->upd_cfg.grid = std::max(1, grid_cap);
     plan->upd_cfg.nontemporal = nt;
     plan->upd_cfg.variant = ctx->tuning.stream_variant;
+    plan->upd_cfg.xcd_swizzle = ctx->tuning.xcd_swizzle >= 0 ? ctx->tuning.xcd_swizzle : kDefaultXcdSwizzle;
     plan->agg_cfg = plan->upd_cfg;
 
     ctx->live_plans += 1;
@@ -909,9 +917,21 @@ extern "C" int32_t selsync_profile_enable(selsync_ctx *ctx, int32_t enable, int3
             ctx->prof_pool[k].push_back(r);
         }
         ctx->prof_used[k] = 0;
+        ctx->prof_seen[k] = 0;
     }
     ctx->prof_cap = max_launches;
     ctx->prof_on = true;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_profile_config(selsync_ctx *ctx, int32_t kind_mask, int32_t stride)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (kind_mask < 0 || kind_mask > 7 || stride < 1)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "kind_mask must be in 0..7 and stride >= 1");
+    ctx->prof_mask = kind_mask;
+    ctx->prof_stride = stride;
     return SELSYNC_OK;
 }
 

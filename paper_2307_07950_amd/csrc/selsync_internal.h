@@ -85,6 +85,7 @@ struct LaunchCfg {
     int grid;
     int nontemporal;
     int variant = 0;   // workgroup shape of the streaming kernel
+    int xcd_swizzle = 0;   // 1: XCD-aware workgroup -> chunk mapping
 };
 
 enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };

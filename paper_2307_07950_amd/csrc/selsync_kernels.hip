@@ -68,6 +68,16 @@ __device__ __forceinline__ uint32_t bf16_bits(float f)
 }
 __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
+// Workgroup -> chunk mapping.  Workgroups are handed to the 8 XCDs round-robin by
+// linear id, and each XCD has its own L2.  With xcd_per > 0 workgroup v takes chunk
+// (v % 8) * xcd_per + v / 8, so every XCD walks one contiguous eighth of the chunk
+// table (and of the tensors): table lines and address translations are fetched by one
+// L2 instead of eight.  xcd_per == 0 is the identity mapping.
+__device__ __forceinline__ int chunk_of_workgroup(int v, int xcd_per)
+{
+    return xcd_per > 0 ? (v & 7) * xcd_per + (v >> 3) : v;
+}
+
 // Sum over the 64 lanes of a wavefront in a fixed butterfly order; result in lane 0.
 __device__ __forceinline__ double wave_sum(double v)
 {
@@ -240,14 +250,18 @@ __device__ __forceinline__ void scalar_range(const TensorRec &r, uint64_t off, u
 template <int BLOCK, int U, bool MIXED, int MODE, bool NT>
 __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ recs,
                                                   const ChunkRec *__restrict__ chunks, int nchunks,
-                                                  double *__restrict__ partials, SgdArgs a)
+                                                  double *__restrict__ partials, SgdArgs a, int xcd_per)
 {
     constexpr bool UPD = MODE != kNormOnly;
     constexpr bool NORM = MODE != kUpdateOnly;
     constexpr uint32_t VEC = 4;
     __shared__ double red[BLOCK / 64];
 
-    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    for (int v = blockIdx.x; v < vtotal; v += gridDim.x) {
+        const int c = chunk_of_workgroup(v, xcd_per);
+        if (c >= nchunks)
+            continue;
         const ChunkRec ch = chunks[c];
         const TensorRec r = recs[ch.rec];
         const uint32_t n = ch.n_flags & kChunkCountMask;
@@ -520,13 +534,17 @@ __device__ __forceinline__ float finish_mean(double s, int K, double invK, int p
 template <int BLOCK, int U, int KC, bool MIXED, bool NT>
 __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restrict__ chunks, int nchunks,
                                                      AggTables tabs, int K, double invK, int pow2,
-                                                     const int32_t *__restrict__ sync_flag, int mode)
+                                                     const int32_t *__restrict__ sync_flag, int mode, int xcd_per)
 {
     if (mode == 0 && *sync_flag == 0)
         return;
     const uint32_t tid = threadIdx.x;
 
-    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    for (int v = blockIdx.x; v < vtotal; v += gridDim.x) {
+        const int c = chunk_of_workgroup(v, xcd_per);
+        if (c >= nchunks)
+            continue;
         const AggChunkRec ch = chunks[c];
         const uint32_t n = ch.n_flags & kChunkCountMask;
         float *const *wtab = tabs.w + (size_t)ch.t * K;
@@ -669,20 +687,20 @@ constexpr int kBlock = 256;
 
 template <int BLOCK, int U, bool MIXED, int MODE, bool NT>
 hipError_t launch_stream_bu(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
-                            const SgdArgs &sgd, int grid, hipStream_t s)
+                            const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
 {
     hipLaunchKernelGGL((k_stream<BLOCK, U, MIXED, MODE, NT>), dim3(grid), dim3(BLOCK), 0, s, recs, chunks, nchunks,
-                       partials, sgd);
+                       partials, sgd, xcd_per);
     return hipGetLastError();
 }
 
 template <bool MIXED, int MODE, bool NT>
 hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
-                           const SgdArgs &sgd, int grid, int variant, hipStream_t s)
+                           const SgdArgs &sgd, int grid, int variant, int xcd_per, hipStream_t s)
 {
     // (workgroup size, 4-element groups per thread)
 #define SELSYNC_V(B, UF) \
-    return launch_stream_bu<B, UF, MIXED, MODE, NT>(recs, chunks, nchunks, partials, sgd, grid, s)
+    return launch_stream_bu<B, UF, MIXED, MODE, NT>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s)
     switch (variant) {
     case 1: SELSYNC_V(256, 2);
     case 2: SELSYNC_V(256, 1);
@@ -699,44 +717,44 @@ hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nc
 
 template <bool MIXED, bool NT>
 hipError_t launch_stream_m(StreamMode mode, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                           double *partials, const SgdArgs &sgd, int grid, int variant, hipStream_t s)
+                           double *partials, const SgdArgs &sgd, int grid, int variant, int xcd_per, hipStream_t s)
 {
     switch (mode) {
     case kNormOnly:
-        return launch_stream_t<MIXED, kNormOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, s);
+        return launch_stream_t<MIXED, kNormOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, xcd_per, s);
     case kUpdateOnly:
-        return launch_stream_t<MIXED, kUpdateOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, s);
+        return launch_stream_t<MIXED, kUpdateOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, xcd_per, s);
     default:
-        return launch_stream_t<MIXED, kUpdateAndNorm, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, s);
+        return launch_stream_t<MIXED, kUpdateAndNorm, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, xcd_per, s);
     }
 }
 
 template <int KC, bool MIXED, bool NT>
 hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                        int mode, int grid, hipStream_t s)
+                        int mode, int grid, int xcd_per, hipStream_t s)
 {
     constexpr int U = (KC == 0 || KC > 4) ? 1 : 4;
     const int pow2 = (K & (K - 1)) == 0;
     hipLaunchKernelGGL((k_aggregate<kBlock, U, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs,
-                       K, 1.0 / (double)K, pow2, flag, mode);
+                       K, 1.0 / (double)K, pow2, flag, mode, xcd_per);
     return hipGetLastError();
 }
 
 template <bool MIXED, bool NT>
 hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                        int mode, int grid, hipStream_t s)
+                        int mode, int grid, int xcd_per, hipStream_t s)
 {
     switch (K) {
     case 1:
-        return launch_agg_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+        return launch_agg_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
     case 2:
-        return launch_agg_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+        return launch_agg_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
     case 4:
-        return launch_agg_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+        return launch_agg_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
     case 8:
-        return launch_agg_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+        return launch_agg_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
     default:
-        return launch_agg_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, s);
+        return launch_agg_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
     }
 }
 
@@ -749,12 +767,14 @@ hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, con
 {
     if (nchunks <= 0)
         return hipSuccess;
-    const int grid = cfg.grid < nchunks ? cfg.grid : nchunks;
+    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
     if (mixed)
-        return cfg.nontemporal ? launch_stream_m<true, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s)
-                               : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s);
-    return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s)
-                           : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, s);
+        return cfg.nontemporal ? launch_stream_m<true, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s)
+                               : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s);
+    return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s)
+                           : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s);
 }
 
 hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s)
@@ -776,12 +796,14 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
 {
     if (nchunks <= 0)
         return hipSuccess;
-    const int grid = cfg.grid < nchunks ? cfg.grid : nchunks;
+    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
     if (mixed)
-        return cfg.nontemporal ? launch_agg_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s)
-                               : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s);
-    return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s)
-                           : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, s);
+        return cfg.nontemporal ? launch_agg_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s)
+                               : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s);
+    return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s)
+                           : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s);
 }
 
 hipError_t launch_reset(const TrackerDev &td, hipStream_t s)
