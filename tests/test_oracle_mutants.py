@@ -1,0 +1,67 @@
+"""Mutation check of the oracle pins (CPU only): each plausible mistake is planted in a COPY of
+the oracle's C source, the copy is built, and tests/test_oracle_pins.py must fail on it.  The
+real oracle and the GPU path are never touched."""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# (name, text in oracle/selsync_oracle.c, replacement)
+MUT = [
+ ("norm float product", "acc += (double)gh * (double)gh;\n    }\n    return acc;\n}\n\ndouble selsync_oracle_norm_sq_accum_bf16", "acc += (double)(gh * gh);\n    }\n    return acc;\n}\n\ndouble selsync_oracle_norm_sq_accum_bf16"),
+ ("norm ignores scale", "float gh = grad_scale * g[j];\n        acc +=", "float gh = g[j];\n        acc +="),
+ ("sgd wd sign", "float d = gh + dec;\n        float mom;\n        if (first) {\n            mom = d;\n        } else {\n            float mm = mu * m[j];\n            mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        w[j] = w[j] - stepv;", "float d = gh - dec;\n        float mom;\n        if (first) {\n            mom = d;\n        } else {\n            float mm = mu * m[j];\n            mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        w[j] = w[j] - stepv;"),
+ ("sgd plus step", "w[j] = w[j] - stepv;", "w[j] = w[j] + stepv;"),
+ ("sgd first ignored", "if (first) {\n            mom = d;\n        } else {\n            float mm = mu * m[j];\n            mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        w[j]", "{\n            float mm = mu * m[j];\n            mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        w[j]"),
+ ("sgd momentum on d", "mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        w[j]", "mom = mu * (m[j] + d);\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        w[j]"),
+ ("tracker alpha^j", "pow(1.0 - t->alpha, (double)j)", "pow(t->alpha, (double)j)"),
+ ("tracker oldest first", "t->hist[t->len - 1 - j]", "t->hist[j]"),
+ ("tracker no fabs", "fabs(s - t->s_prev) / t->s_prev", "(s - t->s_prev) / t->s_prev"),
+ ("tracker divide by s", "fabs(s - t->s_prev) / t->s_prev", "fabs(s - t->s_prev) / s"),
+ ("tracker unnormalised", "double s = num / den;", "double s = num;"),
+ ("avg drops last", "for (int k = 0; k < K; ++k)\n            s += (double)replicas[k][j];", "for (int k = 0; k < K - 1; ++k)\n            s += (double)replicas[k][j];"),
+ ("avg float accumulate", "double s = 0.0;\n        for (int k = 0; k < K; ++k)\n            s += (double)replicas[k][j];\n        float mean = (float)(s / (double)K);", "float s = 0.0f;\n        for (int k = 0; k < K; ++k)\n            s += replicas[k][j];\n        float mean = s / (float)K;"),
+ ("avg no writeback", "for (int k = 0; k < K; ++k)\n            replicas[k][j] = mean;", "for (int k = 1; k < K; ++k)\n            replicas[k][j] = mean;"),
+ ("flag strict", "return delta_g >= threshold ? 1 : 0;", "return delta_g > threshold ? 1 : 0;"),
+ ("bf16 truncates", "u += 0x7fffu + lsb;", "u += 0;"),
+ ("bf16 ties away", "u += 0x7fffu + lsb;", "u += 0x8000u;"),
+]
+
+
+@pytest.fixture(scope="module")
+def tree(tmp_path_factory):
+    base = str(tmp_path_factory.mktemp("mutants"))
+    for d in ("oracle", "tests", "paper_2307_07950_amd"):
+        shutil.copytree(os.path.join(ROOT, d), os.path.join(base, d),
+                        ignore=shutil.ignore_patterns("*.so", "__pycache__", "csrc", "*.tmp.*"))
+    return base
+
+
+def run_pins(base):
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "-q", "-x",
+                        "-p", "no:cacheprovider"], cwd=base, capture_output=True, text=True, timeout=300)
+    return r.returncode, r.stdout[-2000:]
+
+
+def test_unmutated_copy_passes(tree):
+    rc, out = run_pins(tree)
+    assert rc == 0, out
+
+
+@pytest.mark.parametrize("name,old,new", MUT, ids=[m[0].replace(" ", "_") for m in MUT])
+def test_pins_catch_planted_mistake(tree, name, old, new):
+    path = os.path.join(tree, "oracle", "selsync_oracle.c")
+    good = open(os.path.join(ROOT, "oracle", "selsync_oracle.c")).read()
+    assert good.count(old) >= 1, "mutation site not found: %s" % name
+    try:
+        open(path, "w").write(good.replace(old, new, 1))
+        os.utime(path, None)
+        rc, out = run_pins(tree)
+        assert rc != 0, "the pins did not notice: %s" % name
+    finally:
+        open(path, "w").write(good)
+        os.utime(path, None)
