@@ -241,8 +241,27 @@ int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sg
 int32_t selsync_read_decision(selsync_ctx *ctx, void *stream, double *norm_sq_out, double *delta_out,
                               int32_t *flags_out, int32_t *sync_out);
 
+/*
+ * Per-tensor squared gradient norms ||grad_scale*g_{k,t}||^2 of the LAST tracking pass
+ * (selsync_track_grad_change or selsync_step) enqueued with this plan, summed from the same
+ * per-chunk partials as the whole-model norm (Sec. II-E motivates per-layer gradient
+ * statistics).  out: HOST array of num_workers * num_tensors doubles, index k*T + t.
+ * Blocking.  SELSYNC_ERR_STATE if no tracking pass has run on the plan.
+ */
+int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *plan, void *stream, double *out);
+
 /* Blocking fetch of the cumulative counters (Eq. 4). */
 int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_stats *out);
+
+/*
+ * Checkpoint / resume of the tracker: windows, previous smoothed values, counters, delta and
+ * the automatic first-step marker as one opaque blob in HOST memory (tensors are the caller's
+ * to save).  A blob can only be restored into a context with the same num_workers, window and
+ * alpha.  Both calls block on `stream`.
+ */
+int32_t selsync_tracker_state_size(const selsync_ctx *ctx, int64_t *bytes);
+int32_t selsync_tracker_get_state(selsync_ctx *ctx, void *stream, void *buf, int64_t bytes);
+int32_t selsync_tracker_set_state(selsync_ctx *ctx, void *stream, const void *buf, int64_t bytes);
 
 /*
  * Per-kernel timing with HIP events recorded on the caller's stream around every

@@ -97,7 +97,11 @@ PROTOTYPES = {
     "selsync_aggregate_params": (_i32, [_vp, _vp, _i32, _vp]),
     "selsync_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_read_decision": (_i32, [_vp, _vp, _dp, _dp, _ip, _ip]),
+    "selsync_read_tensor_norms": (_i32, [_vp, _vp, _vp, _dp]),
     "selsync_get_stats": (_i32, [_vp, _vp, ctypes.POINTER(selsync_stats)]),
+    "selsync_tracker_state_size": (_i32, [_vp, ctypes.POINTER(ctypes.c_int64)]),
+    "selsync_tracker_get_state": (_i32, [_vp, _vp, _vp, ctypes.c_int64]),
+    "selsync_tracker_set_state": (_i32, [_vp, _vp, _vp, ctypes.c_int64]),
     "selsync_profile_enable": (_i32, [_vp, _i32, _i32]),
     "selsync_profile_config": (_i32, [_vp, _i32, _i32]),
     "selsync_profile_summary": (_i32, [_vp, _i32, ctypes.POINTER(ctypes.c_int64), _dp]),
@@ -286,11 +290,29 @@ class SelSync:
                          allow_warn=True)
         return self._decision(rc, n, d, f, s)
 
+    def read_tensor_norms(self, plan: Plan, stream=None) -> List[List[float]]:
+        """[k][t] squared norms of the last tracking pass on `plan`."""
+        T = plan.info()["num_tensors"]
+        out = (ctypes.c_double * max(1, self.num_workers * T))()
+        self._check(selsync_read_tensor_norms(self._h, plan._h, _vp(_stream_handle(stream)), out))
+        return [[out[k * T + t] for t in range(T)] for k in range(self.num_workers)]
+
     def stats(self, stream=None) -> dict:
         st = selsync_stats()
         self._check(selsync_get_stats(self._h, _vp(_stream_handle(stream)), ctypes.byref(st)))
         return {"steps_local": st.steps_local, "steps_sync": st.steps_sync, "lssr": st.lssr,
                 "max_delta": st.max_delta, "nonfinite_steps": st.nonfinite_steps}
+
+    def get_state(self, stream=None) -> bytes:
+        n = ctypes.c_int64()
+        self._check(selsync_tracker_state_size(self._h, ctypes.byref(n)))
+        buf = ctypes.create_string_buffer(n.value)
+        self._check(selsync_tracker_get_state(self._h, _vp(_stream_handle(stream)), buf, n.value))
+        return buf.raw
+
+    def set_state(self, blob: bytes, stream=None):
+        buf = ctypes.create_string_buffer(blob, len(blob))
+        self._check(selsync_tracker_set_state(self._h, _vp(_stream_handle(stream)), buf, len(blob)))
 
     def profile_enable(self, enable: bool = True, max_launches: int = 4096):
         self._check(selsync_profile_enable(self._h, int(enable), max_launches))

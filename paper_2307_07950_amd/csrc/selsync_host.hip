@@ -39,6 +39,7 @@ struct selsync_ctx {
     selsync_tuning tuning{0, 0, -1, 0, 0, -1};
     // device state: one allocation, sub-pointers in td
     void *d_state = nullptr;
+    size_t state_bytes = 0;        // size of the d_state allocation
     size_t out_bytes = 0;          // bytes of the DecisionHeader block incl. the K-arrays
     TrackerDev td{};
     void *h_out = nullptr;         // pinned mirror of the decision block
@@ -72,6 +73,10 @@ struct selsync_plan {
     int2 *d_segs = nullptr;
     double *d_seg_sums = nullptr;
     int32_t *d_seg_begin = nullptr;
+    // per-tensor norms (observability): chunk range of every (worker, tensor) pair
+    int32_t *d_tensor_chunk_begin = nullptr;
+    double *d_tensor_norms = nullptr;
+    bool partials_valid = false;     // a tracking pass has been enqueued on this plan
     AggChunkRec *d_agg_chunks = nullptr;
     AggTables agg{};
     LaunchCfg upd_cfg{1, 1, 0};
@@ -274,6 +279,7 @@ int32_t resolve_sgd(selsync_ctx *ctx, const selsync_sgd *sgd, SgdArgs *out)
 // a1 final passes + a2: (optional) segment reduction, then the single-workgroup tracker.
 int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
 {
+    plan->partials_valid = true;
     ProfScope p(ctx, 1, s);
     if (plan->n_segs > 0) {
         HIP_TRY(ctx, launch_reduce(plan->d_partials, plan->d_segs, plan->n_segs, plan->d_seg_sums, s));
@@ -379,6 +385,7 @@ extern "C" int32_t selsync_create(const selsync_config *cfg, selsync_ctx **out)
     const size_t o_hasprev = take(sizeof(int32_t) * K);
     const size_t o_weights = take(sizeof(double) * W);
     const size_t o_thr = take(sizeof(double));
+    ctx->state_bytes = off;
     hipError_t e = hipMalloc(&ctx->d_state, off);
     if (e != hipSuccess)
         return bail(e == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP);
@@ -549,6 +556,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     std::vector<TensorRec> recs;
     std::vector<ChunkRec> chunks;
     std::vector<int32_t> chunk_begin(K + 1, 0);
+    std::vector<int32_t> tensor_chunk_begin((size_t)K * T + 1, 0);
     if (grads) {
         recs.resize((size_t)K * T);
         for (int k = 0; k < K; ++k) {
@@ -565,6 +573,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
                     r.lowp = nullptr;
                 }
                 recs[(size_t)k * T + t] = r;
+                tensor_chunk_begin[(size_t)k * T + t] = (int32_t)chunks.size();
                 const bool al = aligned16(r.g) && aligned16(r.w) && aligned16(r.m) && (!mixed || aligned16(r.lowp));
                 split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
                     ChunkRec c;
@@ -576,6 +585,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
             }
         }
         chunk_begin[K] = (int32_t)chunks.size();
+        tensor_chunk_begin[(size_t)K * T] = (int32_t)chunks.size();
     }
     if (chunks.size() > (size_t)INT32_MAX)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan (%zu chunks)", chunks.size());
@@ -652,6 +662,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     const size_t o_segs = take(segs.size() * sizeof(int2));
     const size_t o_segsum = take(segs.size() * sizeof(double));
     const size_t o_segbegin = take(seg_begin.size() * sizeof(int32_t));
+    const size_t o_tcb = take(tensor_chunk_begin.size() * sizeof(int32_t));
+    const size_t o_tnorm = take((size_t)K * T * sizeof(double));
     const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
     const size_t o_aw = take(agg_w.size() * sizeof(float *));
     const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
@@ -668,6 +680,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     put(o_begin, chunk_begin.data(), chunk_begin.size() * sizeof(int32_t));
     put(o_segs, segs.data(), segs.size() * sizeof(int2));
     put(o_segbegin, seg_begin.data(), seg_begin.size() * sizeof(int32_t));
+    put(o_tcb, tensor_chunk_begin.data(), tensor_chunk_begin.size() * sizeof(int32_t));
     put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
     put(o_aw, agg_w.data(), agg_w.size() * sizeof(float *));
     put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
@@ -693,6 +706,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->d_segs = reinterpret_cast<int2 *>(b + o_segs);
     plan->d_seg_sums = reinterpret_cast<double *>(b + o_segsum);
     plan->d_seg_begin = reinterpret_cast<int32_t *>(b + o_segbegin);
+    plan->d_tensor_chunk_begin = reinterpret_cast<int32_t *>(b + o_tcb);
+    plan->d_tensor_norms = reinterpret_cast<double *>(b + o_tnorm);
     plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
     plan->agg.w = reinterpret_cast<float *const *>(b + o_aw);
     plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
@@ -870,6 +885,25 @@ extern "C" int32_t selsync_read_decision(selsync_ctx *ctx, void *stream, double 
                           nullptr);
 }
 
+extern "C" int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *plan, void *stream, double *out)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    if (!out)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "out is NULL");
+    if (!plan->partials_valid)
+        return fail(ctx, SELSYNC_ERR_STATE, "no tracking pass has run on this plan yet");
+    const int n = plan->K * plan->T;
+    if (n == 0)
+        return SELSYNC_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(ctx, launch_tensor_norms(plan->d_partials, plan->d_tensor_chunk_begin, n, plan->d_tensor_norms, s));
+    HIP_TRY(ctx, hipMemcpyAsync(out, plan->d_tensor_norms, sizeof(double) * n, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    return SELSYNC_OK;
+}
+
 extern "C" int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_stats *out)
 {
     if (!ctx)
@@ -889,6 +923,67 @@ extern "C" int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_sta
     out->lssr = tot ? (double)h.steps_local / (double)tot : std::nan("");
     out->max_delta = h.max_delta;
     out->nonfinite_steps = h.nonfinite_steps;
+    return SELSYNC_OK;
+}
+
+namespace {
+struct StateHeader {
+    uint64_t magic;
+    int32_t num_workers, window;
+    double alpha;
+    int64_t local_steps;
+    uint64_t payload_bytes;
+};
+constexpr uint64_t kStateMagic = 0x53454c53594e4331ull;   // "SELSYNC1"
+}  // namespace
+
+extern "C" int32_t selsync_tracker_state_size(const selsync_ctx *ctx, int64_t *bytes)
+{
+    if (!ctx || !bytes)
+        return SELSYNC_ERR_INVALID_ARG;
+    *bytes = (int64_t)(sizeof(StateHeader) + ctx->state_bytes);
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_tracker_get_state(selsync_ctx *ctx, void *stream, void *buf, int64_t bytes)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!buf || bytes < (int64_t)(sizeof(StateHeader) + ctx->state_bytes))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "buffer is NULL or smaller than selsync_tracker_state_size");
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    StateHeader h{kStateMagic, ctx->cfg.num_workers, ctx->cfg.window, ctx->cfg.alpha, ctx->local_steps,
+                  (uint64_t)ctx->state_bytes};
+    std::memcpy(buf, &h, sizeof h);
+    HIP_TRY(ctx, hipMemcpyAsync(static_cast<char *>(buf) + sizeof h, ctx->d_state, ctx->state_bytes,
+                                hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_tracker_set_state(selsync_ctx *ctx, void *stream, const void *buf, int64_t bytes)
+{
+    if (!ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    if (!buf || bytes < (int64_t)sizeof(StateHeader))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "buffer is NULL or too small");
+    StateHeader h;
+    std::memcpy(&h, buf, sizeof h);
+    if (h.magic != kStateMagic || h.num_workers != ctx->cfg.num_workers || h.window != ctx->cfg.window ||
+        h.alpha != ctx->cfg.alpha || h.payload_bytes != ctx->state_bytes ||
+        bytes < (int64_t)(sizeof h + h.payload_bytes))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "state blob does not match this context (workers/window/alpha)");
+    int32_t rc = check_device(ctx);
+    if (rc)
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_state, static_cast<const char *>(buf) + sizeof h, ctx->state_bytes,
+                                hipMemcpyHostToDevice, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    ctx->local_steps = h.local_steps;
     return SELSYNC_OK;
 }
 

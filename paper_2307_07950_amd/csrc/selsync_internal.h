@@ -111,6 +111,10 @@ hipError_t launch_track(const TrackerDev &td, const double *partials, const int3
 hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
                             const int32_t *sync_flag, int mode, const LaunchCfg &cfg, hipStream_t s);
 
+// out[i] = sum of partials[range_begin[i] .. range_begin[i+1]), one workgroup per range.
+hipError_t launch_tensor_norms(const double *partials, const int32_t *range_begin, int nranges, double *out,
+                               hipStream_t s);
+
 hipError_t launch_reset(const TrackerDev &td, hipStream_t s);
 hipError_t launch_set_delta(const TrackerDev &td, double delta, hipStream_t s);
 

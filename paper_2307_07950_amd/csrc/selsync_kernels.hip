@@ -324,21 +324,17 @@ constexpr int kReduceBlock = 256;
 
 // Intermediate level of the deterministic norm reduction: workgroup j sums the per-chunk
 // partials of segment j (a fixed range inside one worker's chunks) and writes one value.
-// Order: thread-strided accumulation (8 independent loads in flight), wavefront
-// shuffle, then the four wave results through LDS in wave order.
-__global__ __launch_bounds__(kReduceBlock) void k_reduce(const double *__restrict__ partials,
-                                                         const int2 *__restrict__ segs,
-                                                         double *__restrict__ seg_sums)
+// Sum of partials[b, e) by one workgroup, fixed order: thread-strided accumulation with 8
+// independent loads in flight, wavefront shuffle, then the four wave results in wave order.
+__device__ __forceinline__ double block_range_sum(const double *__restrict__ partials, int b, int e, double *red)
 {
-    __shared__ double red[kReduceBlock / 64];
-    const int2 sg = segs[blockIdx.x];
     double a8[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-    for (int i = sg.x + (int)threadIdx.x; i < sg.y; i += 8 * kReduceBlock) {
+    for (int i = b + (int)threadIdx.x; i < e; i += 8 * kReduceBlock) {
         double v[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int idx = i + j * kReduceBlock;
-            v[j] = idx < sg.y ? partials[idx] : 0.0;
+            v[j] = idx < e ? partials[idx] : 0.0;
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j)
@@ -349,8 +345,30 @@ __global__ __launch_bounds__(kReduceBlock) void k_reduce(const double *__restric
     if ((threadIdx.x & 63) == 0)
         red[threadIdx.x >> 6] = acc;
     __syncthreads();
+    return ((red[0] + red[1]) + red[2]) + red[3];
+}
+
+// Per-tensor squared norms from the per-chunk partials of the last tracking pass: workgroup i
+// sums the chunk range of one (worker, tensor) pair.
+__global__ __launch_bounds__(kReduceBlock) void k_tensor_norms(const double *__restrict__ partials,
+                                                               const int32_t *__restrict__ range_begin,
+                                                               double *__restrict__ out)
+{
+    __shared__ double red[kReduceBlock / 64];
+    const double s = block_range_sum(partials, range_begin[blockIdx.x], range_begin[blockIdx.x + 1], red);
     if (threadIdx.x == 0)
-        seg_sums[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
+        out[blockIdx.x] = s;
+}
+
+__global__ __launch_bounds__(kReduceBlock) void k_reduce(const double *__restrict__ partials,
+                                                         const int2 *__restrict__ segs,
+                                                         double *__restrict__ seg_sums)
+{
+    __shared__ double red[kReduceBlock / 64];
+    const int2 sg = segs[blockIdx.x];
+    const double s = block_range_sum(partials, sg.x, sg.y, red);
+    if (threadIdx.x == 0)
+        seg_sums[blockIdx.x] = s;
 }
 
 // ---------------------------------------------------------------- k_track
@@ -782,6 +800,15 @@ hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, do
     if (nsegs <= 0)
         return hipSuccess;
     hipLaunchKernelGGL(k_reduce, dim3(nsegs), dim3(kReduceBlock), 0, s, partials, segs, seg_sums);
+    return hipGetLastError();
+}
+
+hipError_t launch_tensor_norms(const double *partials, const int32_t *range_begin, int nranges, double *out,
+                               hipStream_t s)
+{
+    if (nranges <= 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(k_tensor_norms, dim3(nranges), dim3(kReduceBlock), 0, s, partials, range_begin, out);
     return hipGetLastError();
 }
 

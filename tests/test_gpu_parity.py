@@ -343,6 +343,62 @@ def test_reset_clears_tracker_and_counters(B):
     ls.close()
 
 
+def test_per_tensor_norms_match_oracle(B):
+    numel = [70001, 0, 5, 4096, 513]
+    K = 3
+    for mixed in (False, True):
+        ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, seed=17)
+        r = rng(97)
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 10.0 ** r.uniform(-3, 0)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(0, grads)
+        with pytest.raises(B.SelSyncError) as e:
+            ls.ctx.read_tensor_norms(ls.plans[0])
+        assert e.value.status == B.SELSYNC_ERR_STATE
+        dec = ls.ctx.track_grad_change(ls.plans[0], 0.5, blocking=True)
+        got = ls.ctx.read_tensor_norms(ls.plans[0])
+        for k in range(K):
+            for t in range(len(numel)):
+                want = O.norm_sq([grads[k][t]], 0.5)
+                assert got[k][t] == pytest.approx(want, rel=1e-12, abs=0.0)
+            assert sum(got[k]) == pytest.approx(dec.norm_sq[k], rel=1e-12)
+        ls.close()
+
+
+def test_tracker_state_checkpoint_and_resume(B):
+    numel = [9000]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=0.05, window=7, alpha=0.3, seed=18)
+    g = [[rng(98 + k).standard_normal(9000).astype(np.float32)] for k in range(K)]
+    ls.bind_grads(0, g)
+    scales = [float(np.float32(v)) for v in np.exp(np.cumsum(rng(99).standard_normal(30) * 0.2))]
+    for t in range(12):
+        ls.ctx.track_grad_change(ls.plans[0], scales[t], blocking=True)
+    blob = ls.ctx.get_state()
+    stats_at_save = ls.ctx.stats()
+    tail_a = [ls.ctx.track_grad_change(ls.plans[0], scales[t], blocking=True) for t in range(12, 30)]
+    # a fresh context with the same configuration resumes from the blob
+    ctx2 = B.SelSync(K, 0.9, 7, 0.3)                 # different delta: the blob restores it
+    plan2 = ctx2.plan(ls.d_grads[0], ls.d_w, ls.d_m, ls.d_glob)
+    ctx2.set_state(blob)
+    assert ctx2.stats() == stats_at_save
+    tail_b = [ctx2.track_grad_change(plan2, scales[t], blocking=True) for t in range(12, 30)]
+    for a, b in zip(tail_a, tail_b):
+        assert a.flags == b.flags and a.sync == b.sync
+        assert [x.hex() for x in a.delta] == [x.hex() for x in b.delta]
+    assert ctx2.stats() == ls.ctx.stats()
+    # a context with another window refuses the blob
+    ctx3 = B.SelSync(K, 0.05, 8, 0.3)
+    with pytest.raises(B.SelSyncError) as e:
+        ctx3.set_state(blob)
+    assert e.value.status == B.SELSYNC_ERR_INVALID_ARG
+    ctx3.close()
+    ctx2.close()
+    ls.close()
+
+
 # ================================================================= the five workloads, lock step
 
 @pytest.mark.parametrize("name,shrink,steps,compare_every", [
