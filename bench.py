@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga"],
+                    help="pa: fused selsync_step (default, the headline); unfused: the three primitives in Alg. 1 "
+                         "order; ga: gradient-aggregation variant (selsync_step_ga)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events in the timed loop (roofline.achieved becomes null)")
@@ -174,7 +177,15 @@ def main():
 
     def run(t0, n):
         for t in range(t0, t0 + n):
-            ctx.step(plans[t % wl.pool], wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
+            plan = plans[t % wl.pool]
+            if args.variant == "pa":
+                ctx.step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
+            elif args.variant == "unfused":
+                ctx.track_grad_change(plan, sig[t], blocking=False)
+                ctx.local_step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
+                ctx.aggregate_params(plan, always=False)
+            else:
+                ctx.step_ga(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -207,6 +218,9 @@ def main():
     assert n_sync + n_local == args.steps
     lssr_run = n_local / args.steps
     b_local, b_sync = algorithmic_bytes(wl, P)
+    if args.variant == "ga":
+        # the decision must precede the update, so the gradients are read twice; no parameter exchange
+        b_local, b_sync = b_local + K * (2 if wl.mixed_bf16 else 4) * P, 0
     total_bytes = args.steps * b_local + n_sync * b_sync
     eff_gbps = total_bytes / elapsed / 1e9
     ms_per_step = elapsed / args.steps * 1e3
@@ -216,7 +230,8 @@ def main():
     agg_ms_all = kern[2][1] / max(1, kern[2][0])          # includes the early-exit launches of local steps
     achieved = b_local / (upd_ms * 1e-3) / 1e9 if kern[0][0] else None
     result = {
-        "metric": "SelSync steps/s (one GPU, K replicas in HBM)",
+        "metric": "SelSync steps/s (one GPU, K replicas in HBM)" + ("" if args.variant == "pa" else
+                                                                       " [variant: %s]" % args.variant),
         "value": args.steps / elapsed,
         "unit": "steps/s",
         "n_gpus": 1,
@@ -249,13 +264,16 @@ def main():
         },
         "other_kernels": None,
     }
+    if args.variant != "pa":
+        result["roofline"] = None        # the roofline object describes the fused kernel of the headline path
+        cpu = None
     if args.all_kernel_events and not args.no_kernel_events:
         result["other_kernels"] = {
             "k_reduce_plus_k_track_avg_ms": trk_ms,
             "k_aggregate_avg_ms_over_all_launches": agg_ms_all,      # local steps launch it too (it exits at once)
             "k_aggregate_est_ms_per_sync": (kern[2][1] / n_sync) if n_sync else None,
         }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.variant == "pa":
         # release the GPU-side working set first: the oracle needs host memory only
         result["cpu_baseline"] = cpu_baseline(wl, lssr_run, args.cpu_steps)
     else:

@@ -235,6 +235,26 @@ int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sg
                      int32_t blocking, double *norm_sq_out, double *delta_out,
                      int32_t *flags_out, int32_t *sync_out);
 
+/* ---- variant: gradient aggregation (Sec. III-C) ------------------------------------------ */
+
+/*
+ * Update of all K replicas under gradient aggregation.  When the decision is "sync"
+ * (mode 0: the device-side decision of the last tracking call; mode 1: always), the scaled
+ * gradients are averaged over the workers, gbar = fl32((sum_k (double)fl32(grad_scale*g_k))/K),
+ * and EVERY worker applies gbar to its OWN parameters and momentum; otherwise every worker
+ * applies its own gradient (the plain local update).  Replicas that have drifted apart stay
+ * apart -- the behaviour the paper contrasts with parameter aggregation.  The global model is
+ * not written.  Counts as a local update for the automatic first-step marker.
+ */
+int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, int32_t mode,
+                          void *stream);
+
+/* One iteration with gradient aggregation: tracking pass over the gradients (a1 + a2), then
+ * selsync_ga_update(mode 0).  Outputs as for selsync_track_grad_change. */
+int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
+                        int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                        int32_t *sync_out);
+
 /* ---- observability ---------------------------------------------------------------- */
 
 /* Blocking fetch of the last step's device-side results (same outputs as tracking). */

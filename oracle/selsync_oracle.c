@@ -165,6 +165,61 @@ void selsync_oracle_average_bf16(float *const *masters, uint16_t *const *copies,
     }
 }
 
+/* ------------------------------------------------------------------ variant: gradient aggregation */
+
+/*
+ * Gradient aggregation (Sec. III-C): on a synchronising step the workers exchange
+ * gradients instead of parameters and every worker applies the same averaged gradient
+ *     gbar_j = fl32( (sum_{k=0..K-1} (double)fl32(grad_scale * g_{k,j})) / K )
+ * to its OWN parameters and momentum.  This only forms gbar; the update itself is
+ * selsync_oracle_sgd_f32 with gbar as the gradient and grad_scale 1.
+ */
+void selsync_oracle_average_grads_f32(const float *const *grads, int K, float grad_scale, float *gbar, int64_t n)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        double s = 0.0;
+        for (int k = 0; k < K; ++k) {
+            float gh = grad_scale * grads[k][j];
+            s += (double)gh;
+        }
+        gbar[j] = (float)(s / (double)K);
+    }
+}
+
+void selsync_oracle_average_grads_bf16(const uint16_t *const *grads, int K, float grad_scale, float *gbar, int64_t n)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        double s = 0.0;
+        for (int k = 0; k < K; ++k) {
+            float gh = grad_scale * selsync_oracle_bf16_to_f32(grads[k][j]);
+            s += (double)gh;
+        }
+        gbar[j] = (float)(s / (double)K);
+    }
+}
+
+/* Mixed-precision update driven by an fp32 gradient (the averaged one). */
+void selsync_oracle_sgd_mixed_f32grad(float *master, float *m, const float *g, uint16_t *copy, int64_t n,
+                                      float lr, float mu, float wd, int first)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = g[j];
+        float dec = wd * master[j];
+        float d = gh + dec;
+        float mom;
+        if (first) {
+            mom = d;
+        } else {
+            float mm = mu * m[j];
+            mom = mm + d;
+        }
+        float stepv = lr * mom;
+        m[j] = mom;
+        master[j] = master[j] - stepv;
+        copy[j] = selsync_oracle_f32_to_bf16(master[j]);
+    }
+}
+
 /* ------------------------------------------------------------------ a2: significance tracker */
 
 /*

@@ -60,6 +60,14 @@ def lib() -> ctypes.CDLL:
         L.selsync_oracle_average_bf16.restype = None
         L.selsync_oracle_average_bf16.argtypes = [ctypes.POINTER(f32p), ctypes.POINTER(u16p), ctypes.c_int,
                                                   f32p, u16p, ctypes.c_int64]
+        L.selsync_oracle_average_grads_f32.restype = None
+        L.selsync_oracle_average_grads_f32.argtypes = [ctypes.POINTER(f32p), ctypes.c_int, ctypes.c_float, f32p,
+                                                       ctypes.c_int64]
+        L.selsync_oracle_average_grads_bf16.restype = None
+        L.selsync_oracle_average_grads_bf16.argtypes = [ctypes.POINTER(u16p), ctypes.c_int, ctypes.c_float, f32p,
+                                                        ctypes.c_int64]
+        L.selsync_oracle_sgd_mixed_f32grad.restype = None
+        L.selsync_oracle_sgd_mixed_f32grad.argtypes = [f32p, f32p, f32p, u16p, ctypes.c_int64] + [ctypes.c_float] * 3 + [ctypes.c_int]
         L.selsync_oracle_tracker_new.restype = ctypes.c_void_p
         L.selsync_oracle_tracker_new.argtypes = [ctypes.c_int, ctypes.c_double]
         L.selsync_oracle_tracker_free.restype = None
@@ -162,6 +170,50 @@ def average_params(replicas: Sequence[Sequence[np.ndarray]], global_model: Seque
         else:
             cptrs = (u16p * K)(*[_u16(copies[k][t]) for k in range(K)])
             L.selsync_oracle_average_bf16(ptrs, cptrs, K, _f32(global_model[t]), _u16(global_copy[t]), n)
+
+
+# ---------------------------------------------------------------- variant: gradient aggregation
+
+def average_grads(grads: Sequence[Sequence[np.ndarray]], grad_scale: float = 1.0) -> List[np.ndarray]:
+    """Mean over the K workers of the scaled gradients, one fp32 array per tensor (Sec. III-C)."""
+    L = lib()
+    K = len(grads)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    out = []
+    for t in range(len(grads[0])):
+        n = grads[0][t].size
+        gbar = np.empty(n, np.float32)
+        if grads[0][t].dtype == np.uint16:
+            ptrs = (u16p * K)(*[_u16(grads[k][t]) for k in range(K)])
+            L.selsync_oracle_average_grads_bf16(ptrs, K, grad_scale, _f32(gbar), n)
+        else:
+            ptrs = (f32p * K)(*[_f32(grads[k][t]) for k in range(K)])
+            L.selsync_oracle_average_grads_f32(ptrs, K, grad_scale, _f32(gbar), n)
+        out.append(gbar)
+    return out
+
+
+def ga_update(grads, params, momenta, lr, momentum, weight_decay, grad_scale=1.0, first=False, sync=True,
+              copies=None) -> None:
+    """Update of all K workers under gradient aggregation: on a synchronising step every
+    worker applies the averaged gradient to its own state, otherwise its own gradient."""
+    L = lib()
+    K = len(params)
+    if not sync:
+        for k in range(K):
+            sgd_update(params[k], momenta[k], grads[k], lr, momentum, weight_decay, grad_scale, first,
+                       None if copies is None else copies[k])
+        return
+    gbar = average_grads(grads, grad_scale)
+    for k in range(K):
+        if copies is None:
+            sgd_update(params[k], momenta[k], gbar, lr, momentum, weight_decay, 1.0, first)
+        else:
+            for t in range(len(gbar)):
+                L.selsync_oracle_sgd_mixed_f32grad(_f32(params[k][t]), _f32(momenta[k][t]), _f32(gbar[t]),
+                                                   _u16(copies[k][t]), gbar[t].size, lr, momentum, weight_decay,
+                                                   int(first))
 
 
 # ---------------------------------------------------------------- a2

@@ -96,6 +96,8 @@ PROTOTYPES = {
     "selsync_local_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp]),
     "selsync_aggregate_params": (_i32, [_vp, _vp, _i32, _vp]),
     "selsync_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_ga_update": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _i32, _vp]),
+    "selsync_step_ga": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_read_decision": (_i32, [_vp, _vp, _dp, _dp, _ip, _ip]),
     "selsync_read_tensor_norms": (_i32, [_vp, _vp, _vp, _dp]),
     "selsync_get_stats": (_i32, [_vp, _vp, ctypes.POINTER(selsync_stats)]),
@@ -281,6 +283,21 @@ class SelSync:
         n, d, f, s = self._outs()
         rc = self._check(selsync_step(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
                                       int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
+        return self._decision(rc, n, d, f, s) if blocking else None
+
+    # -- variant: gradient aggregation
+    def ga_update(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                  grad_scale: float = 1.0, first_step: int = -1, always: bool = False, stream=None):
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step)
+        self._check(selsync_ga_update(self._h, plan._h, ctypes.byref(sgd), 1 if always else 0,
+                                      _vp(_stream_handle(stream))))
+
+    def step_ga(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                grad_scale: float = 1.0, first_step: int = -1, blocking: bool = False, stream=None):
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step)
+        n, d, f, s = self._outs()
+        rc = self._check(selsync_step_ga(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
+                                         int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
         return self._decision(rc, n, d, f, s) if blocking else None
 
     # -- observability

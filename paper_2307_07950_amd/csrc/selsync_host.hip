@@ -609,6 +609,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     std::vector<uint16_t *> agg_c(mixed ? (size_t)T * K : 0);
     std::vector<float *> agg_g(T);
     std::vector<uint16_t *> agg_gc(mixed ? T : 0);
+    std::vector<const void *> agg_grad(grads ? (size_t)T * K : 0);
+    std::vector<float *> agg_m(grads ? (size_t)T * K : 0);
     for (int t = 0; t < T; ++t) {
         bool al = true;
         for (int k = 0; k < K; ++k) {
@@ -621,6 +623,14 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
             }
             al = al && aligned16(agg_w[(size_t)t * K + k]);
         }
+        bool al_grads = grads != nullptr;
+        if (grads) {
+            for (int k = 0; k < K; ++k) {
+                agg_grad[(size_t)t * K + k] = grads[k].tensors[t].data;
+                agg_m[(size_t)t * K + k] = static_cast<float *>(momenta[k].tensors[t].data);
+                al_grads = al_grads && aligned16(agg_grad[(size_t)t * K + k]) && aligned16(agg_m[(size_t)t * K + k]);
+            }
+        }
         agg_g[t] = static_cast<float *>(global[0].tensors[t].data);
         al = al && aligned16(agg_g[t]);
         if (mixed) {
@@ -630,7 +640,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
         split_tensor(numel[t], agg_chunk, [&](int64_t off, int64_t n) {
             AggChunkRec c;
             c.t = (uint32_t)t;
-            c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u);
+            c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u) | (al_grads ? kChunkAlignedGrads : 0u);
             c.off = (uint64_t)off;
             agg_chunks.push_back(c);
         });
@@ -669,6 +679,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
     const size_t o_ag = take(agg_g.size() * sizeof(float *));
     const size_t o_agc = take(agg_gc.size() * sizeof(uint16_t *));
+    const size_t o_agrad = take(agg_grad.size() * sizeof(void *));
+    const size_t o_am = take(agg_m.size() * sizeof(float *));
 
     std::vector<char> blob(off, 0);
     auto put = [&](size_t o, const void *src, size_t bytes) {
@@ -686,6 +698,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
     put(o_ag, agg_g.data(), agg_g.size() * sizeof(float *));
     put(o_agc, agg_gc.data(), agg_gc.size() * sizeof(uint16_t *));
+    put(o_agrad, agg_grad.data(), agg_grad.size() * sizeof(void *));
+    put(o_am, agg_m.data(), agg_m.size() * sizeof(float *));
 
     hipError_t e = hipMalloc(&plan->d_blob, off);
     if (e == hipSuccess)
@@ -713,6 +727,8 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
     plan->agg.global = reinterpret_cast<float *const *>(b + o_ag);
     plan->agg.glowp = reinterpret_cast<uint16_t *const *>(b + o_agc);
+    plan->agg.g = reinterpret_cast<const void *const *>(b + o_agrad);
+    plan->agg.m = reinterpret_cast<float *const *>(b + o_am);
 
     plan->upd_cfg.grid = std::max(1, grid_cap);
     plan->upd_cfg.nontemporal = nt;
@@ -866,6 +882,58 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
         HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
                                       &ctx->td.out->sync, 0, plan->agg_cfg, s));
     }
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
+// =============================================================================== variant: gradient aggregation
+
+extern "C" int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, int32_t mode,
+                                     void *stream)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    if (mode != 0 && mode != 1)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "mode must be 0 (follow the decision) or 1 (always aggregate)");
+    SgdArgs a;
+    if ((rc = resolve_sgd(ctx, sgd, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 2, s);
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+                                      &ctx->td.out->sync, mode, a, plan->agg_cfg, s));
+    }
+    ctx->local_steps += 1;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
+                                   int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                                   int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    SgdArgs a;
+    if ((rc = resolve_sgd(ctx, sgd, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
+                                   plan->d_partials, a, plan->upd_cfg, s));
+    }
+    if ((rc = enqueue_track(ctx, plan, s)))
+        return rc;
+    {
+        ProfScope p(ctx, 2, s);
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+                                      &ctx->td.out->sync, 0, a, plan->agg_cfg, s));
+    }
+    ctx->local_steps += 1;
     if (blocking)
         return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
     return SELSYNC_OK;

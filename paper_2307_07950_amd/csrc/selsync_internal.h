@@ -35,6 +35,7 @@ struct AggChunkRec {
 };
 
 constexpr uint32_t kChunkAligned = 0x80000000u;
+constexpr uint32_t kChunkAlignedGrads = 0x40000000u;   // aggregation chunks: gradients and momenta aligned too
 constexpr uint32_t kChunkCountMask = 0x0fffffffu;
 
 // Aggregation pointer tables (device arrays).
@@ -43,6 +44,8 @@ struct AggTables {
     uint16_t *const *lowp;     // [T*K]  bf16 copies (mixed only)
     float *const *global;      // [T]
     uint16_t *const *glowp;    // [T]    (mixed only)
+    const void *const *g;      // [T*K]  gradients (only when the plan has gradients)
+    float *const *m;           // [T*K]  momentum buffers (only when the plan has gradients)
 };
 
 // Results of the last step plus the cumulative counters; one contiguous block so a
@@ -114,6 +117,12 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
 // out[i] = sum of partials[range_begin[i] .. range_begin[i+1]), one workgroup per range.
 hipError_t launch_tensor_norms(const double *partials, const int32_t *range_begin, int nranges, double *out,
                                hipStream_t s);
+
+// Gradient-aggregation update (Sec. III-C): when the decision is "sync" (or mode 1) every worker
+// applies the mean gradient to its own parameters and momentum, otherwise its own gradient.
+hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
+                            const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
+                            hipStream_t s);
 
 hipError_t launch_reset(const TrackerDev &td, hipStream_t s);
 hipError_t launch_set_delta(const TrackerDev &td, double delta, hipStream_t s);

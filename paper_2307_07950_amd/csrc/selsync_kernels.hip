@@ -699,6 +699,160 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
     }
 }
 
+// ---------------------------------------------------------------- k_update_ga
+
+// Mean of K scaled gradients, fp64 sum in worker order, one rounding to fp32.
+template <int KC>
+__device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, double invK, int pow2)
+{
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    const int n = KC > 0 ? KC : K;
+    for (int k = 0; k < n; ++k) {
+        const float a0 = gs * g[k].x, a1 = gs * g[k].y, a2 = gs * g[k].z, a3 = gs * g[k].w;
+        s0 += (double)a0;
+        s1 += (double)a1;
+        s2 += (double)a2;
+        s3 += (double)a3;
+    }
+    f32x4 r;
+    r.x = finish_mean(s0, n, invK, pow2);
+    r.y = finish_mean(s1, n, invK, pow2);
+    r.z = finish_mean(s2, n, invK, pow2);
+    r.w = finish_mean(s3, n, invK, pow2);
+    return r;
+}
+
+__device__ __forceinline__ f32x4 widen4(u32x2 v)
+{
+    f32x4 g;
+    g.x = bf16_lo(v.x);
+    g.y = bf16_hi(v.x);
+    g.z = bf16_lo(v.y);
+    g.w = bf16_hi(v.y);
+    return g;
+}
+
+// Update of all K workers under gradient aggregation.  One workgroup walks one chunk of
+// one tensor across the K workers: with the decision "sync" the mean gradient is applied
+// to every worker's own (w, m); otherwise each worker applies its own gradient (the plain
+// local update).  K compile-time (KC > 0) keeps all 3K loads of a vector in flight.
+template <int BLOCK, int KC, bool MIXED, bool NT>
+__global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, int nchunks,
+                                                     AggTables tabs, int K, double invK, int pow2,
+                                                     const int32_t *__restrict__ sync_flag, int mode, SgdArgs a,
+                                                     int xcd_per)
+{
+    constexpr int KM = KC > 0 ? KC : 1;
+    const bool sync = mode == 1 || *sync_flag != 0;
+    SgdArgs a1 = a;   // applied to the mean gradient, which is already scaled
+    a1.gs = 1.f;
+    const uint32_t tid = threadIdx.x;
+    double unused = 0.0;
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    for (int v = blockIdx.x; v < vtotal; v += gridDim.x) {
+        const int c = chunk_of_workgroup(v, xcd_per);
+        if (c >= nchunks)
+            continue;
+        const AggChunkRec ch = chunks[c];
+        const uint32_t n = ch.n_flags & kChunkCountMask;
+        const size_t row = (size_t)ch.t * K;
+        uint32_t done = 0;
+        if constexpr (KC > 0) {
+            if ((ch.n_flags & kChunkAligned) && (ch.n_flags & kChunkAlignedGrads)) {
+                SELSYNC_GLOBAL f32x4 *wp[KM];
+                SELSYNC_GLOBAL f32x4 *mp[KM];
+                const SELSYNC_GLOBAL f32x4 *gp[KM];
+                const SELSYNC_GLOBAL u32x2 *gbp[KM];
+                SELSYNC_GLOBAL u32x2 *cp[KM];
+#pragma unroll
+                for (int k = 0; k < KC; ++k) {
+                    wp[k] = as_global<f32x4>(tabs.w[row + k] + ch.off);
+                    mp[k] = as_global<f32x4>(tabs.m[row + k] + ch.off);
+                    gp[k] = MIXED ? nullptr : as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + ch.off);
+                    gbp[k] = MIXED ? as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + ch.off)
+                                   : nullptr;
+                    cp[k] = MIXED ? as_global<u32x2>(tabs.lowp[row + k] + ch.off) : nullptr;
+                }
+                const uint32_t nvec = n / 4;
+                for (uint32_t i = tid; i < nvec; i += BLOCK) {
+                    f32x4 gv[KM], wv[KM], mv[KM];
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
+                        if (MIXED)
+                            gv[k] = widen4(ld<NT>(gbp[k] + i));
+                        else
+                            gv[k] = ld<NT>(gp[k] + i);
+                        wv[k] = ld<NT>(wp[k] + i);
+                        mv[k] = 0.f;
+                        if (!a.first)
+                            mv[k] = ld<NT>(mp[k] + i);
+                    }
+                    if (sync) {
+                        const f32x4 gbar = mean_grad4<KC>(gv, KC, a.gs, invK, pow2);
+#pragma unroll
+                        for (int k = 0; k < KC; ++k)
+                            elem4<true, false>(gbar, wv[k], mv[k], a1, unused);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < KC; ++k)
+                            elem4<true, false>(gv[k], wv[k], mv[k], a, unused);
+                    }
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
+                        st<NT>(wp[k] + i, wv[k]);
+                        st<NT>(mp[k] + i, mv[k]);
+                        if (MIXED) {
+                            u32x2 cv;
+                            cv.x = bf16_pack(wv[k].x, wv[k].y);
+                            cv.y = bf16_pack(wv[k].z, wv[k].w);
+                            st<NT>(cp[k] + i, cv);
+                        }
+                    }
+                }
+                done = nvec * 4;
+            }
+        }
+        // element-at-a-time: unaligned tensors, ragged tails, and any K without a compiled shape
+        for (uint32_t i = done + tid; i < n; i += BLOCK) {
+            const uint64_t e = ch.off + i;
+            float gbar = 0.f;
+            if (sync) {
+                double s = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    float g;
+                    if (MIXED)
+                        g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
+                    else
+                        g = as_global<const float>(tabs.g[row + k])[e];
+                    const float gh = a.gs * g;
+                    s += (double)gh;
+                }
+                gbar = finish_mean(s, K, invK, pow2);
+            }
+            for (int k = 0; k < K; ++k) {
+                SELSYNC_GLOBAL float *wq = as_global<float>(tabs.w[row + k]);
+                SELSYNC_GLOBAL float *mq = as_global<float>(tabs.m[row + k]);
+                float w = wq[e];
+                float m = a.first ? 0.f : mq[e];
+                if (sync) {
+                    elem<true, false>(gbar, w, m, a1, unused);
+                } else {
+                    float g;
+                    if (MIXED)
+                        g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
+                    else
+                        g = as_global<const float>(tabs.g[row + k])[e];
+                    elem<true, false>(g, w, m, a, unused);
+                }
+                wq[e] = w;
+                mq[e] = m;
+                if (MIXED)
+                    as_global<uint16_t>(tabs.lowp[row + k])[e] = (uint16_t)bf16_bits(w);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- dispatch helpers
 
 constexpr int kBlock = 256;
@@ -831,6 +985,52 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
                                : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s);
     return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s)
                            : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s);
+}
+
+namespace {
+template <int KC, bool MIXED, bool NT>
+hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
+                       int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
+{
+    const int pow2 = (K & (K - 1)) == 0;
+    hipLaunchKernelGGL((k_update_ga<kBlock, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs, K,
+                       1.0 / (double)K, pow2, flag, mode, sgd, xcd_per);
+    return hipGetLastError();
+}
+
+template <bool MIXED, bool NT>
+hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
+                       int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
+{
+    switch (K) {
+    case 1:
+        return launch_ga_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+    case 2:
+        return launch_ga_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+    case 4:
+        return launch_ga_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+    case 8:
+        return launch_ga_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+    default:
+        return launch_ga_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+    }
+}
+}  // namespace
+
+hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
+                            const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
+                            hipStream_t s)
+{
+    if (nchunks <= 0)
+        return hipSuccess;
+    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
+    if (mixed)
+        return cfg.nontemporal ? launch_ga_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
+                               : launch_ga_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
+    return cfg.nontemporal ? launch_ga_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
+                           : launch_ga_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
 }
 
 hipError_t launch_reset(const TrackerDev &td, hipStream_t s)

@@ -123,24 +123,8 @@ class LockStep:
         else:
             self.plans[slot] = self.ctx.plan(dg, self.d_w, self.d_m, self.d_glob)
 
-    # ---- one step on both sides
-    def step(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True,
-             compare_tensors: bool = True):
-        B = self.B
-        plan = self.plans[slot]
-        first = self.steps_done == 0
-        if fused:
-            dec = self.ctx.step(plan, lr, mu, wd, gs, first_step=int(first), blocking=True)
-        else:
-            dec = self.ctx.track_grad_change(plan, gs, blocking=True)
-            self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first))
-            self.ctx.aggregate_params(plan, always=False)
-        g = self.h_grads[slot]
-        rec = self.oracle.track(g, gs)
-        for k in range(self.K):
-            O.sgd_update(self.h_w[k], self.h_m[k], g[k], lr, mu, wd, gs, first,
-                         None if not self.mixed else self.h_c[k])
-        # --- a1 / a2 parity
+    def _check_decision(self, dec, rec) -> int:
+        """Compare norms, Delta and flags of one step; returns the decision both sides follow."""
         for k in range(self.K):
             x, y = dec.norm_sq[k], rec.norm_sq[k]
             if math.isfinite(y):
@@ -165,6 +149,26 @@ class LockStep:
             self.forced += 1
             self.oracle.steps_sync += dec.sync - rec.sync
             self.oracle.steps_local -= dec.sync - rec.sync
+        return sync
+
+    # ---- one step on both sides
+    def step(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True,
+             compare_tensors: bool = True):
+        B = self.B
+        plan = self.plans[slot]
+        first = self.steps_done == 0
+        if fused:
+            dec = self.ctx.step(plan, lr, mu, wd, gs, first_step=int(first), blocking=True)
+        else:
+            dec = self.ctx.track_grad_change(plan, gs, blocking=True)
+            self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first))
+            self.ctx.aggregate_params(plan, always=False)
+        g = self.h_grads[slot]
+        rec = self.oracle.track(g, gs)
+        for k in range(self.K):
+            O.sgd_update(self.h_w[k], self.h_m[k], g[k], lr, mu, wd, gs, first,
+                         None if not self.mixed else self.h_c[k])
+        sync = self._check_decision(dec, rec)
         if sync:
             pre = [np.max(np.abs(np.stack([self.h_w[k][t] for k in range(self.K)])), axis=0).astype(np.float64)
                    for t in range(len(self.numel))]
@@ -173,6 +177,26 @@ class LockStep:
         self.steps_done += 1
         if compare_tensors or sync:          # every aggregation is checked, local steps on request
             self.compare(after_sync=bool(sync))
+        return dec, rec
+
+    def step_ga(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True):
+        """One iteration under gradient aggregation (Sec. III-C) on both sides."""
+        plan = self.plans[slot]
+        first = self.steps_done == 0
+        glob_before = [to_host(x) for x in self.d_glob]
+        if fused:
+            dec = self.ctx.step_ga(plan, lr, mu, wd, gs, first_step=int(first), blocking=True)
+        else:
+            dec = self.ctx.track_grad_change(plan, gs, blocking=True)
+            self.ctx.ga_update(plan, lr, mu, wd, gs, first_step=int(first), always=False)
+        g = self.h_grads[slot]
+        rec = self.oracle.track(g, gs)
+        sync = self._check_decision(dec, rec)
+        O.ga_update(g, self.h_w, self.h_m, lr, mu, wd, gs, first, bool(sync), self.h_c)
+        self.steps_done += 1
+        self.compare(after_sync=False)
+        for t in range(len(self.numel)):        # gradient aggregation never writes the global model
+            assert to_host(self.d_glob[t]).tobytes() == glob_before[t].tobytes()
         return dec, rec
 
     def compare(self, after_sync: bool = False):

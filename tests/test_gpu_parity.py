@@ -399,6 +399,56 @@ def test_tracker_state_checkpoint_and_resume(B):
     ls.close()
 
 
+# ================================================================= variant: gradient aggregation
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_gradient_aggregation_matches_oracle(B, K, mixed, misalign):
+    numel = [70001, 5, 4096, 0, 1023]
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=19)
+    r = rng(110 + K)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    # let the replicas drift apart first so that "replicas stay apart" is visible
+    for k in range(K):
+        for t, n in enumerate(numel):
+            ls.h_w[k][t] += np.float32(1e-3 * k)
+            ls.d_w[k][t].copy_(torch.from_numpy(ls.h_w[k][t]))
+            if mixed:
+                ls.h_c[k][t][...] = W.round_to_bf16_bits(ls.h_w[k][t])
+                ls.d_c[k][t].copy_(PU.to_dev(ls.h_c[k][t]))
+    syncs = 0
+    for t in range(9):
+        dec, rec = ls.step_ga([0, 1, 2, 2, 0, 1, 1, 2, 0][t], 0.05, 0.9, 1e-4, [1.0, 0.7][t % 2], fused=(t % 3 != 1))
+        syncs += rec.sync
+    assert syncs > 0 and syncs < 9 and ls.worst_ulp == 0
+    if K > 1:       # Sec. III-C: after gradient aggregation the workers' models are still different
+        assert PU.to_host(ls.d_w[0][0]).tobytes() != PU.to_host(ls.d_w[K - 1][0]).tobytes()
+    ls.close()
+
+
+def test_gradient_aggregation_always_mode_and_bsp_equivalence(B):
+    # from identical replicas, aggregating every step keeps all workers bit-identical (BSP with GA)
+    numel = [33333, 100]
+    K = 4
+    ls = PU.LockStep(B, numel, K, delta=float("inf"), seed=20)
+    for slot in range(2):
+        ls.bind_grads(slot, [[rng(130 + 10 * slot + k).standard_normal(n).astype(np.float32) for n in numel]
+                             for k in range(K)])
+    for t in range(4):
+        ls.ctx.ga_update(ls.plans[t % 2], 0.1, 0.9, 5e-4, 1.0, first_step=int(t == 0), always=True)
+        O.ga_update(ls.h_grads[t % 2], ls.h_w, ls.h_m, 0.1, 0.9, 5e-4, 1.0, t == 0, True)
+        ls.compare()
+        for k in range(1, K):
+            assert PU.to_host(ls.d_w[k][0]).tobytes() == PU.to_host(ls.d_w[0][0]).tobytes()
+    ls.close()
+
+
 # ================================================================= the five workloads, lock step
 
 @pytest.mark.parametrize("name,shrink,steps,compare_every", [

@@ -499,6 +499,73 @@ def test_average_bf16_mode():
         assert np.array_equal(copies[k][0], gc[0])
 
 
+# =============================================================== variant: gradient aggregation (Sec. III-C)
+
+def test_ga_identical_gradients_average_to_themselves_and_exact_mean():
+    g = rng(50).standard_normal(300).astype(np.float32)
+    for K in (1, 2, 3, 8):
+        gbar = O.average_grads([[g.copy()] for _ in range(K)], 0.37)[0]
+        assert gbar.tobytes() == (np.float32(0.37) * g).tobytes()
+    K = 5
+    gs = [[rng(51 + k).standard_normal(200).astype(np.float32)] for k in range(K)]
+    gbar = O.average_grads(gs)[0]
+    for j in range(200):
+        exact = sum(Fraction(float(gk[0][j])) for gk in gs) / K
+        ulp = Fraction(float(np.spacing(np.abs(gbar[j]))))
+        assert abs(Fraction(float(gbar[j])) - exact) <= ulp * Fraction(51, 100)
+    bits = [[O.f32_to_bf16(gk[0])] for gk in gs]
+    wide = [[(b[0].astype(np.uint32) << 16).view(np.float32).copy()] for b in bits]
+    assert O.average_grads(bits, 1.5)[0].tobytes() == O.average_grads(wide, 1.5)[0].tobytes()
+
+
+def test_ga_sync_keeps_replica_offsets_while_pa_removes_them():
+    # two replicas that differ by a constant, same momentum, no weight decay: a GA step moves both
+    # by the same amount (they stay apart, Sec. III-C), a PA step makes them identical
+    K, n = 2, 64
+    r = rng(52)
+    base = r.standard_normal(n).astype(np.float32)
+    grads = [[r.standard_normal(n).astype(np.float32)] for _ in range(K)]
+    m0 = r.standard_normal(n).astype(np.float32)
+    params = [[base.copy()], [base + np.float32(0.5)]]
+    mom = [[m0.copy()], [m0.copy()]]
+    O.ga_update(grads, params, mom, 0.1, 0.9, 0.0, sync=True)
+    assert mom[0][0].tobytes() == mom[1][0].tobytes()
+    np.testing.assert_allclose(params[1][0] - params[0][0], 0.5, rtol=0, atol=1e-6)
+    glob = [np.zeros(n, np.float32)]
+    O.average_params(params, glob)
+    assert params[0][0].tobytes() == params[1][0].tobytes()
+    # a local GA step (sync=False) is the plain per-worker update
+    p2, m2 = [[base.copy()]], [[m0.copy()]]
+    p3, m3 = [[base.copy()]], [[m0.copy()]]
+    O.ga_update([grads[0]], p2, m2, 0.1, 0.9, 1e-3, sync=False)
+    O.sgd_update(p3[0], m3[0], grads[0], 0.1, 0.9, 1e-3)
+    assert p2[0][0].tobytes() == p3[0][0].tobytes() and m2[0][0].tobytes() == m3[0][0].tobytes()
+
+
+def test_ga_equals_pa_when_every_step_synchronises_from_identical_start():
+    # Sec. III-C: with all workers starting from the same model and synchronising every step,
+    # gradient and parameter aggregation coincide (up to rounding): mean_k(mu*m_k + g_k) = mu*mean(m_k) + gbar
+    K, n = 4, 500
+    r = rng(53)
+    w0 = (r.standard_normal(n) * 0.05).astype(np.float32)
+    pa_w = [[w0.copy()] for _ in range(K)]
+    pa_m = [[np.zeros(n, np.float32)] for _ in range(K)]
+    ga_w = [[w0.copy()] for _ in range(K)]
+    ga_m = [[np.zeros(n, np.float32)] for _ in range(K)]
+    glob = [np.zeros(n, np.float32)]
+    for t in range(10):
+        grads = [[(r.standard_normal(n) * 1e-2).astype(np.float32)] for _ in range(K)]
+        for k in range(K):
+            O.sgd_update(pa_w[k], pa_m[k], grads[k], 0.1, 0.9, 5e-4, first=(t == 0))
+        O.average_params(pa_w, glob)
+        O.ga_update(grads, ga_w, ga_m, 0.1, 0.9, 5e-4, first=(t == 0), sync=True)
+        for k in range(1, K):
+            assert ga_w[k][0].tobytes() == ga_w[0][0].tobytes()       # GA from identical start stays identical
+        np.testing.assert_allclose(ga_w[0][0], pa_w[0][0], rtol=0, atol=2e-7)
+        np.testing.assert_allclose(ga_m[0][0], np.mean([m[0].astype(np.float64) for m in pa_m], axis=0),
+                                   rtol=0, atol=2e-8)
+
+
 # =============================================================== end to end, independent re-derivation
 
 def test_c1_decision_sequence_matches_independent_numpy_pandas_run():
