@@ -42,9 +42,11 @@ def parse_args():
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
-    ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga"],
+    ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga", "adam"],
                     help="pa: fused selsync_step (default, the headline); unfused: the three primitives in Alg. 1 "
-                         "order; ga: gradient-aggregation variant (selsync_step_ga)")
+                         "order; ga: gradient-aggregation variant (selsync_step_ga); adam: Adam as the local update "
+                         "(selsync_step_adam, 28 B per parameter)")
+    ap.add_argument("--window", type=int, default=0, help="EWMA window (default: the workload's, 25)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events in the timed loop (roofline.achieved becomes null)")
@@ -160,6 +162,8 @@ def main():
     wl = W.get(args.workload, shrink=args.shrink)
     K, P, T = wl.num_workers, wl.num_params, wl.num_tensors
     st = make_device_state(torch, wl, wl.seed)
+    if args.window > 0:
+        wl.window = args.window
     ctx = B.SelSync(K, wl.delta, wl.window)
     if args.chunk_elems or args.blocks_per_cu or args.nontemporal >= 0:
         ctx.set_tuning(args.chunk_elems, args.blocks_per_cu, args.nontemporal)
@@ -171,6 +175,10 @@ def main():
         else:
             plans.append(ctx.plan(st["grads"][slot], st["w"], st["m"], st["glob"]))
     info = plans[0].info()
+    if args.variant == "adam":
+        st["v"] = [[torch.zeros_like(x) for x in st["w"][k]] for k in range(K)]
+        for p in plans:
+            ctx.bind_second_moment(p, st["v"])
 
     total = args.warmup + args.steps
     sig = wl.sigmas(total) if total <= wl.steps else [float(wl.sigma(t)) for t in range(total)]
@@ -184,8 +192,10 @@ def main():
                 ctx.track_grad_change(plan, sig[t], blocking=False)
                 ctx.local_step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
                 ctx.aggregate_params(plan, always=False)
-            else:
+            elif args.variant == "ga":
                 ctx.step_ga(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
+            else:
+                ctx.step_adam(plan, 1e-4, 0.9, 0.999, 1e-8, 0.0, sig[t], step=t + 1)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -221,6 +231,8 @@ def main():
     if args.variant == "ga":
         # the decision must precede the update, so the gradients are read twice; no parameter exchange
         b_local, b_sync = b_local + K * (2 if wl.mixed_bf16 else 4) * P, 0
+    if args.variant == "adam":
+        b_local += K * 8 * P                 # second-moment buffer read and written
     total_bytes = args.steps * b_local + n_sync * b_sync
     eff_gbps = total_bytes / elapsed / 1e9
     ms_per_step = elapsed / args.steps * 1e3

@@ -94,6 +94,22 @@ typedef struct selsync_sgd {
                               -1: decide automatically (first local update since create/reset)        */
 } selsync_sgd;
 
+/* Hyper-parameters of the Adam variant of the local update (the AlexNet recipe of Sec. IV-A
+ * uses Adam with a fixed learning rate):
+ *   gh = grad_scale*g; gd = gh + weight_decay*w; m = b1*m + (1-b1)*gd; v = b2*v + ((1-b2)*gd)*gd;
+ *   w = w - (lr*(m/bc1)) / (sqrt(v/bc2) + eps),   bc1 = 1 - b1^t, bc2 = 1 - b2^t
+ * in fp32 with one rounding per operation and correctly rounded division / square root.
+ * The betas are doubles: 1-b and 1-b^t are formed in double and rounded once to fp32. */
+typedef struct selsync_adam {
+    double  beta1, beta2;  /* in [0, 1)                                                            */
+    float   lr;
+    float   eps;
+    float   weight_decay;  /* added to the gradient (L2 form)                                       */
+    float   grad_scale;
+    int64_t step;          /* 1-based step t of the bias corrections; <= 0: local updates since
+                              create/reset, plus one.  At t = 1 the moment buffers are taken as zero */
+} selsync_adam;
+
 /* Cumulative counters (LSSR is Eq. 4; max_delta is the extremum M of Sec. III-B over finite values). */
 typedef struct selsync_stats {
     int64_t steps_local;
@@ -234,6 +250,26 @@ int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan, int32_t m
 int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
                      int32_t blocking, double *norm_sq_out, double *delta_out,
                      int32_t *flags_out, int32_t *sync_out);
+
+/* ---- variant: Adam local update (Sec. IV-A, AlexNet recipe) ---------------------------------- */
+
+/*
+ * Bind second-moment buffers v[K] (fp32, same shapes as the momenta, which then serve as the
+ * first moment) to a plan that has gradients.  Caller-owned device memory; must not overlap
+ * any other buffer of the plan; a tensor whose momentum buffer is 16-byte aligned must have a
+ * 16-byte aligned second-moment buffer.  Waits for the device.
+ */
+int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const selsync_tensor_list *second_moment);
+
+/* Adam update of all K replicas in place (the local update of Alg. 1 line 9 with Adam). */
+int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream);
+
+/* One whole iteration with Adam as the local update: fused update + tracking pass over the
+ * gradients, tracker, predicated parameter aggregation (moment buffers are not averaged).
+ * Outputs as for selsync_track_grad_change. */
+int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
+                          int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                          int32_t *sync_out);
 
 /* ---- variant: gradient aggregation (Sec. III-C) ------------------------------------------ */
 

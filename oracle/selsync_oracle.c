@@ -165,6 +165,76 @@ void selsync_oracle_average_bf16(float *const *masters, uint16_t *const *copies,
     }
 }
 
+/* ------------------------------------------------------------------ variant: Adam local update */
+
+/*
+ * Adam (the optimiser of the AlexNet recipe in Sec. IV-A) as the local update of Alg. 1
+ * line 9, fp32, one rounding per operation, in this order:
+ *     gh = fl(grad_scale*g);  gd = fl(gh + fl(wd*w))
+ *     m  = fl(fl(b1*m) + fl(omb1*gd));   v = fl(fl(b2*v) + fl(fl(omb2*gd)*gd))
+ *     mh = fl(m/bc1);  vh = fl(v/bc2)
+ *     w  = fl(w - fl(fl(lr*mh) / fl(sqrt(vh) + eps)))
+ * omb1 = fl(1-b1), omb2 = fl(1-b2), bc1 = fl(1 - b1^t), bc2 = fl(1 - b2^t) are formed by the
+ * caller (in double, rounded to fp32) for step t = 1, 2, ...; at t = 1 the buffers are taken
+ * as zero whatever they hold.
+ */
+void selsync_oracle_adam_f32(float *w, float *m, float *v, const float *g, int64_t n, float lr, float b1, float b2,
+                             float omb1, float omb2, float eps, float wd, float grad_scale, float bc1, float bc2,
+                             int first)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = grad_scale * g[j];
+        float dec = wd * w[j];
+        float gd = gh + dec;
+        float mo = first ? 0.0f : m[j];
+        float vo = first ? 0.0f : v[j];
+        float t1 = b1 * mo;
+        float t2 = omb1 * gd;
+        float mn = t1 + t2;
+        float t3 = b2 * vo;
+        float t4 = omb2 * gd;
+        float t5 = t4 * gd;
+        float vn = t3 + t5;
+        float mh = mn / bc1;
+        float vh = vn / bc2;
+        float num = lr * mh;
+        float den = sqrtf(vh) + eps;
+        float q = num / den;
+        m[j] = mn;
+        v[j] = vn;
+        w[j] = w[j] - q;
+    }
+}
+
+void selsync_oracle_adam_bf16(float *master, float *m, float *v, const uint16_t *g, uint16_t *copy, int64_t n,
+                              float lr, float b1, float b2, float omb1, float omb2, float eps, float wd,
+                              float grad_scale, float bc1, float bc2, int first)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = grad_scale * selsync_oracle_bf16_to_f32(g[j]);
+        float dec = wd * master[j];
+        float gd = gh + dec;
+        float mo = first ? 0.0f : m[j];
+        float vo = first ? 0.0f : v[j];
+        float t1 = b1 * mo;
+        float t2 = omb1 * gd;
+        float mn = t1 + t2;
+        float t3 = b2 * vo;
+        float t4 = omb2 * gd;
+        float t5 = t4 * gd;
+        float vn = t3 + t5;
+        float mh = mn / bc1;
+        float vh = vn / bc2;
+        float num = lr * mh;
+        float den = sqrtf(vh) + eps;
+        float q = num / den;
+        m[j] = mn;
+        v[j] = vn;
+        master[j] = master[j] - q;
+        copy[j] = selsync_oracle_f32_to_bf16(master[j]);
+    }
+}
+
 /* ------------------------------------------------------------------ variant: gradient aggregation */
 
 /*

@@ -68,6 +68,10 @@ def lib() -> ctypes.CDLL:
                                                         ctypes.c_int64]
         L.selsync_oracle_sgd_mixed_f32grad.restype = None
         L.selsync_oracle_sgd_mixed_f32grad.argtypes = [f32p, f32p, f32p, u16p, ctypes.c_int64] + [ctypes.c_float] * 3 + [ctypes.c_int]
+        L.selsync_oracle_adam_f32.restype = None
+        L.selsync_oracle_adam_f32.argtypes = [f32p, f32p, f32p, f32p, ctypes.c_int64] + [ctypes.c_float] * 10 + [ctypes.c_int]
+        L.selsync_oracle_adam_bf16.restype = None
+        L.selsync_oracle_adam_bf16.argtypes = [f32p, f32p, f32p, u16p, u16p, ctypes.c_int64] + [ctypes.c_float] * 10 + [ctypes.c_int]
         L.selsync_oracle_tracker_new.restype = ctypes.c_void_p
         L.selsync_oracle_tracker_new.argtypes = [ctypes.c_int, ctypes.c_double]
         L.selsync_oracle_tracker_free.restype = None
@@ -170,6 +174,32 @@ def average_params(replicas: Sequence[Sequence[np.ndarray]], global_model: Seque
         else:
             cptrs = (u16p * K)(*[_u16(copies[k][t]) for k in range(K)])
             L.selsync_oracle_average_bf16(ptrs, cptrs, K, _f32(global_model[t]), _u16(global_copy[t]), n)
+
+
+# ---------------------------------------------------------------- variant: Adam local update
+
+def adam_constants(beta1: float, beta2: float, step: int):
+    """(omb1, omb2, bc1, bc2) as the fp32 values the update uses: 1-beta and the bias
+    corrections 1-beta^t of step t (1-based), formed in double and rounded once."""
+    b1, b2 = float(beta1), float(beta2)        # the betas are double-precision inputs
+    return (float(np.float32(1.0 - b1)), float(np.float32(1.0 - b2)),
+            float(np.float32(1.0 - b1 ** step)), float(np.float32(1.0 - b2 ** step)))
+
+
+def adam_update(params, m, v, grads, lr, beta1, beta2, eps, weight_decay, step: int, grad_scale: float = 1.0,
+                copies=None) -> None:
+    """In-place Adam update of one replica at 1-based step `step` (Sec. IV-A, AlexNet recipe)."""
+    L = lib()
+    omb1, omb2, bc1, bc2 = adam_constants(beta1, beta2, step)
+    for t in range(len(params)):
+        n = params[t].size
+        if copies is None:
+            L.selsync_oracle_adam_f32(_f32(params[t]), _f32(m[t]), _f32(v[t]), _f32(grads[t]), n, lr, beta1, beta2,
+                                      omb1, omb2, eps, weight_decay, grad_scale, bc1, bc2, int(step == 1))
+        else:
+            L.selsync_oracle_adam_bf16(_f32(params[t]), _f32(m[t]), _f32(v[t]), _u16(grads[t]), _u16(copies[t]), n,
+                                       lr, beta1, beta2, omb1, omb2, eps, weight_decay, grad_scale, bc1, bc2,
+                                       int(step == 1))
 
 
 # ---------------------------------------------------------------- variant: gradient aggregation

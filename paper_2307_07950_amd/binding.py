@@ -61,6 +61,12 @@ class selsync_sgd(ctypes.Structure):
                 ("grad_scale", ctypes.c_float), ("first_step", ctypes.c_int32)]
 
 
+class selsync_adam(ctypes.Structure):
+    _fields_ = [("beta1", ctypes.c_double), ("beta2", ctypes.c_double), ("lr", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("grad_scale", ctypes.c_float),
+                ("step", ctypes.c_int64)]
+
+
 class selsync_stats(ctypes.Structure):
     _fields_ = [("steps_local", ctypes.c_int64), ("steps_sync", ctypes.c_int64), ("lssr", ctypes.c_double),
                 ("max_delta", ctypes.c_double), ("nonfinite_steps", ctypes.c_int64)]
@@ -96,6 +102,9 @@ PROTOTYPES = {
     "selsync_local_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp]),
     "selsync_aggregate_params": (_i32, [_vp, _vp, _i32, _vp]),
     "selsync_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_plan_bind_second_moment": (_i32, [_vp, _tl]),
+    "selsync_local_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp]),
+    "selsync_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_ga_update": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _i32, _vp]),
     "selsync_step_ga": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_read_decision": (_i32, [_vp, _vp, _dp, _dp, _ip, _ip]),
@@ -283,6 +292,28 @@ class SelSync:
         n, d, f, s = self._outs()
         rc = self._check(selsync_step(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
                                       int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
+        return self._decision(rc, n, d, f, s) if blocking else None
+
+    # -- variant: Adam local update
+    def bind_second_moment(self, plan: Plan, second_moment):
+        if len(second_moment) != self.num_workers:
+            raise ValueError("expected %d lists" % self.num_workers)
+        arr, keep = _marshal_lists(second_moment)
+        self._check(selsync_plan_bind_second_moment(plan._h, arr))
+        plan._keep.append(keep)
+
+    def local_step_adam(self, plan: Plan, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                        weight_decay: float = 0.0, grad_scale: float = 1.0, step: int = 0, stream=None):
+        ad = selsync_adam(beta1, beta2, lr, eps, weight_decay, grad_scale, step)
+        self._check(selsync_local_step_adam(self._h, plan._h, ctypes.byref(ad), _vp(_stream_handle(stream))))
+
+    def step_adam(self, plan: Plan, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                  weight_decay: float = 0.0, grad_scale: float = 1.0, step: int = 0, blocking: bool = False,
+                  stream=None):
+        ad = selsync_adam(beta1, beta2, lr, eps, weight_decay, grad_scale, step)
+        n, d, f, s = self._outs()
+        rc = self._check(selsync_step_adam(self._h, plan._h, ctypes.byref(ad), _vp(_stream_handle(stream)),
+                                           int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
         return self._decision(rc, n, d, f, s) if blocking else None
 
     # -- variant: gradient aggregation

@@ -15,6 +15,8 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # one rounding per written fp32 operation: no multiply-add contraction anywhere
     "-ffp-contract=off",
+    # IEEE-correct fp32 division and square root (the Adam variant relies on them)
+    "-fhip-fp32-correctly-rounded-divide-sqrt",
     # do not let the compiler form packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",

@@ -30,6 +30,12 @@ struct ProfRec {
     hipEvent_t start, stop;
 };
 
+// Address range of one bound tensor (for the overlap check).
+struct Interval {
+    uintptr_t lo, hi;
+    bool written;
+};
+
 }  // namespace
 
 struct selsync_ctx {
@@ -77,6 +83,10 @@ struct selsync_plan {
     int32_t *d_tensor_chunk_begin = nullptr;
     double *d_tensor_norms = nullptr;
     bool partials_valid = false;     // a tracking pass has been enqueued on this plan
+    std::vector<TensorRec> h_recs;   // host copy (re-uploaded when second-moment buffers are bound)
+    std::vector<int64_t> numel;      // per-tensor element counts
+    std::vector<Interval> ivals;     // every bound buffer (checked again when more buffers are bound)
+    bool has_second_moment = false;
     AggChunkRec *d_agg_chunks = nullptr;
     AggTables agg{};
     LaunchCfg upd_cfg{1, 1, 0};
@@ -141,11 +151,6 @@ struct ProfScope {
         if (rec)
             (void)hipEventRecord(rec->stop, s);
     }
-};
-
-struct Interval {
-    uintptr_t lo, hi;
-    bool written;
 };
 
 // Validate one [K] array of lists against the reference shape; collect intervals.
@@ -655,6 +660,9 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->P = P;
     plan->mixed = mixed;
     plan->has_grads = grads != nullptr;
+    plan->h_recs = recs;
+    plan->numel = numel;
+    plan->ivals = ivals;
     plan->n_upd_chunks = (int)chunks.size();
     plan->n_agg_chunks = (int)agg_chunks.size();
 
@@ -873,6 +881,118 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
         ProfScope p(ctx, 0, s);
         HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
                                    plan->d_partials, a, plan->upd_cfg, s));
+    }
+    ctx->local_steps += 1;
+    if ((rc = enqueue_track(ctx, plan, s)))
+        return rc;
+    {
+        ProfScope p(ctx, 2, s);
+        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+                                      &ctx->td.out->sync, 0, plan->agg_cfg, s));
+    }
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
+// =============================================================================== variant: Adam local update
+
+namespace {
+int32_t resolve_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *ad, AdamArgs *out)
+{
+    if (!ad)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "adam is NULL");
+    if (!plan->has_second_moment)
+        return fail(ctx, SELSYNC_ERR_STATE, "no second-moment buffers bound (selsync_plan_bind_second_moment)");
+    if (!(ad->beta1 >= 0.0 && ad->beta1 < 1.0) || !(ad->beta2 >= 0.0 && ad->beta2 < 1.0))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "betas must be in [0, 1)");
+    const int64_t t = ad->step > 0 ? ad->step : ctx->local_steps + 1;
+    out->lr = ad->lr;
+    out->b1 = (float)ad->beta1;
+    out->b2 = (float)ad->beta2;
+    out->omb1 = (float)(1.0 - ad->beta1);
+    out->omb2 = (float)(1.0 - ad->beta2);
+    out->eps = ad->eps;
+    out->wd = ad->weight_decay;
+    out->gs = ad->grad_scale;
+    out->bc1 = (float)(1.0 - std::pow(ad->beta1, (double)t));
+    out->bc2 = (float)(1.0 - std::pow(ad->beta2, (double)t));
+    out->first = t == 1 ? 1 : 0;
+    return SELSYNC_OK;
+}
+}  // namespace
+
+extern "C" int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const selsync_tensor_list *v)
+{
+    if (!plan || !plan->ctx)
+        return SELSYNC_ERR_INVALID_ARG;
+    selsync_ctx *ctx = plan->ctx;
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    if (!v)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "second-moment lists are NULL");
+    std::vector<Interval> ivals;
+    if ((rc = check_lists(ctx, "second_moment", v, plan->K, plan->T, plan->numel, SELSYNC_F32, true, ivals)))
+        return rc;
+    for (int k = 0; k < plan->K; ++k)
+        for (int t = 0; t < plan->T; ++t) {
+            TensorRec &r = plan->h_recs[(size_t)k * plan->T + t];
+            float *vp = static_cast<float *>(v[k].tensors[t].data);
+            if (plan->numel[t] > 0 && aligned16(r.m) && !aligned16(vp))
+                return fail(ctx, SELSYNC_ERR_INVALID_ARG,
+                            "second_moment[%d] tensor %d must be 16-byte aligned because its momentum tensor is", k, t);
+        }
+    // the new buffers are written: together with everything already bound they may not overlap
+    std::vector<Interval> all = plan->ivals;
+    all.insert(all.end(), ivals.begin(), ivals.end());
+    if ((rc = check_overlap(ctx, all)))
+        return rc;
+    for (int k = 0; k < plan->K; ++k)
+        for (int t = 0; t < plan->T; ++t)
+            plan->h_recs[(size_t)k * plan->T + t].v = static_cast<float *>(v[k].tensors[t].data);
+    (void)hipDeviceSynchronize();
+    if (!plan->h_recs.empty())
+        HIP_TRY(ctx, hipMemcpy(plan->d_recs, plan->h_recs.data(), plan->h_recs.size() * sizeof(TensorRec),
+                               hipMemcpyHostToDevice));
+    plan->has_second_moment = true;      // plan->ivals stays the base set, so buffers can be re-bound
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam,
+                                           void *stream)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    AdamArgs a;
+    if ((rc = resolve_adam(ctx, plan, adam, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
+                                        plan->d_partials, a, plan->upd_cfg, s));
+    }
+    ctx->local_steps += 1;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
+                                     int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                                     int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    AdamArgs a;
+    if ((rc = resolve_adam(ctx, plan, adam, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream_adam(true, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
+                                        plan->d_partials, a, plan->upd_cfg, s));
     }
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))

@@ -16,6 +16,7 @@ struct TensorRec {
     float *w;        // fp32 parameter (mixed mode: fp32 master)
     float *m;        // fp32 momentum buffer
     uint16_t *lowp;  // bf16 working copy (mixed mode only)
+    float *v;        // fp32 second-moment buffer (Adam variant only, else null)
 };
 
 // One unit of work of the multi-tensor streaming kernel: `n` consecutive elements
@@ -78,6 +79,11 @@ struct TrackerDev {
     int32_t window;
 };
 
+struct AdamArgs {
+    float lr, b1, b2, omb1, omb2, eps, wd, gs, bc1, bc2;
+    int32_t first;   // step 1: moment buffers are taken as zero
+};
+
 struct SgdArgs {
     float lr, mu, wd, gs;
     int32_t first;
@@ -108,6 +114,10 @@ hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, con
 
 // Sums partials[segs[j].x .. segs[j].y) into seg_sums[j], one workgroup per segment.
 hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s);
+
+// Adam variant of the streaming kernel: update (+ norm partials when with_norm).
+hipError_t launch_stream_adam(bool with_norm, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
+                              double *partials, const AdamArgs &a, const LaunchCfg &cfg, hipStream_t s);
 
 hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s);
 

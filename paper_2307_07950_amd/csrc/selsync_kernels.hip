@@ -67,6 +67,16 @@ __device__ __forceinline__ uint32_t bf16_bits(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+// Four bf16 values in two dwords -> four fp32 values (exact).
+__device__ __forceinline__ f32x4 widen4(u32x2 v)
+{
+    f32x4 g;
+    g.x = bf16_lo(v.x);
+    g.y = bf16_hi(v.x);
+    g.z = bf16_lo(v.y);
+    g.w = bf16_hi(v.y);
+    return g;
+}
 
 // Workgroup -> chunk mapping.  Workgroups are handed to the 8 XCDs round-robin by
 // linear id, and each XCD has its own L2.  With xcd_per > 0 workgroup v takes chunk
@@ -314,6 +324,149 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
                 }
                 __syncthreads();
             }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- k_stream_adam
+
+// One element of the Adam variant (optimiser of the AlexNet recipe, Sec. IV-A), fp32, one
+// rounding per operation; division and square root are the correctly rounded ones:
+//   gh = gs*g; gd = gh + wd*w; m = b1*m + omb1*gd; v = b2*v + (omb2*gd)*gd;
+//   w = w - (lr*(m/bc1)) / (sqrt(v/bc2) + eps)
+template <bool NORM>
+__device__ __forceinline__ void elem_adam(float g, float &w, float &m, float &v, const AdamArgs &a, double &acc)
+{
+    const float gh = a.gs * g;
+    if (NORM)
+        acc = __builtin_fma((double)gh, (double)gh, acc);
+    const float dec = a.wd * w;
+    const float gd = gh + dec;
+    const float t1 = a.b1 * m;
+    const float t2 = a.omb1 * gd;
+    const float mn = t1 + t2;
+    const float t3 = a.b2 * v;
+    const float t4 = a.omb2 * gd;
+    const float t5 = t4 * gd;
+    const float vn = t3 + t5;
+    const float mh = mn / a.bc1;
+    const float vh = vn / a.bc2;
+    const float num = a.lr * mh;
+    const float den = __builtin_sqrtf(vh) + a.eps;
+    const float q = num / den;
+    m = mn;
+    v = vn;
+    w = w - q;
+}
+
+template <bool NORM>
+__device__ __forceinline__ void elem4_adam(const f32x4 &g, f32x4 &w, f32x4 &m, f32x4 &v, const AdamArgs &a,
+                                           double &acc)
+{
+    float w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
+    float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
+    float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
+    elem_adam<NORM>(g.x, w0, m0, v0, a, acc);
+    elem_adam<NORM>(g.y, w1, m1, v1, a, acc);
+    elem_adam<NORM>(g.z, w2, m2, v2, a, acc);
+    elem_adam<NORM>(g.w, w3, m3, v3, a, acc);
+    w.x = w0; w.y = w1; w.z = w2; w.w = w3;
+    m.x = m0; m.y = m1; m.z = m2; m.w = m3;
+    v.x = v0; v.y = v1; v.z = v2; v.w = v3;
+}
+
+// Same chunk table, same one-wave workgroup shape as k_stream; four streams read (g, w, m, v),
+// three written (w, m, v) plus the bf16 copy in mixed mode: 28 algorithmic bytes per element.
+template <int BLOCK, int U, bool MIXED, bool NORM>
+__global__ __launch_bounds__(BLOCK) void k_stream_adam(const TensorRec *__restrict__ recs,
+                                                       const ChunkRec *__restrict__ chunks, int nchunks,
+                                                       double *__restrict__ partials, AdamArgs a, int xcd_per)
+{
+    static_assert(BLOCK == 64, "single-wave workgroups only");
+    const uint32_t tid = threadIdx.x;
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    for (int vv = blockIdx.x; vv < vtotal; vv += gridDim.x) {
+        const int c = chunk_of_workgroup(vv, xcd_per);
+        if (c >= nchunks)
+            continue;
+        const ChunkRec ch = chunks[c];
+        const TensorRec r = recs[ch.rec];
+        const uint32_t n = ch.n_flags & kChunkCountMask;
+        double acc = 0.0;
+        uint32_t done = 0;
+        if (ch.n_flags & kChunkAligned) {
+            const uint32_t nvec = n / 4;
+            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + ch.off);
+            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + ch.off);
+            SELSYNC_GLOBAL f32x4 *v4 = as_global<f32x4>(r.v + ch.off);
+            const SELSYNC_GLOBAL f32x4 *g4 = as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + ch.off);
+            const SELSYNC_GLOBAL u32x2 *gb4 = as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
+            SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + ch.off);
+            for (uint32_t base = 0; base < nvec; base += BLOCK * U) {
+                f32x4 gv[U], wv[U], mv[U], vv4[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t i = base + u * BLOCK + tid;
+                    gv[u] = 0.f;
+                    wv[u] = 0.f;
+                    mv[u] = 0.f;
+                    vv4[u] = 0.f;
+                    if (i < nvec) {
+                        if (MIXED)
+                            gv[u] = widen4(ld<true>(gb4 + i));
+                        else
+                            gv[u] = ld<true>(g4 + i);
+                        wv[u] = ld<true>(w4 + i);
+                        if (!a.first) {
+                            mv[u] = ld<true>(m4 + i);
+                            vv4[u] = ld<true>(v4 + i);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t i = base + u * BLOCK + tid;
+                    if (i < nvec) {
+                        elem4_adam<NORM>(gv[u], wv[u], mv[u], vv4[u], a, acc);
+                        st<true>(w4 + i, wv[u]);
+                        st<true>(m4 + i, mv[u]);
+                        st<true>(v4 + i, vv4[u]);
+                        if (MIXED) {
+                            u32x2 cv;
+                            cv.x = bf16_pack(wv[u].x, wv[u].y);
+                            cv.y = bf16_pack(wv[u].z, wv[u].w);
+                            st<true>(c4 + i, cv);
+                        }
+                    }
+                }
+            }
+            done = nvec * 4;
+        }
+        {
+            const SELSYNC_GLOBAL float *gf = as_global<const float>(r.g);
+            const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(r.g);
+            SELSYNC_GLOBAL float *wp = as_global<float>(r.w);
+            SELSYNC_GLOBAL float *mp = as_global<float>(r.m);
+            SELSYNC_GLOBAL float *vp = as_global<float>(r.v);
+            SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(r.lowp);
+            for (uint32_t i = done + tid; i < n; i += BLOCK) {
+                const uint64_t e = ch.off + i;
+                const float g = MIXED ? __uint_as_float(((uint32_t)gh[e]) << 16) : gf[e];
+                float w = wp[e];
+                float m = a.first ? 0.f : mp[e];
+                float v = a.first ? 0.f : vp[e];
+                elem_adam<NORM>(g, w, m, v, a, acc);
+                wp[e] = w;
+                mp[e] = m;
+                vp[e] = v;
+                if (MIXED)
+                    cp[e] = (uint16_t)bf16_bits(w);
+            }
+        }
+        if (NORM) {
+            const double s = wave_sum(acc);
+            if (tid == 0)
+                partials[c] = s;
         }
     }
 }
@@ -722,16 +875,6 @@ __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, dou
     return r;
 }
 
-__device__ __forceinline__ f32x4 widen4(u32x2 v)
-{
-    f32x4 g;
-    g.x = bf16_lo(v.x);
-    g.y = bf16_hi(v.x);
-    g.z = bf16_lo(v.y);
-    g.w = bf16_hi(v.y);
-    return g;
-}
-
 // Update of all K workers under gradient aggregation.  One workgroup walks one chunk of
 // one tensor across the K workers: with the decision "sync" the mean gradient is applied
 // to every worker's own (w, m); otherwise each worker applies its own gradient (the plain
@@ -947,6 +1090,32 @@ hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, con
                                : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s);
     return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s)
                            : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s);
+}
+
+hipError_t launch_stream_adam(bool with_norm, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
+                              double *partials, const AdamArgs &a, const LaunchCfg &cfg, hipStream_t s)
+{
+    if (nchunks <= 0)
+        return hipSuccess;
+    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
+    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
+    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
+#define SELSYNC_ADAM(MX, NM) \
+    hipLaunchKernelGGL((k_stream_adam<64, 2, MX, NM>), dim3(grid), dim3(64), 0, s, recs, chunks, nchunks, partials, a, \
+                       xcd_per)
+    if (mixed) {
+        if (with_norm)
+            SELSYNC_ADAM(true, true);
+        else
+            SELSYNC_ADAM(true, false);
+    } else {
+        if (with_norm)
+            SELSYNC_ADAM(false, true);
+        else
+            SELSYNC_ADAM(false, false);
+    }
+#undef SELSYNC_ADAM
+    return hipGetLastError();
 }
 
 hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s)

@@ -179,6 +179,42 @@ class LockStep:
             self.compare(after_sync=bool(sync))
         return dec, rec
 
+    def enable_adam(self):
+        """Allocate second-moment buffers on both sides and bind them to every plan."""
+        self.h_v = [[np.zeros_like(a) for a in self.h_w[k]] for k in range(self.K)]
+        self.d_v = [[to_dev(a, self.misalign) for a in self.h_v[k]] for k in range(self.K)]
+        for plan in self.plans.values():
+            self.ctx.bind_second_moment(plan, self.d_v)
+
+    def step_adam(self, slot: int, lr: float, b1: float, b2: float, eps: float, wd: float, gs: float = 1.0,
+                  fused: bool = True):
+        """One iteration with Adam as the local update on both sides (parameter aggregation on sync)."""
+        plan = self.plans[slot]
+        t = self.steps_done + 1
+        if fused:
+            dec = self.ctx.step_adam(plan, lr, b1, b2, eps, wd, gs, step=t, blocking=True)
+        else:
+            dec = self.ctx.track_grad_change(plan, gs, blocking=True)
+            self.ctx.local_step_adam(plan, lr, b1, b2, eps, wd, gs, step=t)
+            self.ctx.aggregate_params(plan, always=False)
+        g = self.h_grads[slot]
+        rec = self.oracle.track(g, gs)
+        for k in range(self.K):
+            O.adam_update(self.h_w[k], self.h_m[k], self.h_v[k], g[k], lr, b1, b2, eps, wd, t, gs,
+                          None if not self.mixed else self.h_c[k])
+        sync = self._check_decision(dec, rec)
+        if sync:
+            self._pre_scale = [np.max(np.abs(np.stack([self.h_w[k][i] for k in range(self.K)])), axis=0)
+                               .astype(np.float64) for i in range(len(self.numel))]
+            O.average_params(self.h_w, self.h_glob, self.h_c, self.h_gc)
+        self.steps_done += 1
+        self.compare(after_sync=bool(sync))
+        for k in range(self.K):
+            for i in range(len(self.numel)):
+                self.worst_ulp = max(self.worst_ulp, assert_update_close(to_host(self.d_v[k][i]), self.h_v[k][i],
+                                                                         "second moment[%d][%d]" % (k, i)))
+        return dec, rec
+
     def step_ga(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True):
         """One iteration under gradient aggregation (Sec. III-C) on both sides."""
         plan = self.plans[slot]

@@ -399,6 +399,58 @@ def test_tracker_state_checkpoint_and_resume(B):
     ls.close()
 
 
+# ================================================================= variant: Adam local update
+
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_adam_variant_matches_oracle(B, mixed, misalign):
+    numel = [70001, 5, 4096, 0, 1023]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=21)
+    r = rng(140)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    with pytest.raises(B.SelSyncError) as e:                 # Adam needs its second-moment buffers
+        ls.ctx.local_step_adam(ls.plans[0], 1e-3)
+    assert e.value.status == B.SELSYNC_ERR_STATE
+    ls.enable_adam()
+    syncs = 0
+    for t in range(9):
+        dec, rec = ls.step_adam([0, 1, 2, 2, 0, 1, 1, 2, 0][t], 1e-3, 0.9, 0.999, 1e-8, [0.0, 1e-2][t % 2],
+                                [1.0, 0.7][t % 2], fused=(t % 3 != 1))
+        syncs += rec.sync
+    assert 0 < syncs < 9
+    assert ls.worst_ulp == 0          # same rounding sequence, correctly rounded divide / sqrt on both sides
+    ls.close()
+
+
+def test_adam_bind_validation(B):
+    K = 2
+    ctx = B.SelSync(K, 0.3)
+    mk = lambda n: torch.zeros(n, dtype=torch.float32, device="cuda")
+    g, p, m, glob = [[mk(100)] for _ in range(K)], [[mk(100)] for _ in range(K)], [[mk(100)] for _ in range(K)], [mk(100)]
+    plan = ctx.plan(g, p, m, glob)
+    def status(fn):
+        with pytest.raises(B.SelSyncError) as e:
+            fn()
+        return e.value.status
+    assert status(lambda: ctx.bind_second_moment(plan, [[mk(99)], [mk(100)]])) == B.SELSYNC_ERR_SHAPE_MISMATCH
+    assert status(lambda: ctx.bind_second_moment(plan, m)) == B.SELSYNC_ERR_INVALID_ARG          # overlaps momenta
+    v = [[mk(100)] for _ in range(K)]
+    assert status(lambda: ctx.bind_second_moment(plan, [v[0], v[0]])) == B.SELSYNC_ERR_INVALID_ARG
+    ctx.bind_second_moment(plan, v)
+    ctx.bind_second_moment(plan, v)                                                              # re-binding is fine
+    assert status(lambda: ctx.local_step_adam(plan, 1e-3, beta1=1.0)) == B.SELSYNC_ERR_INVALID_ARG
+    ctx.local_step_adam(plan, 1e-3)
+    agg_only = ctx.plan(None, p, None, glob)
+    assert status(lambda: ctx.bind_second_moment(agg_only, v)) == B.SELSYNC_ERR_STATE
+    ctx.close()
+
+
 # ================================================================= variant: gradient aggregation
 
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 8])

@@ -499,6 +499,90 @@ def test_average_bf16_mode():
         assert np.array_equal(copies[k][0], gc[0])
 
 
+# =============================================================== variant: Adam local update (Sec. IV-A recipe)
+
+def test_adam_first_step_is_lr_times_sign_of_gradient():
+    # t = 1: m = (1-b1) g, v = (1-b2) g^2, bias corrections cancel them: w -= lr * g / (|g| + eps)
+    g = np.array([0.5, -2.0, 1e-3, -7.25], np.float32)
+    w = np.zeros(4, np.float32)
+    m = np.full(4, 9.0, np.float32)           # stale buffers must be ignored at t = 1
+    v = np.full(4, 9.0, np.float32)
+    O.adam_update([w], [m], [v], [g], 1e-2, 0.9, 0.999, 1e-8, 0.0, step=1)
+    np.testing.assert_allclose(w, -1e-2 * np.sign(g), rtol=1e-5)
+    np.testing.assert_allclose(m, 0.1 * g, rtol=1e-6)
+    np.testing.assert_allclose(v, 0.001 * g.astype(np.float64) ** 2, rtol=1e-6)
+
+
+def test_adam_lr_zero_is_noop_and_zero_gradient_decays_moments():
+    r = rng(60)
+    w = r.standard_normal(100).astype(np.float32)
+    m = r.standard_normal(100).astype(np.float32)
+    v = np.abs(r.standard_normal(100)).astype(np.float32)
+    g = r.standard_normal(100).astype(np.float32)
+    w0 = w.copy()
+    O.adam_update([w], [m], [v], [g], 0.0, 0.9, 0.999, 1e-8, 0.0, step=5)
+    assert w.tobytes() == w0.tobytes()
+    m1, v1 = m.copy(), v.copy()
+    O.adam_update([w], [m], [v], [np.zeros(100, np.float32)], 0.0, 0.5, 0.25, 1e-8, 0.0, step=6)
+    assert m.tobytes() == (np.float32(0.5) * m1).tobytes() and v.tobytes() == (np.float32(0.25) * v1).tobytes()
+
+
+def test_adam_matches_torch_optim_adam_over_steps():
+    torch = pytest.importorskip("torch")
+    r = rng(61)
+    n, lr, b1, b2, eps = 800, 1e-4, 0.9, 0.999, 1e-8
+    w = (r.standard_normal(n) * 0.05).astype(np.float32)
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.Adam([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=0.0)
+    for t in range(1, 9):
+        g = (r.standard_normal(n) * 1e-2).astype(np.float32)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        O.adam_update([w], [m], [v], [g], lr, b1, b2, eps, 0.0, step=t)
+        # the library orders the arithmetic differently (sqrt(v)/sqrt(bc2), step_size = lr/bc1): agree to ~1e-6 of a step
+        np.testing.assert_allclose(w, p.detach().numpy(), rtol=0, atol=lr * 2e-5 + 1.5e-8)   # + ~2 ulp of w
+        np.testing.assert_allclose(m, opt.state[p]["exp_avg"].numpy(), rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(v, opt.state[p]["exp_avg_sq"].numpy(), rtol=2e-6, atol=1e-13)
+    # weight decay is added to the gradient (L2 form), as in the library
+    w2 = w.copy(); m2 = m.copy(); v2 = v.copy()
+    p2 = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt2 = torch.optim.Adam([p2], lr=lr, betas=(b1, b2), eps=eps, weight_decay=0.1)
+    g = (r.standard_normal(n) * 1e-2).astype(np.float32)
+    p2.grad = torch.from_numpy(g.copy())
+    opt2.step()
+    O.adam_update([w2], [np.zeros(n, np.float32)], [np.zeros(n, np.float32)], [g], lr, b1, b2, eps, 0.1, step=1)
+    np.testing.assert_allclose(w2, p2.detach().numpy(), rtol=0, atol=lr * 2e-5 + 1.5e-8)
+
+
+def test_adam_fp64_recomputation_and_bf16_mode():
+    r = rng(62)
+    n = 500
+    w = r.standard_normal(n).astype(np.float32)
+    m = (r.standard_normal(n) * 1e-2).astype(np.float32)
+    v = (np.abs(r.standard_normal(n)) * 1e-4).astype(np.float32)
+    g = (r.standard_normal(n) * 1e-2).astype(np.float32)
+    lr, b1, b2, eps, wd, gs, t = 1e-3, 0.9, 0.999, 1e-8, 1e-2, 0.7, 4
+    gd = gs * g.astype(np.float64) + wd * w.astype(np.float64)
+    m64 = b1 * m + (1 - b1) * gd
+    v64 = b2 * v + (1 - b2) * gd * gd
+    w64 = w - lr * (m64 / (1 - b1 ** t)) / (np.sqrt(v64 / (1 - b2 ** t)) + eps)
+    gbits = O.f32_to_bf16(g)
+    gwide = (gbits.astype(np.uint32) << 16).view(np.float32).copy()
+    wa, ma, va = w.copy(), m.copy(), v.copy()
+    O.adam_update([wa], [ma], [va], [g], lr, b1, b2, eps, wd, step=t, grad_scale=gs)
+    np.testing.assert_allclose(wa, w64, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(ma, m64, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(va, v64, rtol=2e-6, atol=1e-12)
+    wb, mb, vb, cb = w.copy(), m.copy(), v.copy(), np.zeros(n, np.uint16)
+    wc, mc, vc = w.copy(), m.copy(), v.copy()
+    O.adam_update([wb], [mb], [vb], [gbits], lr, b1, b2, eps, wd, step=t, grad_scale=gs, copies=[cb])
+    O.adam_update([wc], [mc], [vc], [gwide], lr, b1, b2, eps, wd, step=t, grad_scale=gs)
+    assert wb.tobytes() == wc.tobytes() and mb.tobytes() == mc.tobytes() and vb.tobytes() == vc.tobytes()
+    assert np.array_equal(cb, O.f32_to_bf16(wb))
+
+
 # =============================================================== variant: gradient aggregation (Sec. III-C)
 
 def test_ga_identical_gradients_average_to_themselves_and_exact_mean():
