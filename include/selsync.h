@@ -291,6 +291,25 @@ int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd 
                         int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                         int32_t *sync_out);
 
+/* ---- data partitioning (Sec. III-D; the step before the hot path, Alg. 1 line 6) ------------ */
+
+/*
+ * Reading order of worker `worker` over `num_samples` samples split into num_workers
+ * contiguous chunks DP0..DP(N-1) (the first num_samples % N chunks hold one sample more).
+ *   scheme 0, default partitioning (DefDP): only the worker's own chunk, in order;
+ *   scheme 1, SelSync partitioning (SelDP): all chunks as a circular queue whose head is
+ *             rotated to the worker's own chunk: DPn, DP(n+1), ..., DP(n-1).
+ * Writes min(*count, capacity) sample indices to `out` (HOST int64 array, may be NULL to only
+ * query) and the length of the order to *count.  Pure host code, no GPU needed.
+ */
+int32_t selsync_partition_order(int64_t num_samples, int32_t num_workers, int32_t worker, int32_t scheme,
+                                int64_t capacity, int64_t *out, int64_t *count);
+
+/* The same order written into a DEVICE int64 array by a kernel on `stream` (for data pipelines
+ * that gather samples on the GPU).  *count is a HOST output. */
+int32_t selsync_partition_order_device(int64_t num_samples, int32_t num_workers, int32_t worker, int32_t scheme,
+                                       int64_t capacity, int64_t *out_device, int64_t *count, void *stream);
+
 /* ---- observability ---------------------------------------------------------------- */
 
 /* Blocking fetch of the last step's device-side results (same outputs as tracking). */

@@ -276,6 +276,35 @@ def flag(delta_g: float, threshold: float) -> int:
     return lib().selsync_oracle_flag(delta_g, threshold)
 
 
+# ---------------------------------------------------------------- data partitioning (Sec. III-D)
+
+def partition_chunks(num_samples: int, num_workers: int):
+    """Split sample indices 0..D-1 into N contiguous chunks DP0..DP(N-1) of (near-)equal size:
+    the first D mod N chunks hold one sample more."""
+    base, rem = divmod(num_samples, num_workers)
+    chunks, start = [], 0
+    for c in range(num_workers):
+        size = base + (1 if c < rem else 0)
+        chunks.append(list(range(start, start + size)))
+        start += size
+    return chunks
+
+
+def defdp_order(num_samples: int, num_workers: int, worker: int):
+    """Default partitioning: worker n only ever sees its own chunk DPn."""
+    return partition_chunks(num_samples, num_workers)[worker]
+
+
+def seldp_order(num_samples: int, num_workers: int, worker: int):
+    """SelSync partitioning: every worker sees ALL chunks, as a circular queue whose head is
+    rotated to the worker's own chunk: worker n reads DPn, DP(n+1), ..., DP(n-1)."""
+    chunks = partition_chunks(num_samples, num_workers)
+    order = []
+    for j in range(num_workers):
+        order.extend(chunks[(worker + j) % num_workers])
+    return order
+
+
 # ---------------------------------------------------------------- one whole step
 
 @dataclass

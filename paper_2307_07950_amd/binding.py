@@ -107,6 +107,10 @@ PROTOTYPES = {
     "selsync_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_ga_update": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _i32, _vp]),
     "selsync_step_ga": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_partition_order": (_i32, [ctypes.c_int64, _i32, _i32, _i32, ctypes.c_int64,
+                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
+    "selsync_partition_order_device": (_i32, [ctypes.c_int64, _i32, _i32, _i32, ctypes.c_int64, _vp,
+                                              ctypes.POINTER(ctypes.c_int64), _vp]),
     "selsync_read_decision": (_i32, [_vp, _vp, _dp, _dp, _ip, _ip]),
     "selsync_read_tensor_norms": (_i32, [_vp, _vp, _vp, _dp]),
     "selsync_get_stats": (_i32, [_vp, _vp, ctypes.POINTER(selsync_stats)]),
@@ -177,6 +181,34 @@ def _marshal_lists(lists: Optional[Sequence[Sequence[torch.Tensor]]]):
         keep.append(list(tl))
     keep.append(arr)
     return arr, keep
+
+
+def partition_order(num_samples: int, num_workers: int, worker: int, seldp: bool = True) -> List[int]:
+    """Host-side reading order of one worker (DefDP or SelDP, Sec. III-D)."""
+    n = ctypes.c_int64()
+    rc = selsync_partition_order(num_samples, num_workers, worker, int(seldp), 0, None, ctypes.byref(n))
+    if rc != SELSYNC_OK:
+        raise SelSyncError(rc, "selsync_partition_order")
+    out = (ctypes.c_int64 * max(1, n.value))()
+    rc = selsync_partition_order(num_samples, num_workers, worker, int(seldp), n.value, out, ctypes.byref(n))
+    if rc != SELSYNC_OK:
+        raise SelSyncError(rc, "selsync_partition_order")
+    return list(out)[:n.value]
+
+
+def partition_order_device(num_samples: int, num_workers: int, worker: int, seldp: bool = True, stream=None):
+    """The same order as an int64 CUDA tensor, produced by a kernel."""
+    n = ctypes.c_int64()
+    rc = selsync_partition_order(num_samples, num_workers, worker, int(seldp), 0, None, ctypes.byref(n))
+    if rc != SELSYNC_OK:
+        raise SelSyncError(rc, "selsync_partition_order")
+    out = torch.empty(n.value, dtype=torch.int64, device="cuda")
+    rc = selsync_partition_order_device(num_samples, num_workers, worker, int(seldp), n.value,
+                                        _vp(out.data_ptr() if n.value else None), ctypes.byref(n),
+                                        _vp(_stream_handle(stream)))
+    if rc != SELSYNC_OK:
+        raise SelSyncError(rc, "selsync_partition_order_device")
+    return out
 
 
 class Plan:

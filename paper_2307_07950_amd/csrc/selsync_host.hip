@@ -895,6 +895,61 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
     return SELSYNC_OK;
 }
 
+// =============================================================================== data partitioning (Sec. III-D)
+
+namespace {
+int32_t partition_count(int64_t D, int32_t N, int32_t n, int32_t scheme, int64_t *count)
+{
+    if (D < 0 || N < 1 || n < 0 || n >= N || (scheme != 0 && scheme != 1) || !count)
+        return SELSYNC_ERR_INVALID_ARG;
+    *count = scheme == 1 ? D : chunk_start(D, N, (int64_t)n + 1) - chunk_start(D, N, n);
+    return SELSYNC_OK;
+}
+}  // namespace
+
+extern "C" int32_t selsync_partition_order(int64_t num_samples, int32_t num_workers, int32_t worker, int32_t scheme,
+                                           int64_t capacity, int64_t *out, int64_t *count)
+{
+    if (!out && !count)
+        return SELSYNC_ERR_INVALID_ARG;
+    int64_t c = 0;
+    int32_t rc = partition_count(num_samples, num_workers, worker, scheme, &c);
+    if (rc)
+        return rc;
+    if (count)
+        *count = c;
+    if (out) {
+        const int64_t lim = c < capacity ? c : capacity;
+        for (int64_t p = 0; p < lim; ++p)
+            out[p] = partition_index(num_samples, num_workers, worker, scheme, p);
+    }
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_partition_order_device(int64_t num_samples, int32_t num_workers, int32_t worker,
+                                                  int32_t scheme, int64_t capacity, int64_t *out_device,
+                                                  int64_t *count, void *stream)
+{
+    int64_t c = 0;
+    int32_t rc = partition_count(num_samples, num_workers, worker, scheme, &c);
+    if (rc)
+        return rc;
+    if (count)
+        *count = c;
+    if (!out_device)
+        return capacity > 0 && c > 0 ? SELSYNC_ERR_INVALID_ARG : SELSYNC_OK;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, out_device) != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return SELSYNC_ERR_NOT_DEVICE_MEM;
+    }
+    const int64_t lim = c < capacity ? c : capacity;
+    if (launch_partition_order(num_samples, num_workers, worker, scheme, lim, out_device,
+                               static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SELSYNC_ERR_HIP;
+    return SELSYNC_OK;
+}
+
 // =============================================================================== variant: Adam local update
 
 namespace {

@@ -99,6 +99,28 @@ struct LaunchCfg {
 
 enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };
 
+// ---- data partitioning (Sec. III-D), shared by the host function and the device kernel ----
+
+// Chunk c of D samples over N workers starts here; the first D % N chunks hold one more sample.
+__host__ __device__ inline int64_t chunk_start(int64_t D, int64_t N, int64_t c)
+{
+    const int64_t base = D / N, rem = D % N;
+    return c * base + (c < rem ? c : rem);
+}
+
+// Sample index at position p of worker n's reading order.
+//   scheme 0 (default partitioning): positions cover the worker's own chunk only.
+//   scheme 1 (SelSync partitioning): all chunks as a circular queue rotated to chunk n,
+//   i.e. chunk n, n+1, ..., N-1, 0, ..., n-1.
+__host__ __device__ inline int64_t partition_index(int64_t D, int64_t N, int64_t n, int scheme, int64_t p)
+{
+    if (scheme == 0)
+        return chunk_start(D, N, n) + p;
+    // the rotated order is the tail [start(n), D) followed by the head [0, start(n))
+    const int64_t tail = D - chunk_start(D, N, n);
+    return p < tail ? chunk_start(D, N, n) + p : p - tail;
+}
+
 // ---- launchers (selsync_kernels.hip) --------------------------------------------
 
 // Elements one workgroup pass of the default streaming kernel shape covers: one
@@ -133,6 +155,10 @@ hipError_t launch_tensor_norms(const double *partials, const int32_t *range_begi
 hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
                             const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
                             hipStream_t s);
+
+// out[p] = partition_index(D, N, n, scheme, p) for p < count (device array).
+hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,
+                                  hipStream_t s);
 
 hipError_t launch_reset(const TrackerDev &td, hipStream_t s);
 hipError_t launch_set_delta(const TrackerDev &td, double delta, hipStream_t s);

@@ -692,6 +692,15 @@ __global__ void k_reset(TrackerDev td)
 
 __global__ void k_set_delta(TrackerDev td, double delta) { *td.delta_thr = delta; }
 
+// Reading order of one worker under DefDP / SelDP (Sec. III-D), written as sample indices.
+__global__ __launch_bounds__(256) void k_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count,
+                                                         int64_t *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < count; p += stride)
+        out[p] = partition_index(D, N, n, scheme, p);
+}
+
 // ---------------------------------------------------------------- k_aggregate
 
 // Mean of K fp32 values in fp64, summed k = 0..K-1, divided by K, rounded once to fp32.
@@ -1200,6 +1209,17 @@ hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, 
                                : launch_ga_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
     return cfg.nontemporal ? launch_ga_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
                            : launch_ga_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
+}
+
+hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,
+                                  hipStream_t s)
+{
+    if (count <= 0)
+        return hipSuccess;
+    const int64_t blocks = (count + 255) / 256;
+    const int grid = (int)(blocks < 65536 ? blocks : 65536);
+    hipLaunchKernelGGL(k_partition_order, dim3(grid), dim3(256), 0, s, D, N, n, scheme, count, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_reset(const TrackerDev &td, hipStream_t s)

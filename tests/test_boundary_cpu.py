@@ -181,3 +181,27 @@ def test_workload_generators_are_seeded_and_order_independent():
     assert g[0].dtype == np.uint16
     f = W.tensor_factors(wl5)
     assert 50 < max(f) / min(f) <= 100.0 + 1e-9
+
+
+@pytest.mark.parametrize("D,N", [(100, 4), (103, 4), (7, 3), (5, 8), (0, 3), (1000, 16), (17, 1), (12345, 7)])
+def test_partition_order_matches_oracle_bit_for_bit(B, D, N):
+    # Sec. III-D: integer work, compared exactly against the oracle's plain construction
+    from oracle import selsync_oracle as O
+    for n in range(N):
+        assert B.partition_order(D, N, n, seldp=True) == O.seldp_order(D, N, n)
+        assert B.partition_order(D, N, n, seldp=False) == O.defdp_order(D, N, n)
+
+
+def test_partition_order_rejects_bad_arguments(B):
+    n = ctypes.c_int64()
+    bad = B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_partition_order(-1, 4, 0, 1, 0, None, ctypes.byref(n)) == bad
+    assert B.selsync_partition_order(10, 0, 0, 1, 0, None, ctypes.byref(n)) == bad
+    assert B.selsync_partition_order(10, 4, 4, 1, 0, None, ctypes.byref(n)) == bad
+    assert B.selsync_partition_order(10, 4, -1, 1, 0, None, ctypes.byref(n)) == bad
+    assert B.selsync_partition_order(10, 4, 0, 2, 0, None, ctypes.byref(n)) == bad
+    assert B.selsync_partition_order(10, 4, 0, 1, 0, None, None) == bad
+    # capacity smaller than the order: only `capacity` entries are written
+    out = (ctypes.c_int64 * 4)(-1, -1, -1, -1)
+    assert B.selsync_partition_order(10, 4, 1, 1, 3, out, ctypes.byref(n)) == 0
+    assert n.value == 10 and list(out) == [3, 4, 5, -1]

@@ -399,6 +399,17 @@ def test_tracker_state_checkpoint_and_resume(B):
     ls.close()
 
 
+# ================================================================= data partitioning (Sec. III-D)
+
+@pytest.mark.parametrize("D,N", [(100, 4), (103, 4), (5, 8), (0, 3), (1_000_003, 16)])
+def test_partition_order_kernel_matches_oracle(B, D, N):
+    for n in sorted({0, 1 % N, N - 1}):
+        for seldp in (True, False):
+            got = B.partition_order_device(D, N, n, seldp).cpu().tolist()
+            want = O.seldp_order(D, N, n) if seldp else O.defdp_order(D, N, n)
+            assert got == want
+
+
 # ================================================================= variant: Adam local update
 
 @pytest.mark.parametrize("mixed", [False, True])

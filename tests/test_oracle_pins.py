@@ -19,6 +19,9 @@ def golden():
         line = line.split("#")[0].split()
         if not line:
             continue
+        if line[0] == "seldp":
+            vals.setdefault("seldp", {})[int(line[1])] = [int(x) for x in line[2:]]
+            continue
         if line[0] == "table1":
             table.append((line[1], float(line[2]), float(line[3])))
         else:
@@ -648,6 +651,34 @@ def test_ga_equals_pa_when_every_step_synchronises_from_identical_start():
         np.testing.assert_allclose(ga_w[0][0], pa_w[0][0], rtol=0, atol=2e-7)
         np.testing.assert_allclose(ga_m[0][0], np.mean([m[0].astype(np.float64) for m in pa_m], axis=0),
                                    rtol=0, atol=2e-8)
+
+
+# =============================================================== data partitioning (Sec. III-D)
+
+def test_seldp_matches_the_papers_four_worker_example():
+    vals, _ = golden()
+    D, N = 4 * 25, 4
+    chunks = O.partition_chunks(D, N)
+    for worker, chunk_order in vals["seldp"].items():
+        want = [i for c in chunk_order for i in chunks[c]]
+        assert O.seldp_order(D, N, worker) == want
+    assert O.seldp_order(D, N, 0) == list(range(D))
+
+
+@pytest.mark.parametrize("D,N", [(100, 4), (103, 4), (7, 3), (5, 8), (0, 3), (1000, 16), (17, 1)])
+def test_partitioning_properties(D, N):
+    chunks = O.partition_chunks(D, N)
+    assert [i for c in chunks for i in c] == list(range(D))               # contiguous cover, no overlap
+    assert max(len(c) for c in chunks) - min(len(c) for c in chunks) <= 1   # "equal-sized" up to the remainder
+    owner = {i: c for c, ch in enumerate(chunks) for i in ch}
+    orders = [O.seldp_order(D, N, n) for n in range(N)]
+    for n in range(N):
+        assert sorted(orders[n]) == list(range(D))                         # every worker can train on every sample
+        assert O.defdp_order(D, N, n) == chunks[n]                         # DefDP: only its own chunk
+        assert orders[n][:len(chunks[n])] == chunks[n]                     # the queue head is the worker's own chunk
+    if D % N == 0 and D > 0:
+        for pos in range(D):     # at any position the N workers read from N different chunks
+            assert len({owner[orders[n][pos]] for n in range(N)}) == N
 
 
 # =============================================================== end to end, independent re-derivation
