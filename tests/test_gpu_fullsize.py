@@ -39,3 +39,35 @@ def test_vgg11_like_full_size_three_steps_with_sync():
     st = ls.ctx.stats()
     assert st["steps_sync"] == 1 and st["steps_local"] == 2
     ls.close()
+
+
+def test_tensor_beyond_2_to_31_elements_uses_64_bit_offsets():
+    """One tensor of 2^31 + 12345 elements (8.6 GB per buffer): every chunk offset past 2^31 must be
+    addressed correctly.  Checked through properties that hold at any size: a constant gradient c
+    gives ||g||^2 = n c^2 exactly, and a constant state stays constant with the value the oracle
+    computes for a single element."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    free, _ = torch.cuda.mem_get_info()
+    n = (1 << 31) + 12345
+    if free < 5 * 4 * n:
+        pytest.skip("not enough free HBM for a 2^31-element case")
+    from oracle import selsync_oracle as O
+    from paper_2307_07950_amd import binding as B
+    import numpy as np
+    g = torch.full((n,), 0.5, dtype=torch.float32, device="cuda")
+    w = torch.full((n,), 1.25, dtype=torch.float32, device="cuda")
+    m = torch.full((n,), -0.75, dtype=torch.float32, device="cuda")
+    glob = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ctx = B.SelSync(1, 0.0)                               # delta 0: the step also aggregates (copies w to global)
+    plan = ctx.plan([[g]], [[w]], [[m]], [glob])
+    assert plan.info()["update_chunks"] == -(-n // 512)
+    dec = ctx.step(plan, 0.1, 0.9, 5e-4, 2.0, first_step=0, blocking=True)
+    assert dec.norm_sq == [float(n)]                      # (2*0.5)^2 * n, exact in fp64
+    hw, hm, hg = np.array([1.25], np.float32), np.array([-0.75], np.float32), np.array([0.5], np.float32)
+    O.sgd_update([hw], [hm], [hg], 0.1, 0.9, 5e-4, 2.0, False)
+    for t, want in ((w, hw[0]), (m, hm[0]), (glob, hw[0])):
+        assert float(t.min()) == float(want) and float(t.max()) == float(want)
+    assert float(w[-1]) == float(hw[0]) and float(w[(1 << 31) + 5]) == float(hw[0])
+    assert dec.sync == 1
+    ctx.close()
