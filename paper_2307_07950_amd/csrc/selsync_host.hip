@@ -11,6 +11,7 @@
 #include <cstdio>
 #include <climits>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -91,6 +92,15 @@ struct selsync_plan {
     AggTables agg{};
     LaunchCfg upd_cfg{1, 1, 0};
     LaunchCfg agg_cfg{1, 1, 0};
+
+    selsync_plan() = default;
+    selsync_plan(const selsync_plan &) = delete;
+    selsync_plan &operator=(const selsync_plan &) = delete;
+    ~selsync_plan()
+    {
+        if (d_blob)
+            (void)hipFree(d_blob);
+    }
 };
 
 namespace {
@@ -115,6 +125,19 @@ int32_t fail(selsync_ctx *ctx, int32_t code, const char *fmt, ...)
             return fail((ctx), e_ == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP,     \
                         "%s failed: %s", #expr, hipGetErrorString(e_));                           \
     } while (0)
+
+// Nothing may throw across the C boundary: host-side containers can (std::bad_alloc).
+template <typename F>
+int32_t guarded(selsync_ctx *ctx, F &&body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, SELSYNC_ERR_OOM, "out of host memory");
+    } catch (...) {
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "unexpected internal error");
+    }
+}
 
 int32_t check_device(selsync_ctx *ctx)
 {
@@ -493,6 +516,12 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
 
 // =============================================================================== plan
 
+namespace {
+int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, const selsync_tensor_list *params,
+                         const selsync_tensor_list *momenta, const selsync_tensor_list *master,
+                         const selsync_tensor_list *global, const selsync_tensor_list *global_lowp, selsync_plan **out);
+}
+
 extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_list *grads,
                                        const selsync_tensor_list *params, const selsync_tensor_list *momenta,
                                        const selsync_tensor_list *master, const selsync_tensor_list *global,
@@ -503,6 +532,14 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     if (!out)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
+    return guarded(ctx, [&] { return plan_create_impl(ctx, grads, params, momenta, master, global, global_lowp, out); });
+}
+
+namespace {
+int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, const selsync_tensor_list *params,
+                         const selsync_tensor_list *momenta, const selsync_tensor_list *master,
+                         const selsync_tensor_list *global, const selsync_tensor_list *global_lowp, selsync_plan **out)
+{
     int32_t rc = check_device(ctx);
     if (rc)
         return rc;
@@ -651,9 +688,7 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
         });
     }
 
-    selsync_plan *plan = new (std::nothrow) selsync_plan();
-    if (!plan)
-        return fail(ctx, SELSYNC_ERR_OOM, "out of host memory");
+    std::unique_ptr<selsync_plan> plan(new selsync_plan());     // frees its device tables on any early exit
     plan->ctx = ctx;
     plan->K = K;
     plan->T = T;
@@ -713,9 +748,6 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     if (e == hipSuccess)
         e = hipMemcpy(plan->d_blob, blob.data(), off, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
-        if (plan->d_blob)
-            (void)hipFree(plan->d_blob);
-        delete plan;
         return fail(ctx, e == hipErrorOutOfMemory ? SELSYNC_ERR_OOM : SELSYNC_ERR_HIP, "plan tables: %s",
                     hipGetErrorString(e));
     }
@@ -745,17 +777,16 @@ extern "C" int32_t selsync_plan_create(selsync_ctx *ctx, const selsync_tensor_li
     plan->agg_cfg = plan->upd_cfg;
 
     ctx->live_plans += 1;
-    *out = plan;
+    *out = plan.release();
     return SELSYNC_OK;
 }
+}  // namespace
 
 extern "C" int32_t selsync_plan_destroy(selsync_plan *plan)
 {
     if (!plan)
         return SELSYNC_OK;
     (void)hipDeviceSynchronize();
-    if (plan->d_blob)
-        (void)hipFree(plan->d_blob);
     if (plan->ctx)
         plan->ctx->live_plans -= 1;
     delete plan;
@@ -979,39 +1010,41 @@ int32_t resolve_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *a
 
 extern "C" int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const selsync_tensor_list *v)
 {
-    if (!plan || !plan->ctx)
-        return SELSYNC_ERR_INVALID_ARG;
-    selsync_ctx *ctx = plan->ctx;
-    int32_t rc = check_plan(ctx, plan, true);
-    if (rc)
-        return rc;
-    if (!v)
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "second-moment lists are NULL");
-    std::vector<Interval> ivals;
-    if ((rc = check_lists(ctx, "second_moment", v, plan->K, plan->T, plan->numel, SELSYNC_F32, true, ivals)))
-        return rc;
-    for (int k = 0; k < plan->K; ++k)
-        for (int t = 0; t < plan->T; ++t) {
-            TensorRec &r = plan->h_recs[(size_t)k * plan->T + t];
-            float *vp = static_cast<float *>(v[k].tensors[t].data);
-            if (plan->numel[t] > 0 && aligned16(r.m) && !aligned16(vp))
-                return fail(ctx, SELSYNC_ERR_INVALID_ARG,
-                            "second_moment[%d] tensor %d must be 16-byte aligned because its momentum tensor is", k, t);
-        }
-    // the new buffers are written: together with everything already bound they may not overlap
-    std::vector<Interval> all = plan->ivals;
-    all.insert(all.end(), ivals.begin(), ivals.end());
-    if ((rc = check_overlap(ctx, all)))
-        return rc;
-    for (int k = 0; k < plan->K; ++k)
-        for (int t = 0; t < plan->T; ++t)
-            plan->h_recs[(size_t)k * plan->T + t].v = static_cast<float *>(v[k].tensors[t].data);
-    (void)hipDeviceSynchronize();
-    if (!plan->h_recs.empty())
-        HIP_TRY(ctx, hipMemcpy(plan->d_recs, plan->h_recs.data(), plan->h_recs.size() * sizeof(TensorRec),
-                               hipMemcpyHostToDevice));
-    plan->has_second_moment = true;      // plan->ivals stays the base set, so buffers can be re-bound
-    return SELSYNC_OK;
+    return guarded(plan ? plan->ctx : nullptr, [&]() -> int32_t {
+        if (!plan || !plan->ctx)
+            return SELSYNC_ERR_INVALID_ARG;
+        selsync_ctx *ctx = plan->ctx;
+        int32_t rc = check_plan(ctx, plan, true);
+        if (rc)
+            return rc;
+        if (!v)
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "second-moment lists are NULL");
+        std::vector<Interval> ivals;
+        if ((rc = check_lists(ctx, "second_moment", v, plan->K, plan->T, plan->numel, SELSYNC_F32, true, ivals)))
+            return rc;
+        for (int k = 0; k < plan->K; ++k)
+            for (int t = 0; t < plan->T; ++t) {
+                TensorRec &r = plan->h_recs[(size_t)k * plan->T + t];
+                float *vp = static_cast<float *>(v[k].tensors[t].data);
+                if (plan->numel[t] > 0 && aligned16(r.m) && !aligned16(vp))
+                    return fail(ctx, SELSYNC_ERR_INVALID_ARG,
+                                "second_moment[%d] tensor %d must be 16-byte aligned because its momentum tensor is", k, t);
+            }
+        // the new buffers are written: together with everything already bound they may not overlap
+        std::vector<Interval> all = plan->ivals;
+        all.insert(all.end(), ivals.begin(), ivals.end());
+        if ((rc = check_overlap(ctx, all)))
+            return rc;
+        for (int k = 0; k < plan->K; ++k)
+            for (int t = 0; t < plan->T; ++t)
+                plan->h_recs[(size_t)k * plan->T + t].v = static_cast<float *>(v[k].tensors[t].data);
+        (void)hipDeviceSynchronize();
+        if (!plan->h_recs.empty())
+            HIP_TRY(ctx, hipMemcpy(plan->d_recs, plan->h_recs.data(), plan->h_recs.size() * sizeof(TensorRec),
+                                   hipMemcpyHostToDevice));
+        plan->has_second_moment = true;      // plan->ivals stays the base set, so buffers can be re-bound
+        return SELSYNC_OK;
+    });
 }
 
 extern "C" int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam,
@@ -1232,34 +1265,36 @@ extern "C" int32_t selsync_tracker_set_state(selsync_ctx *ctx, void *stream, con
 
 extern "C" int32_t selsync_profile_enable(selsync_ctx *ctx, int32_t enable, int32_t max_launches)
 {
-    if (!ctx)
-        return SELSYNC_ERR_INVALID_ARG;
-    int32_t rc = check_device(ctx);
-    if (rc)
-        return rc;
-    if (!enable) {
-        ctx->prof_on = false;
-        return SELSYNC_OK;
-    }
-    if (max_launches < 1 || max_launches > (1 << 20))
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "max_launches out of range");
-    for (int k = 0; k < 3; ++k) {
-        while ((int)ctx->prof_pool[k].size() < max_launches) {
-            ProfRec r;
-            HIP_TRY(ctx, hipEventCreate(&r.start));
-            hipError_t e = hipEventCreate(&r.stop);
-            if (e != hipSuccess) {
-                (void)hipEventDestroy(r.start);
-                return fail(ctx, SELSYNC_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
-            }
-            ctx->prof_pool[k].push_back(r);
+    return guarded(ctx, [&]() -> int32_t {
+        if (!ctx)
+            return SELSYNC_ERR_INVALID_ARG;
+        int32_t rc = check_device(ctx);
+        if (rc)
+            return rc;
+        if (!enable) {
+            ctx->prof_on = false;
+            return SELSYNC_OK;
         }
-        ctx->prof_used[k] = 0;
-        ctx->prof_seen[k] = 0;
-    }
-    ctx->prof_cap = max_launches;
-    ctx->prof_on = true;
-    return SELSYNC_OK;
+        if (max_launches < 1 || max_launches > (1 << 20))
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "max_launches out of range");
+        for (int k = 0; k < 3; ++k) {
+            while ((int)ctx->prof_pool[k].size() < max_launches) {
+                ProfRec r;
+                HIP_TRY(ctx, hipEventCreate(&r.start));
+                hipError_t e = hipEventCreate(&r.stop);
+                if (e != hipSuccess) {
+                    (void)hipEventDestroy(r.start);
+                    return fail(ctx, SELSYNC_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+                }
+                ctx->prof_pool[k].push_back(r);
+            }
+            ctx->prof_used[k] = 0;
+            ctx->prof_seen[k] = 0;
+        }
+        ctx->prof_cap = max_launches;
+        ctx->prof_on = true;
+        return SELSYNC_OK;
+    });
 }
 
 extern "C" int32_t selsync_profile_config(selsync_ctx *ctx, int32_t kind_mask, int32_t stride)
