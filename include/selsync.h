@@ -29,7 +29,9 @@
  *     each other or the gradients; this is checked at plan time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work
  *     is ordered on that stream.  Per-step calls never allocate memory and never
- *     synchronise the host unless `blocking` is non-zero.
+ *     synchronise the host unless `blocking` is non-zero; non-blocking per-step calls
+ *     enqueue kernels only (no copies, no memsets), so a caller may capture them in a
+ *     HIP graph and replay it (timing events must be off while capturing).
  *   - One context may be used by one host thread at a time.
  */
 #ifndef SELSYNC_H

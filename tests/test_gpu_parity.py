@@ -399,6 +399,60 @@ def test_tracker_state_checkpoint_and_resume(B):
     ls.close()
 
 
+def test_step_can_be_captured_in_a_hip_graph_and_replayed(B):
+    """selsync_step neither allocates nor synchronises, so a caller may capture it.  Every replay
+    (with eager work and synchronisations between replays) must equal the eager run bit for bit."""
+    numel = [150001, 777, 4096]
+    K = 4
+    r = rng(150)
+    grads = [[(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel] for _ in range(K)]
+    scales = [1.0, 1.0, 3.0, 1.0, 1.0, 0.2, 1.0]
+
+    def fresh():
+        ls = PU.LockStep(B, numel, K, delta=0.2, window=4, alpha=0.5, seed=22)
+        ls.bind_grads(0, grads)
+        return ls
+
+    # eager reference: step 0 with first_step=1, then 6 identical-argument steps (grad_scale via the tensor below)
+    eager = fresh()
+    eager.ctx.step(eager.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=1)
+    decs_e = []
+    for t in range(6):
+        for k in range(K):                       # eager work between steps: rescale worker gradients in place
+            for x in eager.d_grads[0][k]:
+                x.mul_(scales[t + 1] / scales[t])
+        decs_e.append(eager.ctx.step(eager.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=0, blocking=True))
+    assert any(d.sync for d in decs_e) and not all(d.sync for d in decs_e)
+
+    graphed = fresh()
+    graphed.ctx.step(graphed.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=1)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.ctx.step(graphed.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=0)
+    # the capture itself does not execute: state is still that of step 0
+    for t in range(6):
+        for k in range(K):
+            for x in graphed.d_grads[0][k]:
+                x.mul_(scales[t + 1] / scales[t])
+        g.replay()
+        torch.cuda.synchronize()
+        d = graphed.ctx.read_decision()
+        assert d.flags == decs_e[t].flags and d.sync == decs_e[t].sync
+        assert [x.hex() for x in d.norm_sq] == [x.hex() for x in decs_e[t].norm_sq]
+        assert [x.hex() for x in d.delta] == [x.hex() for x in decs_e[t].delta]
+    for k in range(K):
+        for t in range(len(numel)):
+            assert PU.to_host(graphed.d_w[k][t]).tobytes() == PU.to_host(eager.d_w[k][t]).tobytes()
+            assert PU.to_host(graphed.d_m[k][t]).tobytes() == PU.to_host(eager.d_m[k][t]).tobytes()
+    for t in range(len(numel)):
+        assert PU.to_host(graphed.d_glob[t]).tobytes() == PU.to_host(eager.d_glob[t]).tobytes()
+    assert graphed.ctx.stats() == eager.ctx.stats()
+    del g
+    eager.close()
+    graphed.close()
+
+
 # ================================================================= data partitioning (Sec. III-D)
 
 @pytest.mark.parametrize("D,N", [(100, 4), (103, 4), (5, 8), (0, 3), (1_000_003, 16)])
