@@ -129,7 +129,8 @@ typedef struct selsync_tuning {
                                   <= 0 (default): one workgroup per chunk                               */
     int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
     int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 1024)        */
-    int32_t stream_variant;    /* workgroup shape of the update/norm kernel, 0 = default (see DESIGN)   */
+    int32_t stream_variant;    /* workgroup shape of the update/norm kernel: 0 = default (one 64-lane
+                                  wave per 512 elements); 1..12 = other measured shapes               */
     int32_t xcd_swizzle;       /* 1: each XCD walks a contiguous eighth of the chunk table; 0: off; <0 default */
 } selsync_tuning;
 

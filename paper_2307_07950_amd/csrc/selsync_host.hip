@@ -503,8 +503,8 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
         return SELSYNC_ERR_INVALID_ARG;
     if (t->chunk_elems > 0 && (t->chunk_elems % kChunkGranule != 0 || t->chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
-    if (t->stream_variant < 0 || t->stream_variant > 9)
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be in 0..9");
+    if (t->stream_variant < 0 || t->stream_variant > 12)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be in 0..12");
     if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kAggTileElems != 0 || t->agg_chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_chunk_elems must be a multiple of %d and <= 2^24",
                     kAggTileElems);

@@ -141,10 +141,9 @@ template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
 __device__ __forceinline__ void tile_f32(const SELSYNC_GLOBAL f32x4 *__restrict__ g4,
                                          SELSYNC_GLOBAL f32x4 *__restrict__ w4,
                                          SELSYNC_GLOBAL f32x4 *__restrict__ m4, uint32_t base, uint32_t nvec,
-                                         const SgdArgs &a, double &acc)
+                                         uint32_t tid, const SgdArgs &a, double &acc)
 {
     f32x4 gv[U], wv[U], mv[U];
-    const uint32_t tid = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t i = base + u * BLOCK + tid;
@@ -181,11 +180,10 @@ __device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x2 *__restric
                                            SELSYNC_GLOBAL f32x4 *__restrict__ w4,
                                            SELSYNC_GLOBAL f32x4 *__restrict__ m4,
                                            SELSYNC_GLOBAL u32x2 *__restrict__ c4, uint32_t base, uint32_t nvec,
-                                           const SgdArgs &a, double &acc)
+                                           uint32_t tid, const SgdArgs &a, double &acc)
 {
     u32x2 gv[U];
     f32x4 wv[U], mv[U];
-    const uint32_t tid = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t i = base + u * BLOCK + tid;
@@ -227,14 +225,14 @@ __device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x2 *__restric
 // and the ragged tail of aligned ones).  Still coalesced: lane i takes element i.
 template <int BLOCK, bool MIXED, bool UPD, bool NORM>
 __device__ __forceinline__ void scalar_range(const TensorRec &r, uint64_t off, uint32_t begin, uint32_t n,
-                                             const SgdArgs &a, double &acc)
+                                             uint32_t tid, const SgdArgs &a, double &acc)
 {
     const SELSYNC_GLOBAL float *gf = as_global<const float>(r.g);
     const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(r.g);
     SELSYNC_GLOBAL float *wp = as_global<float>(r.w);
     SELSYNC_GLOBAL float *mp = as_global<float>(r.m);
     SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(r.lowp);
-    for (uint32_t i = begin + threadIdx.x; i < n; i += BLOCK) {
+    for (uint32_t i = begin + tid; i < n; i += BLOCK) {
         const uint64_t e = off + i;
         float g;
         if (MIXED)
@@ -257,18 +255,24 @@ __device__ __forceinline__ void scalar_range(const TensorRec &r, uint64_t off, u
     }
 }
 
-template <int BLOCK, int U, bool MIXED, int MODE, bool NT>
-__global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ recs,
-                                                  const ChunkRec *__restrict__ chunks, int nchunks,
-                                                  double *__restrict__ partials, SgdArgs a, int xcd_per)
+// WPB > 1 packs that many independent single-wave units (BLOCK must be 64) into one workgroup:
+// same memory behaviour per wave, fewer workgroups for the dispatcher.
+template <int BLOCK, int U, bool MIXED, int MODE, bool NT, int WPB = 1>
+__global__ __launch_bounds__(BLOCK *WPB) void k_stream(const TensorRec *__restrict__ recs,
+                                                       const ChunkRec *__restrict__ chunks, int nchunks,
+                                                       double *__restrict__ partials, SgdArgs a, int xcd_per)
 {
+    static_assert(WPB == 1 || BLOCK == 64, "wave packing needs single-wave units");
     constexpr bool UPD = MODE != kNormOnly;
     constexpr bool NORM = MODE != kUpdateOnly;
     constexpr uint32_t VEC = 4;
     __shared__ double red[BLOCK / 64];
+    const uint32_t tid = WPB > 1 ? (threadIdx.x & 63u) : threadIdx.x;
+    const int unit0 = WPB > 1 ? (int)(blockIdx.x * WPB + (threadIdx.x >> 6)) : (int)blockIdx.x;
+    const int unit_stride = (int)gridDim.x * WPB;
 
     const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    for (int v = blockIdx.x; v < vtotal; v += gridDim.x) {
+    for (int v = unit0; v < vtotal; v += unit_stride) {
         const int c = chunk_of_workgroup(v, xcd_per);
         if (c >= nchunks)
             continue;
@@ -287,21 +291,21 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
                 SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + ch.off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
-                    tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, c4, base, nvec, a, acc);
+                    tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, c4, base, nvec, tid, a, acc);
                 if (base < nvec)
-                    tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, c4, base, nvec, a, acc);
+                    tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, c4, base, nvec, tid, a, acc);
             } else {
                 const SELSYNC_GLOBAL f32x4 *g4 =
                     as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + ch.off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
-                    tile_f32<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, base, nvec, a, acc);
+                    tile_f32<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, base, nvec, tid, a, acc);
                 if (base < nvec)
-                    tile_f32<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, base, nvec, a, acc);
+                    tile_f32<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, base, nvec, tid, a, acc);
             }
-            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, nvec * VEC, n, a, acc);
+            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, nvec * VEC, n, tid, a, acc);
         } else {
-            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, n, a, acc);
+            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, n, tid, a, acc);
         }
 
         if (NORM) {
@@ -309,7 +313,7 @@ __global__ __launch_bounds__(BLOCK) void k_stream(const TensorRec *__restrict__ 
             // through LDS in wave order.  Either way: one fixed slot per chunk.
             const double s = wave_sum(acc);
             if constexpr (BLOCK == 64) {
-                if (threadIdx.x == 0)
+                if (tid == 0)
                     partials[c] = s;
             } else {
                 if ((threadIdx.x & 63) == 0)
@@ -1009,12 +1013,13 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
 
 constexpr int kBlock = 256;
 
-template <int BLOCK, int U, bool MIXED, int MODE, bool NT>
+template <int BLOCK, int U, bool MIXED, int MODE, bool NT, int WPB = 1>
 hipError_t launch_stream_bu(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
                             const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_stream<BLOCK, U, MIXED, MODE, NT>), dim3(grid), dim3(BLOCK), 0, s, recs, chunks, nchunks,
-                       partials, sgd, xcd_per);
+    const int wgs = (grid + WPB - 1) / WPB;
+    hipLaunchKernelGGL((k_stream<BLOCK, U, MIXED, MODE, NT, WPB>), dim3(wgs), dim3(BLOCK * WPB), 0, s, recs, chunks,
+                       nchunks, partials, sgd, xcd_per);
     return hipGetLastError();
 }
 
@@ -1034,6 +1039,9 @@ hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nc
     case 7: SELSYNC_V(64, 1);
     case 8: SELSYNC_V(128, 1);
     case 9: SELSYNC_V(256, 4);
+    case 10: return launch_stream_bu<64, 2, MIXED, MODE, NT, 2>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s);
+    case 11: return launch_stream_bu<64, 2, MIXED, MODE, NT, 4>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s);
+    case 12: return launch_stream_bu<64, 2, MIXED, MODE, NT, 8>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s);
     default: SELSYNC_V(64, 2);   // 0 and 6: single-wave workgroups, 512 elements each (measured best)
     }
 #undef SELSYNC_V

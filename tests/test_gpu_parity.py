@@ -178,7 +178,7 @@ def test_many_chunks_take_the_segment_reduction_level(B, mixed):
 
 
 @pytest.mark.parametrize("variant,chunk", [(0, 512), (0, 1024), (1, 2048), (2, 1024), (3, 2048), (4, 1024), (5, 1024),
-                                           (7, 256), (8, 512), (9, 4096), (9, 65536)])
+                                           (7, 256), (8, 512), (9, 4096), (9, 65536), (10, 512), (11, 512), (12, 1024)])
 @pytest.mark.parametrize("persistent", [0, 2])
 def test_every_workgroup_shape_gives_the_same_results(B, variant, chunk, persistent):
     numel = [100003, 513, 4096, 255]
