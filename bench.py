@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events in the timed loop (roofline.achieved becomes null)")
-    ap.add_argument("--event-stride", type=int, default=4,
+    ap.add_argument("--event-stride", type=int, default=8,
                     help="bracket every n-th launch of the dominant kernel with HIP events inside the timed loop")
     ap.add_argument("--all-kernel-events", action="store_true",
                     help="bracket every launch of every kernel (costs ~1.4 %% of the step time)")
