@@ -23,8 +23,12 @@
  *   - The CALLER owns every tensor buffer; the library never frees or reallocates
  *     them.  Descriptors are copied at plan time; the data pointers must stay valid
  *     (and the memory allocated) until all work enqueued with that plan has finished.
- *   - Tensors are contiguous.  Pointers need only element alignment; tensors whose
- *     pointers are all 16-byte aligned take the 128-bit vector path.
+ *   - Tensors are contiguous.  Pointers need only element alignment.  When all buffers of
+ *     a tensor (its gradient, parameter, momentum, ...) sit at the same position relative
+ *     to 16-byte alignment -- always true for 16-byte aligned buffers, and for views at the
+ *     same element offset into aligned arenas -- the library peels up to 3 elements and
+ *     runs 128-bit accesses over the rest; otherwise that tensor is processed element by
+ *     element (same results, lower bandwidth).
  *   - Buffers that are written (params, momenta, masters, global) must not overlap
  *     each other or the gradients; this is checked at plan time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work

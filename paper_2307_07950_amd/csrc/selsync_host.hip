@@ -244,7 +244,15 @@ int32_t check_overlap(selsync_ctx *ctx, std::vector<Interval> &iv)
     return SELSYNC_OK;
 }
 
-bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// Phase of a stream: element index (mod 4) of its first element relative to vector alignment
+// (16 bytes for fp32 streams, 8 bytes for bf16 streams).  Streams with equal phase become
+// vector-aligned together after peeling (4 - phase) % 4 elements.
+int stream_phase(const void *p, size_t elem_size)
+{
+    return (int)((reinterpret_cast<uintptr_t>(p) / elem_size) & 3u);
+}
+
+uint32_t head_bits(int phase) { return (uint32_t)((4 - phase) & 3) << kChunkHeadShift; }
 
 // The chunking rule of the multi-tensor tables: every tensor is cut, from element 0,
 // into pieces of `chunk` elements with one shorter last piece; empty tensors give none.
@@ -616,11 +624,13 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
                 }
                 recs[(size_t)k * T + t] = r;
                 tensor_chunk_begin[(size_t)k * T + t] = (int32_t)chunks.size();
-                const bool al = aligned16(r.g) && aligned16(r.w) && aligned16(r.m) && (!mixed || aligned16(r.lowp));
+                const int ph = stream_phase(r.w, 4);
+                const bool al = stream_phase(r.g, mixed ? 2 : 4) == ph && stream_phase(r.m, 4) == ph &&
+                                (!mixed || stream_phase(r.lowp, 2) == ph);
                 split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
                     ChunkRec c;
                     c.rec = (uint32_t)((size_t)k * T + t);
-                    c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u);
+                    c.n_flags = (uint32_t)n | (al ? (kChunkAligned | head_bits(ph)) : 0u);
                     c.off = (uint64_t)off;
                     chunks.push_back(c);
                 });
@@ -654,35 +664,36 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     std::vector<const void *> agg_grad(grads ? (size_t)T * K : 0);
     std::vector<float *> agg_m(grads ? (size_t)T * K : 0);
     for (int t = 0; t < T; ++t) {
+        agg_g[t] = static_cast<float *>(global[0].tensors[t].data);
+        const int ph = stream_phase(agg_g[t], 4);
         bool al = true;
         for (int k = 0; k < K; ++k) {
             if (mixed) {
                 agg_w[(size_t)t * K + k] = static_cast<float *>(master[k].tensors[t].data);
                 agg_c[(size_t)t * K + k] = static_cast<uint16_t *>(params[k].tensors[t].data);
-                al = al && aligned16(agg_c[(size_t)t * K + k]);
+                al = al && stream_phase(agg_c[(size_t)t * K + k], 2) == ph;
             } else {
                 agg_w[(size_t)t * K + k] = static_cast<float *>(params[k].tensors[t].data);
             }
-            al = al && aligned16(agg_w[(size_t)t * K + k]);
+            al = al && stream_phase(agg_w[(size_t)t * K + k], 4) == ph;
         }
         bool al_grads = grads != nullptr;
         if (grads) {
             for (int k = 0; k < K; ++k) {
                 agg_grad[(size_t)t * K + k] = grads[k].tensors[t].data;
                 agg_m[(size_t)t * K + k] = static_cast<float *>(momenta[k].tensors[t].data);
-                al_grads = al_grads && aligned16(agg_grad[(size_t)t * K + k]) && aligned16(agg_m[(size_t)t * K + k]);
+                al_grads = al_grads && stream_phase(agg_grad[(size_t)t * K + k], mixed ? 2 : 4) == ph &&
+                           stream_phase(agg_m[(size_t)t * K + k], 4) == ph;
             }
         }
-        agg_g[t] = static_cast<float *>(global[0].tensors[t].data);
-        al = al && aligned16(agg_g[t]);
         if (mixed) {
             agg_gc[t] = static_cast<uint16_t *>(global_lowp[0].tensors[t].data);
-            al = al && aligned16(agg_gc[t]);
+            al = al && stream_phase(agg_gc[t], 2) == ph;
         }
         split_tensor(numel[t], agg_chunk, [&](int64_t off, int64_t n) {
             AggChunkRec c;
             c.t = (uint32_t)t;
-            c.n_flags = (uint32_t)n | (al ? kChunkAligned : 0u) | (al_grads ? kChunkAlignedGrads : 0u);
+            c.n_flags = (uint32_t)n | (al ? (kChunkAligned | head_bits(ph)) : 0u) | (al_grads ? kChunkAlignedGrads : 0u);
             c.off = (uint64_t)off;
             agg_chunks.push_back(c);
         });
@@ -1026,9 +1037,15 @@ extern "C" int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const sel
             for (int t = 0; t < plan->T; ++t) {
                 TensorRec &r = plan->h_recs[(size_t)k * plan->T + t];
                 float *vp = static_cast<float *>(v[k].tensors[t].data);
-                if (plan->numel[t] > 0 && aligned16(r.m) && !aligned16(vp))
+                // if this tensor takes the vector path (all its streams share one address phase), the
+                // second-moment buffer must share that phase too
+                const int ph = stream_phase(r.w, 4);
+                const bool vec = stream_phase(r.g, plan->mixed ? 2 : 4) == ph && stream_phase(r.m, 4) == ph &&
+                                 (!plan->mixed || stream_phase(r.lowp, 2) == ph);
+                if (plan->numel[t] > 0 && vec && stream_phase(vp, 4) != ph)
                     return fail(ctx, SELSYNC_ERR_INVALID_ARG,
-                                "second_moment[%d] tensor %d must be 16-byte aligned because its momentum tensor is", k, t);
+                                "second_moment[%d] tensor %d must have the same address phase (mod 16 bytes) as its "
+                                "momentum tensor", k, t);
             }
         // the new buffers are written: together with everything already bound they may not overlap
         std::vector<Interval> all = plan->ivals;

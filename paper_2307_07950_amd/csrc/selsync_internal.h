@@ -35,8 +35,12 @@ struct AggChunkRec {
     uint64_t off;
 };
 
+// Flag bits of n_flags.  "Aligned" means: every stream of the chunk has the same phase p
+// (element index mod 4 of its address relative to 16-byte alignment; bf16 streams relative to
+// 8-byte alignment), so after peeling head = (4 - p) % 4 elements all streams are vector-aligned.
 constexpr uint32_t kChunkAligned = 0x80000000u;
-constexpr uint32_t kChunkAlignedGrads = 0x40000000u;   // aggregation chunks: gradients and momenta aligned too
+constexpr uint32_t kChunkAlignedGrads = 0x40000000u;   // aggregation chunks: gradients and momenta share the phase too
+constexpr uint32_t kChunkHeadShift = 28;               // bits 28..29: head element count
 constexpr uint32_t kChunkCountMask = 0x0fffffffu;
 
 // Aggregation pointer tables (device arrays).

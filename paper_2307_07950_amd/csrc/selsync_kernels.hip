@@ -88,6 +88,13 @@ __device__ __forceinline__ int chunk_of_workgroup(int v, int xcd_per)
     return xcd_per > 0 ? (v & 7) * xcd_per + (v >> 3) : v;
 }
 
+// Elements to process one by one before the 16-byte aligned body of a chunk starts (0..3).
+__device__ __forceinline__ uint32_t chunk_head(uint32_t n_flags, uint32_t n)
+{
+    const uint32_t h = (n_flags >> kChunkHeadShift) & 3u;
+    return h < n ? h : n;
+}
+
 // Sum over the 64 lanes of a wavefront in a fixed butterfly order; result in lane 0.
 __device__ __forceinline__ double wave_sum(double v)
 {
@@ -282,13 +289,19 @@ __global__ __launch_bounds__(BLOCK *WPB) void k_stream(const TensorRec *__restri
         double acc = 0.0;
 
         if (ch.n_flags & kChunkAligned) {
-            const uint32_t nvec = n / VEC;
-            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + ch.off);
-            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + ch.off);
+            // all streams share one phase relative to 16-byte alignment: peel `head` elements,
+            // run 128-bit vectors over the aligned body, finish the ragged tail element-wise
+            const uint32_t head = chunk_head(ch.n_flags, n);
+            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, head, tid, a, acc);
+            const uint64_t off = ch.off + head;
+            const uint32_t nb = n - head;
+            const uint32_t nvec = nb / VEC;
+            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + off);
+            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + off);
             if (MIXED) {
                 const SELSYNC_GLOBAL u32x2 *g4 =
-                    as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
-                SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + ch.off);
+                    as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + off);
+                SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
                     tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, c4, base, nvec, tid, a, acc);
@@ -296,14 +309,14 @@ __global__ __launch_bounds__(BLOCK *WPB) void k_stream(const TensorRec *__restri
                     tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, c4, base, nvec, tid, a, acc);
             } else {
                 const SELSYNC_GLOBAL f32x4 *g4 =
-                    as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + ch.off);
+                    as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + off);
                 uint32_t base = 0;
                 for (; base + BLOCK * U <= nvec; base += BLOCK * U)
                     tile_f32<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, base, nvec, tid, a, acc);
                 if (base < nvec)
                     tile_f32<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, base, nvec, tid, a, acc);
             }
-            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, nvec * VEC, n, tid, a, acc);
+            scalar_range<BLOCK, MIXED, UPD, NORM>(r, off, nvec * VEC, nb, tid, a, acc);
         } else {
             scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, n, tid, a, acc);
         }
@@ -398,14 +411,17 @@ __global__ __launch_bounds__(BLOCK) void k_stream_adam(const TensorRec *__restri
         const uint32_t n = ch.n_flags & kChunkCountMask;
         double acc = 0.0;
         uint32_t done = 0;
+        uint32_t head = 0;
         if (ch.n_flags & kChunkAligned) {
-            const uint32_t nvec = n / 4;
-            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + ch.off);
-            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + ch.off);
-            SELSYNC_GLOBAL f32x4 *v4 = as_global<f32x4>(r.v + ch.off);
-            const SELSYNC_GLOBAL f32x4 *g4 = as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + ch.off);
-            const SELSYNC_GLOBAL u32x2 *gb4 = as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + ch.off);
-            SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + ch.off);
+            head = chunk_head(ch.n_flags, n);
+            const uint64_t off = ch.off + head;
+            const uint32_t nvec = (n - head) / 4;
+            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + off);
+            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + off);
+            SELSYNC_GLOBAL f32x4 *v4 = as_global<f32x4>(r.v + off);
+            const SELSYNC_GLOBAL f32x4 *g4 = as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + off);
+            const SELSYNC_GLOBAL u32x2 *gb4 = as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + off);
+            SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + off);
             for (uint32_t base = 0; base < nvec; base += BLOCK * U) {
                 f32x4 gv[U], wv[U], mv[U], vv4[U];
 #pragma unroll
@@ -447,13 +463,16 @@ __global__ __launch_bounds__(BLOCK) void k_stream_adam(const TensorRec *__restri
             done = nvec * 4;
         }
         {
+            // element-wise: the peeled head, the ragged tail, or the whole chunk when unaligned
             const SELSYNC_GLOBAL float *gf = as_global<const float>(r.g);
             const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(r.g);
             SELSYNC_GLOBAL float *wp = as_global<float>(r.w);
             SELSYNC_GLOBAL float *mp = as_global<float>(r.m);
             SELSYNC_GLOBAL float *vp = as_global<float>(r.v);
             SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(r.lowp);
-            for (uint32_t i = done + tid; i < n; i += BLOCK) {
+            const uint32_t rest = n - head - done;          // elements after the vector body
+            for (uint32_t j = tid; j < head + rest; j += BLOCK) {
+                const uint32_t i = j < head ? j : j + done;
                 const uint64_t e = ch.off + i;
                 const float g = MIXED ? __uint_as_float(((uint32_t)gh[e]) << 16) : gf[e];
                 float w = wp[e];
@@ -735,7 +754,8 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
         uint16_t *const *ctab = MIXED ? tabs.lowp + (size_t)ch.t * K : nullptr;
         SELSYNC_GLOBAL float *gp = as_global<float>(tabs.global[ch.t] + ch.off);
         SELSYNC_GLOBAL uint16_t *gcp = MIXED ? as_global<uint16_t>(tabs.glowp[ch.t] + ch.off) : nullptr;
-        uint32_t done = 0;
+        uint32_t done = 0;   // elements covered by the 128-bit body [head, head + done)
+        uint32_t head = 0;   // elements peeled before it
 
         if constexpr (KC > 0) {
             // K known at compile time: replica pointers live in registers, all K*U loads
@@ -748,7 +768,8 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                 cp[k] = MIXED ? as_global<uint16_t>(ctab[k] + ch.off) : nullptr;
             }
             if (ch.n_flags & kChunkAligned) {
-                const uint32_t nvec = n / 4;
+                head = chunk_head(ch.n_flags, n);
+                const uint32_t nvec = (n - head) / 4;
                 for (uint32_t base = 0; base < nvec; base += BLOCK * U) {
                     f32x4 v[U][KC];
 #pragma unroll
@@ -758,7 +779,7 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                             const uint32_t i = base + u * BLOCK + tid;
                             v[u][k] = 0.f;
                             if (i < nvec)
-                                v[u][k] = ld<NT>((const SELSYNC_GLOBAL f32x4 *)(wp[k]) + i);
+                                v[u][k] = ld<NT>((const SELSYNC_GLOBAL f32x4 *)(wp[k] + head) + i);
                         }
                     }
 #pragma unroll
@@ -778,25 +799,26 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                             r.y = finish_mean(s1, KC, invK, pow2);
                             r.z = finish_mean(s2, KC, invK, pow2);
                             r.w = finish_mean(s3, KC, invK, pow2);
-                            st<NT>((SELSYNC_GLOBAL f32x4 *)(gp) + i, r);
+                            st<NT>((SELSYNC_GLOBAL f32x4 *)(gp + head) + i, r);
                             u32x2 h;
                             if (MIXED) {
                                 h.x = bf16_pack(r.x, r.y);
                                 h.y = bf16_pack(r.z, r.w);
-                                st<NT>((SELSYNC_GLOBAL u32x2 *)(gcp) + i, h);
+                                st<NT>((SELSYNC_GLOBAL u32x2 *)(gcp + head) + i, h);
                             }
 #pragma unroll
                             for (int k = 0; k < KC; ++k) {
-                                st<NT>((SELSYNC_GLOBAL f32x4 *)(wp[k]) + i, r);
+                                st<NT>((SELSYNC_GLOBAL f32x4 *)(wp[k] + head) + i, r);
                                 if (MIXED)
-                                    st<NT>((SELSYNC_GLOBAL u32x2 *)(cp[k]) + i, h);
+                                    st<NT>((SELSYNC_GLOBAL u32x2 *)(cp[k] + head) + i, h);
                             }
                         }
                     }
                 }
                 done = nvec * 4;
             }
-            for (uint32_t i = done + tid; i < n; i += BLOCK) {
+            for (uint32_t j = tid; j < n - done; j += BLOCK) {   // peeled head, then ragged tail
+                const uint32_t i = j < head ? j : j + done;
                 double s = 0.0;
 #pragma unroll
                 for (int k = 0; k < KC; ++k)
@@ -816,11 +838,12 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
         } else {
             // Any other K: same arithmetic, replica pointers re-read from the table.
             if (ch.n_flags & kChunkAligned) {
-                const uint32_t nvec = n / 4;
+                head = chunk_head(ch.n_flags, n);
+                const uint32_t nvec = (n - head) / 4;
                 for (uint32_t i = tid; i < nvec; i += BLOCK) {
                     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
                     for (int k = 0; k < K; ++k) {
-                        const f32x4 v = ld<NT>(as_global<const f32x4>(wtab[k] + ch.off) + i);
+                        const f32x4 v = ld<NT>(as_global<const f32x4>(wtab[k] + ch.off + head) + i);
                         s0 += (double)v.x;
                         s1 += (double)v.y;
                         s2 += (double)v.z;
@@ -831,22 +854,23 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
                     r.y = finish_mean(s1, K, invK, pow2);
                     r.z = finish_mean(s2, K, invK, pow2);
                     r.w = finish_mean(s3, K, invK, pow2);
-                    st<NT>((SELSYNC_GLOBAL f32x4 *)(gp) + i, r);
+                    st<NT>((SELSYNC_GLOBAL f32x4 *)(gp + head) + i, r);
                     u32x2 h;
                     if (MIXED) {
                         h.x = bf16_pack(r.x, r.y);
                         h.y = bf16_pack(r.z, r.w);
-                        st<NT>((SELSYNC_GLOBAL u32x2 *)(gcp) + i, h);
+                        st<NT>((SELSYNC_GLOBAL u32x2 *)(gcp + head) + i, h);
                     }
                     for (int k = 0; k < K; ++k) {
-                        st<NT>(as_global<f32x4>(wtab[k] + ch.off) + i, r);
+                        st<NT>(as_global<f32x4>(wtab[k] + ch.off + head) + i, r);
                         if (MIXED)
-                            st<NT>(as_global<u32x2>(ctab[k] + ch.off) + i, h);
+                            st<NT>(as_global<u32x2>(ctab[k] + ch.off + head) + i, h);
                     }
                 }
                 done = nvec * 4;
             }
-            for (uint32_t i = done + tid; i < n; i += BLOCK) {
+            for (uint32_t j = tid; j < n - done; j += BLOCK) {   // peeled head, then ragged tail
+                const uint32_t i = j < head ? j : j + done;
                 double s = 0.0;
                 for (int k = 0; k < K; ++k)
                     s += (double)as_global<const float>(wtab[k])[ch.off + i];
@@ -912,9 +936,12 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
         const AggChunkRec ch = chunks[c];
         const uint32_t n = ch.n_flags & kChunkCountMask;
         const size_t row = (size_t)ch.t * K;
-        uint32_t done = 0;
+        uint32_t done = 0;   // elements covered by the 128-bit body [head, head + done)
+        uint32_t head = 0;
         if constexpr (KC > 0) {
             if ((ch.n_flags & kChunkAligned) && (ch.n_flags & kChunkAlignedGrads)) {
+                head = chunk_head(ch.n_flags, n);
+                const uint64_t off = ch.off + head;
                 SELSYNC_GLOBAL f32x4 *wp[KM];
                 SELSYNC_GLOBAL f32x4 *mp[KM];
                 const SELSYNC_GLOBAL f32x4 *gp[KM];
@@ -922,14 +949,14 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                 SELSYNC_GLOBAL u32x2 *cp[KM];
 #pragma unroll
                 for (int k = 0; k < KC; ++k) {
-                    wp[k] = as_global<f32x4>(tabs.w[row + k] + ch.off);
-                    mp[k] = as_global<f32x4>(tabs.m[row + k] + ch.off);
-                    gp[k] = MIXED ? nullptr : as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + ch.off);
-                    gbp[k] = MIXED ? as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + ch.off)
+                    wp[k] = as_global<f32x4>(tabs.w[row + k] + off);
+                    mp[k] = as_global<f32x4>(tabs.m[row + k] + off);
+                    gp[k] = MIXED ? nullptr : as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + off);
+                    gbp[k] = MIXED ? as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + off)
                                    : nullptr;
-                    cp[k] = MIXED ? as_global<u32x2>(tabs.lowp[row + k] + ch.off) : nullptr;
+                    cp[k] = MIXED ? as_global<u32x2>(tabs.lowp[row + k] + off) : nullptr;
                 }
-                const uint32_t nvec = n / 4;
+                const uint32_t nvec = (n - head) / 4;
                 for (uint32_t i = tid; i < nvec; i += BLOCK) {
                     f32x4 gv[KM], wv[KM], mv[KM];
 #pragma unroll
@@ -969,7 +996,8 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
             }
         }
         // element-at-a-time: unaligned tensors, ragged tails, and any K without a compiled shape
-        for (uint32_t i = done + tid; i < n; i += BLOCK) {
+        for (uint32_t j = tid; j < n - done; j += BLOCK) {
+            const uint32_t i = j < head ? j : j + done;
             const uint64_t e = ch.off + i;
             float gbar = 0.f;
             if (sync) {

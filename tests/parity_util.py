@@ -75,7 +75,7 @@ class LockStep:
 
     def __init__(self, B, shapes_numel: Sequence[int], K: int, delta: float, window: int = 25, alpha: float = -1.0,
                  mixed: bool = False, init_params: Optional[List[np.ndarray]] = None, misalign: int = 0,
-                 tuning: Optional[dict] = None, seed: int = 0):
+                 tuning: Optional[dict] = None, seed: int = 0, misalign_g: Optional[int] = None):
         self.B, self.K, self.mixed = B, K, mixed
         self.numel = list(shapes_numel)
         if init_params is None:
@@ -99,6 +99,7 @@ class LockStep:
             self.d_c = [[to_dev(a, misalign) for a in self.h_c[k]] for k in range(K)]
             self.d_gc = [to_dev(a, misalign) for a in self.h_gc]
         self.misalign = misalign
+        self.misalign_g = misalign if misalign_g is None else misalign_g     # gradients may sit at another phase
         self.ctx = B.SelSync(K, delta, window, alpha)
         if tuning:
             self.ctx.set_tuning(**tuning)
@@ -115,7 +116,7 @@ class LockStep:
         """grads[k][t]: host arrays (fp32, or bf16 bits in mixed mode)."""
         self.h_grads = getattr(self, "h_grads", {})
         self.h_grads[slot] = grads
-        dg = [[to_dev(a, self.misalign) for a in grads[k]] for k in range(self.K)]
+        dg = [[to_dev(a, self.misalign_g) for a in grads[k]] for k in range(self.K)]
         self.d_grads[slot] = dg
         if self.mixed:
             self.plans[slot] = self.ctx.plan(dg, self.d_c, self.d_m, self.d_glob, master=self.d_w,

@@ -123,6 +123,27 @@ def test_local_step_matches_oracle_over_steps(B, sizes, mixed, misalign):
     ls.close()
 
 
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("phase_w,phase_g", [(0, 1), (2, 0), (1, 3), (3, 3), (2, 2)])
+def test_streams_at_different_address_phases(B, mixed, phase_w, phase_g):
+    # equal phases: head peel + 128-bit body; different phases: the element-wise path.  Same results.
+    numel = [70001, 5, 4096, 2, 1023]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, misalign=phase_w, misalign_g=phase_g, seed=23)
+    r = rng(25)
+    grads = []
+    for k in range(K):
+        gk = [(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel]
+        grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+    ls.bind_grads(0, grads)
+    for t in range(3):
+        ls.step(0, lr=0.1, mu=0.9, wd=5e-4, gs=0.9, fused=(t != 1))      # delta 0: every step also aggregates
+    ls.steps_done = 0
+    ls.step_ga(0, 0.1, 0.9, 5e-4, 0.9)
+    assert ls.worst_ulp == 0
+    ls.close()
+
+
 def test_local_step_lr_zero_is_noop_and_plain_sgd_special_case(B):
     numel = [40000, 17]
     ls = PU.LockStep(B, numel, 1, delta=float("inf"), seed=5)
