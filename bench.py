@@ -42,6 +42,11 @@ def parse_args():
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--agg-chunk-elems", type=int, default=0)
+    ap.add_argument("--ga-chunk-elems", type=int, default=0)
+    ap.add_argument("--stream-shape", type=int, default=0,
+                    help="update/norm kernel shape 10*C + U (C chunks per wavefront, U 128-bit accesses per lane)")
+    ap.add_argument("--table-layout", type=int, default=0, help="0 striped by XCD (default), 1 linear, 2 XCD-contiguous")
     ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga", "adam"],
                     help="pa: fused selsync_step (default, the headline); unfused: the three primitives in Alg. 1 "
                          "order; ga: gradient-aggregation variant (selsync_step_ga); adam: Adam as the local update "
@@ -165,8 +170,11 @@ def main():
     if args.window > 0:
         wl.window = args.window
     ctx = B.SelSync(K, wl.delta, wl.window)
-    if args.chunk_elems or args.blocks_per_cu or args.nontemporal >= 0:
-        ctx.set_tuning(args.chunk_elems, args.blocks_per_cu, args.nontemporal)
+    if (args.chunk_elems or args.blocks_per_cu or args.nontemporal >= 0 or args.agg_chunk_elems or args.ga_chunk_elems
+            or args.stream_shape or args.table_layout):
+        ctx.set_tuning(args.chunk_elems, args.blocks_per_cu, args.nontemporal, args.agg_chunk_elems,
+                       stream_variant=args.stream_shape, ga_chunk_elems=args.ga_chunk_elems,
+                       table_layout=args.table_layout)
     plans = []
     for slot in range(wl.pool):
         if wl.mixed_bf16:

@@ -133,9 +133,16 @@ typedef struct selsync_tuning {
                                   <= 0 (default): one workgroup per chunk                               */
     int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
     int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 1024)        */
-    int32_t stream_variant;    /* workgroup shape of the update/norm kernel: 0 = default (one 64-lane
-                                  wave per 512 elements); 1..12 = other measured shapes               */
-    int32_t xcd_swizzle;       /* 1: each XCD walks a contiguous eighth of the chunk table; 0: off; <0 default */
+    int32_t stream_variant;    /* shape of the update/norm kernel, 10*C + U: each 64-lane wavefront takes C
+                                  chunks at once with U 128-bit accesses per lane, stream and pass.
+                                  One of 11 12 14 21 22 41 42 81; 0 = default (11 for updates, 41 for
+                                  the norm-only pass)                                                    */
+    int32_t xcd_swizzle;       /* aggregation kernels: 1 = each XCD walks a contiguous eighth of the chunk
+                                  table; 0: off; <0 default                                              */
+    int32_t ga_chunk_elems;    /* elements per chunk of the gradient-aggregation update (multiple of 256) */
+    int32_t table_layout;      /* chunk table and partial sums of the update/norm kernel:
+                                  0 (default) striped by XCD, chunks dispatched in model order;
+                                  1 linear; 2 striped, each XCD walks a contiguous eighth of the model   */
 } selsync_tuning;
 
 typedef struct selsync_ctx  selsync_ctx;    /* opaque: tracker state, counters, workspace owner */

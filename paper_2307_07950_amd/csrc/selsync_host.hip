@@ -20,8 +20,9 @@ using namespace selsync;
 
 namespace {
 
-constexpr int kDefaultChunkElems = kTileElems;   // one workgroup pass per chunk: a one-shot grid
+constexpr int kDefaultChunkElems = kChunkGranule;   // one 128-bit access per lane and stream: a one-shot grid
 constexpr int kDefaultXcdSwizzle = 0;
+constexpr int kDefaultGaChunkElems = 1024;
 constexpr int kMaxWorkers = 1024;
 constexpr int kSegChunks = 2048;          // chunks per segment of the intermediate reduction
 constexpr int kDirectChunkLimit = 16384;  // up to this many chunks the tracker sums them directly
@@ -43,7 +44,7 @@ struct selsync_ctx {
     selsync_config cfg;
     int device = 0;
     int num_cus = 256;
-    selsync_tuning tuning{0, 0, -1, 0, 0, -1};
+    selsync_tuning tuning{0, 0, -1, 0, 0, -1, 0, 0};
     // device state: one allocation, sub-pointers in td
     void *d_state = nullptr;
     size_t state_bytes = 0;        // size of the d_state allocation
@@ -69,12 +70,11 @@ struct selsync_plan {
     int64_t P = 0;
     bool mixed = false;
     bool has_grads = false;
-    int n_upd_chunks = 0, n_agg_chunks = 0;
+    int n_upd_chunks = 0, n_agg_chunks = 0, n_ga_chunks = 0;
     void *d_blob = nullptr;        // all tables in one allocation
     TensorRec *d_recs = nullptr;
-    ChunkRec *d_chunks = nullptr;
+    StreamTable tab{};             // chunk table of the streaming kernels and its geometry
     int32_t *d_chunk_begin = nullptr;
-    double *d_partials = nullptr;
     // intermediate reduction level (used when there are many chunks)
     int n_segs = 0;
     int2 *d_segs = nullptr;
@@ -89,7 +89,9 @@ struct selsync_plan {
     std::vector<Interval> ivals;     // every bound buffer (checked again when more buffers are bound)
     bool has_second_moment = false;
     AggChunkRec *d_agg_chunks = nullptr;
+    AggChunkRec *d_ga_chunks = nullptr;   // finer table for the gradient-aggregation update (always does work)
     AggTables agg{};
+    int ga_block = 256;
     LaunchCfg upd_cfg{1, 1, 0};
     LaunchCfg agg_cfg{1, 1, 0};
 
@@ -318,10 +320,11 @@ int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
     plan->partials_valid = true;
     ProfScope p(ctx, 1, s);
     if (plan->n_segs > 0) {
-        HIP_TRY(ctx, launch_reduce(plan->d_partials, plan->d_segs, plan->n_segs, plan->d_seg_sums, s));
-        HIP_TRY(ctx, launch_track(ctx->td, plan->d_seg_sums, plan->d_seg_begin, s));
+        HIP_TRY(ctx, launch_reduce(plan->tab.partials, plan->tab.slot_per, plan->d_segs, plan->n_segs,
+                                   plan->d_seg_sums, s));
+        HIP_TRY(ctx, launch_track(ctx->td, plan->d_seg_sums, 0, plan->d_seg_begin, s));
     } else {
-        HIP_TRY(ctx, launch_track(ctx->td, plan->d_partials, plan->d_chunk_begin, s));
+        HIP_TRY(ctx, launch_track(ctx->td, plan->tab.partials, plan->tab.slot_per, plan->d_chunk_begin, s));
     }
     return SELSYNC_OK;
 }
@@ -511,11 +514,18 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
         return SELSYNC_ERR_INVALID_ARG;
     if (t->chunk_elems > 0 && (t->chunk_elems % kChunkGranule != 0 || t->chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
-    if (t->stream_variant < 0 || t->stream_variant > 12)
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be in 0..12");
+    {
+        static const int shapes[] = {0, 11, 12, 14, 21, 22, 41, 42, 81};
+        if (std::find(std::begin(shapes), std::end(shapes), t->stream_variant) == std::end(shapes))
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be 0 or one of 11 12 14 21 22 41 42 81");
+    }
     if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kAggTileElems != 0 || t->agg_chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_chunk_elems must be a multiple of %d and <= 2^24",
                     kAggTileElems);
+    if (t->ga_chunk_elems > 0 && (t->ga_chunk_elems % kChunkGranule != 0 || t->ga_chunk_elems > (1 << 24)))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "ga_chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
+    if (t->table_layout < 0 || t->table_layout > 2)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "table_layout must be 0, 1 or 2");
     if (t->blocks_per_cu > 64)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "blocks_per_cu must be <= 64");
     ctx->tuning = *t;
@@ -598,13 +608,14 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
 
     const int chunk = effective_chunk(ctx);
     const int agg_chunk = ctx->tuning.agg_chunk_elems > 0 ? ctx->tuning.agg_chunk_elems : default_agg_chunk(K);
+    const int ga_chunk = ctx->tuning.ga_chunk_elems > 0 ? ctx->tuning.ga_chunk_elems : kDefaultGaChunkElems;
     // blocks_per_cu <= 0: one workgroup per chunk (one-shot grid); > 0: a persistent grid of that many per CU
     const int grid_cap = ctx->tuning.blocks_per_cu > 0 ? ctx->num_cus * ctx->tuning.blocks_per_cu : INT_MAX;
     const int nt = ctx->tuning.nontemporal >= 0 ? ctx->tuning.nontemporal : 1;
 
     // ---- host tables
     std::vector<TensorRec> recs;
-    std::vector<ChunkRec> chunks;
+    std::vector<ChunkRec> chunks;     // in chunk order: worker by worker, tensor by tensor
     std::vector<int32_t> chunk_begin(K + 1, 0);
     std::vector<int32_t> tensor_chunk_begin((size_t)K * T + 1, 0);
     if (grads) {
@@ -622,16 +633,17 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
                     r.w = static_cast<float *>(params[k].tensors[t].data);
                     r.lowp = nullptr;
                 }
-                recs[(size_t)k * T + t] = r;
                 tensor_chunk_begin[(size_t)k * T + t] = (int32_t)chunks.size();
                 const int ph = stream_phase(r.w, 4);
                 const bool al = stream_phase(r.g, mixed ? 2 : 4) == ph && stream_phase(r.m, 4) == ph &&
                                 (!mixed || stream_phase(r.lowp, 2) == ph);
-                split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
+                r.numel = numel[t];
+                r.flags = al ? (kChunkAligned | head_bits(ph)) : 0u;
+                recs[(size_t)k * T + t] = r;
+                split_tensor(numel[t], chunk, [&](int64_t off, int64_t) {
                     ChunkRec c;
                     c.rec = (uint32_t)((size_t)k * T + t);
-                    c.n_flags = (uint32_t)n | (al ? (kChunkAligned | head_bits(ph)) : 0u);
-                    c.off = (uint64_t)off;
+                    c.j = (uint32_t)(off / chunk);
                     chunks.push_back(c);
                 });
             }
@@ -639,8 +651,21 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
         chunk_begin[K] = (int32_t)chunks.size();
         tensor_chunk_begin[(size_t)K * T] = (int32_t)chunks.size();
     }
-    if (chunks.size() > (size_t)INT32_MAX)
+    if (chunks.size() > (size_t)INT32_MAX - 8 * kStripeGranule)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan (%zu chunks)", chunks.size());
+
+    // Slot order of the table (and of the partial sums).  Striped layouts hold 8 stripes of `per`
+    // slots, padded with empty slots; workgroup b of the streaming kernel works on stripe b % 8.
+    const int layout = ctx->tuning.table_layout;
+    const int nchunks = (int)chunks.size();
+    int per = 0;
+    if (layout != kLayoutLinear && nchunks > 0)
+        per = (int)align_up((size_t)(nchunks + 7) / 8, kStripeGranule);
+    const int nslots = per > 0 ? 8 * per : nchunks;
+    const int slot_per = layout == kLayoutStriped ? per : 0;
+    std::vector<ChunkRec> slots((size_t)nslots, ChunkRec{kNoChunk, 0u});
+    for (int c = 0; c < nchunks; ++c)
+        slots[(size_t)chunk_slot(c, slot_per)] = chunks[c];
 
     // With many chunks the per-chunk partials first collapse into fixed segments of
     // kSegChunks consecutive chunks (never crossing a worker boundary); the tracker kernel
@@ -656,7 +681,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
         seg_begin[K] = (int32_t)segs.size();
     }
 
-    std::vector<AggChunkRec> agg_chunks;
+    std::vector<AggChunkRec> agg_chunks, ga_chunks;
     std::vector<float *> agg_w((size_t)T * K);
     std::vector<uint16_t *> agg_c(mixed ? (size_t)T * K : 0);
     std::vector<float *> agg_g(T);
@@ -697,7 +722,18 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             c.off = (uint64_t)off;
             agg_chunks.push_back(c);
         });
+        if (grads)
+            split_tensor(numel[t], ga_chunk, [&](int64_t off, int64_t n) {
+                AggChunkRec c;
+                c.t = (uint32_t)t;
+                c.n_flags = (uint32_t)n | (al ? (kChunkAligned | head_bits(ph)) : 0u) |
+                            (al_grads ? kChunkAlignedGrads : 0u);
+                c.off = (uint64_t)off;
+                ga_chunks.push_back(c);
+            });
     }
+    if (agg_chunks.size() > (size_t)INT32_MAX || ga_chunks.size() > (size_t)INT32_MAX)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan");
 
     std::unique_ptr<selsync_plan> plan(new selsync_plan());     // frees its device tables on any early exit
     plan->ctx = ctx;
@@ -709,8 +745,10 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->h_recs = recs;
     plan->numel = numel;
     plan->ivals = ivals;
-    plan->n_upd_chunks = (int)chunks.size();
+    plan->n_upd_chunks = nchunks;
     plan->n_agg_chunks = (int)agg_chunks.size();
+    plan->n_ga_chunks = (int)ga_chunks.size();
+    plan->ga_block = ga_chunk < 1024 ? 64 : 256;     // one-wave workgroups for the fine tables
 
     // ---- one device allocation for every table
     size_t off = 0;
@@ -720,15 +758,16 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
         return o;
     };
     const size_t o_recs = take(recs.size() * sizeof(TensorRec));
-    const size_t o_chunks = take(chunks.size() * sizeof(ChunkRec));
+    const size_t o_chunks = take(slots.size() * sizeof(ChunkRec));
     const size_t o_begin = take(chunk_begin.size() * sizeof(int32_t));
-    const size_t o_part = take(chunks.size() * sizeof(double));
+    const size_t o_part = take(slots.size() * sizeof(double));
     const size_t o_segs = take(segs.size() * sizeof(int2));
     const size_t o_segsum = take(segs.size() * sizeof(double));
     const size_t o_segbegin = take(seg_begin.size() * sizeof(int32_t));
     const size_t o_tcb = take(tensor_chunk_begin.size() * sizeof(int32_t));
     const size_t o_tnorm = take((size_t)K * T * sizeof(double));
     const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
+    const size_t o_gac = take(ga_chunks.size() * sizeof(AggChunkRec));
     const size_t o_aw = take(agg_w.size() * sizeof(float *));
     const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
     const size_t o_ag = take(agg_g.size() * sizeof(float *));
@@ -742,12 +781,13 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             std::memcpy(blob.data() + o, src, bytes);
     };
     put(o_recs, recs.data(), recs.size() * sizeof(TensorRec));
-    put(o_chunks, chunks.data(), chunks.size() * sizeof(ChunkRec));
+    put(o_chunks, slots.data(), slots.size() * sizeof(ChunkRec));
     put(o_begin, chunk_begin.data(), chunk_begin.size() * sizeof(int32_t));
     put(o_segs, segs.data(), segs.size() * sizeof(int2));
     put(o_segbegin, seg_begin.data(), seg_begin.size() * sizeof(int32_t));
     put(o_tcb, tensor_chunk_begin.data(), tensor_chunk_begin.size() * sizeof(int32_t));
     put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
+    put(o_gac, ga_chunks.data(), ga_chunks.size() * sizeof(AggChunkRec));
     put(o_aw, agg_w.data(), agg_w.size() * sizeof(float *));
     put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
     put(o_ag, agg_g.data(), agg_g.size() * sizeof(float *));
@@ -764,9 +804,15 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     }
     char *b = static_cast<char *>(plan->d_blob);
     plan->d_recs = reinterpret_cast<TensorRec *>(b + o_recs);
-    plan->d_chunks = reinterpret_cast<ChunkRec *>(b + o_chunks);
+    plan->tab.recs = plan->d_recs;
+    plan->tab.slots = reinterpret_cast<ChunkRec *>(b + o_chunks);
+    plan->tab.partials = reinterpret_cast<double *>(b + o_part);
+    plan->tab.nchunks = nchunks;
+    plan->tab.nslots = nslots;
+    plan->tab.per = per;
+    plan->tab.slot_per = slot_per;
+    plan->tab.chunk_elems = (uint32_t)chunk;
     plan->d_chunk_begin = reinterpret_cast<int32_t *>(b + o_begin);
-    plan->d_partials = reinterpret_cast<double *>(b + o_part);
     plan->n_segs = (int)segs.size();
     plan->d_segs = reinterpret_cast<int2 *>(b + o_segs);
     plan->d_seg_sums = reinterpret_cast<double *>(b + o_segsum);
@@ -774,6 +820,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->d_tensor_chunk_begin = reinterpret_cast<int32_t *>(b + o_tcb);
     plan->d_tensor_norms = reinterpret_cast<double *>(b + o_tnorm);
     plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
+    plan->d_ga_chunks = reinterpret_cast<AggChunkRec *>(b + o_gac);
     plan->agg.w = reinterpret_cast<float *const *>(b + o_aw);
     plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
     plan->agg.global = reinterpret_cast<float *const *>(b + o_ag);
@@ -864,8 +911,7 @@ extern "C" int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *pla
     SgdArgs a{0.f, 0.f, 0.f, grad_scale, 0};
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
-                                   plan->d_partials, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s));
     }
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
@@ -885,8 +931,7 @@ extern "C" int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, cons
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
-                                   plan->d_partials, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s));
     }
     ctx->local_steps += 1;
     return SELSYNC_OK;
@@ -921,8 +966,7 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
-                                   plan->d_partials, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->tab, a, plan->upd_cfg, s));
     }
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))
@@ -1076,8 +1120,7 @@ extern "C" int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan,
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
-                                        plan->d_partials, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->tab, a, plan->upd_cfg, s));
     }
     ctx->local_steps += 1;
     return SELSYNC_OK;
@@ -1096,8 +1139,7 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream_adam(true, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
-                                        plan->d_partials, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream_adam(true, plan->mixed, plan->tab, a, plan->upd_cfg, s));
     }
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))
@@ -1128,7 +1170,7 @@ extern "C" int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg, plan->K,
                                       &ctx->td.out->sync, mode, a, plan->agg_cfg, s));
     }
     ctx->local_steps += 1;
@@ -1148,14 +1190,13 @@ extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const s
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->d_recs, plan->d_chunks, plan->n_upd_chunks,
-                                   plan->d_partials, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s));
     }
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
     {
         ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg, plan->K,
                                       &ctx->td.out->sync, 0, a, plan->agg_cfg, s));
     }
     ctx->local_steps += 1;
@@ -1191,7 +1232,7 @@ extern "C" int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *pla
     if (n == 0)
         return SELSYNC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(ctx, launch_tensor_norms(plan->d_partials, plan->d_tensor_chunk_begin, n, plan->d_tensor_norms, s));
+    HIP_TRY(ctx, launch_tensor_norms(plan->tab.partials, plan->tab.slot_per, plan->d_tensor_chunk_begin, n, plan->d_tensor_norms, s));
     HIP_TRY(ctx, hipMemcpyAsync(out, plan->d_tensor_norms, sizeof(double) * n, hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
     return SELSYNC_OK;

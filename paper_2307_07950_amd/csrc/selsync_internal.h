@@ -10,22 +10,42 @@ namespace selsync {
 
 // ---- device-visible tables --------------------------------------------------
 
-// Pointers of one (worker k, tensor t) pair; index k*T + t.
-struct TensorRec {
+// One (worker k, tensor t) pair; index k*T + t.  64 bytes, so a record never straddles a
+// cache line and one scalar load fetches it.
+struct alignas(64) TensorRec {
     const void *g;   // gradient (fp32, or bf16 in mixed mode)
     float *w;        // fp32 parameter (mixed mode: fp32 master)
     float *m;        // fp32 momentum buffer
     uint16_t *lowp;  // bf16 working copy (mixed mode only)
     float *v;        // fp32 second-moment buffer (Adam variant only, else null)
+    int64_t numel;   // elements of the tensor
+    uint32_t flags;  // kChunkAligned | head bits (same meaning as in AggChunkRec::n_flags)
+    uint32_t pad_;
 };
 
-// One unit of work of the multi-tensor streaming kernel: `n` consecutive elements
-// of one tensor of one worker, starting at element `off`.
+// One unit of work of the multi-tensor streaming kernel: chunk j of one tensor of one
+// worker, i.e. elements [j*chunk_elems, min((j+1)*chunk_elems, numel)).  8 bytes: at 256
+// elements per chunk the table is 1/128 of one fp32 stream.
 struct ChunkRec {
-    uint32_t rec;      // index into the TensorRec table
-    uint32_t n_flags;  // bits 0..27: element count; bit 31: all pointers 16-byte aligned
-    uint64_t off;      // first element
+    uint32_t rec;   // index into the TensorRec table; kNoChunk marks a padding slot
+    uint32_t j;     // chunk index inside the tensor
 };
+constexpr uint32_t kNoChunk = 0xffffffffu;
+
+// Where chunk c's table record and partial sum live.  Workgroups of a launch go to the 8
+// XCDs (each with its own L2) round-robin by workgroup id.  In the striped layout the slots
+// are stored as 8 stripes of `per` slots and workgroup b works on stripe b % 8, so the
+// records and partial sums of one XCD's workgroups are contiguous in memory: every table
+// line is fetched by one L2 instead of eight, every line of partial sums is written by one.
+//   layout 0 (striped, chunk order = dispatch order): chunk c sits in slot (c%8)*per + c/8
+//   layout 1 (linear):                                slot c, workgroup b takes slots b*C..
+//   layout 2 (striped slots, chunks stored linearly): slot c; XCD x walks chunks [x*per, (x+1)*per)
+enum TableLayout { kLayoutStriped = 0, kLayoutLinear = 1, kLayoutXcdContiguous = 2 };
+
+__host__ __device__ inline int64_t chunk_slot(int64_t c, int per_if_striped)
+{
+    return per_if_striped > 0 ? (c & 7) * (int64_t)per_if_striped + (c >> 3) : c;
+}
 
 // One unit of work of the aggregation kernel: `n` consecutive elements of tensor t
 // across all K replicas.
@@ -97,8 +117,20 @@ struct SgdArgs {
 struct LaunchCfg {
     int grid;
     int nontemporal;
-    int variant = 0;   // workgroup shape of the streaming kernel
-    int xcd_swizzle = 0;   // 1: XCD-aware workgroup -> chunk mapping
+    int variant = 0;       // streaming kernel: 10*C + U (C chunks per wave, U vectors per lane and tile); 0 = default
+    int xcd_swizzle = 0;   // aggregation kernels: 1 = XCD-aware workgroup -> chunk mapping
+};
+
+// Geometry of a plan's chunk table (see TableLayout).
+struct StreamTable {
+    const TensorRec *recs = nullptr;
+    const ChunkRec *slots = nullptr;
+    double *partials = nullptr;    // one per slot
+    int nchunks = 0;               // real chunks
+    int nslots = 0;                // table entries including padding
+    int per = 0;                   // slots per stripe; 0 in the linear layout
+    int slot_per = 0;              // `per` for chunk_slot(): > 0 only when chunks are stored striped (layout 0)
+    uint32_t chunk_elems = 0;
 };
 
 enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };
@@ -127,36 +159,40 @@ __host__ __device__ inline int64_t partition_index(int64_t D, int64_t N, int64_t
 
 // ---- launchers (selsync_kernels.hip) --------------------------------------------
 
-// Elements one workgroup pass of the default streaming kernel shape covers: one
-// wavefront x 2 groups of 4 elements per lane (128-bit per fp32 stream, 64-bit per bf16 stream).
-constexpr int kTileElems = 512;
-// Chunk sizes must be a multiple of this (the smallest workgroup shape's tile).
+// Chunk sizes are a multiple of this: one wavefront x one group of 4 elements per lane
+// (128 bits per fp32 stream, 64 bits per bf16 stream).
 constexpr int kChunkGranule = 256;
+// Stripes are padded to a multiple of this many slots (the largest chunks-per-wave count).
+constexpr int kStripeGranule = 16;
 // Smallest aggregation tile: 256 threads x one 128-bit vector.
 constexpr int kAggTileElems = 1024;
 
-hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                         double *partials, const SgdArgs &sgd, const LaunchCfg &cfg, hipStream_t s);
-
-// Sums partials[segs[j].x .. segs[j].y) into seg_sums[j], one workgroup per segment.
-hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s);
+hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
+                         hipStream_t s);
 
 // Adam variant of the streaming kernel: update (+ norm partials when with_norm).
-hipError_t launch_stream_adam(bool with_norm, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                              double *partials, const AdamArgs &a, const LaunchCfg &cfg, hipStream_t s);
+hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a,
+                              const LaunchCfg &cfg, hipStream_t s);
 
-hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s);
+// Sums the partials of chunks segs[j].x .. segs[j].y - 1 into seg_sums[j], one workgroup per
+// segment.  slot_per: see chunk_slot().
+hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs, int nsegs, double *seg_sums,
+                         hipStream_t s);
+
+// values[begin[k] .. begin[k+1]) are worker k's partial sums: per-chunk ones (looked up through
+// chunk_slot(., slot_per)) or per-segment ones (slot_per = 0).
+hipError_t launch_track(const TrackerDev &td, const double *values, int slot_per, const int32_t *begin, hipStream_t s);
 
 hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
                             const int32_t *sync_flag, int mode, const LaunchCfg &cfg, hipStream_t s);
 
-// out[i] = sum of partials[range_begin[i] .. range_begin[i+1]), one workgroup per range.
-hipError_t launch_tensor_norms(const double *partials, const int32_t *range_begin, int nranges, double *out,
-                               hipStream_t s);
+// out[i] = sum of the partials of chunks range_begin[i] .. range_begin[i+1] - 1, one workgroup per range.
+hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32_t *range_begin, int nranges,
+                               double *out, hipStream_t s);
 
 // Gradient-aggregation update (Sec. III-C): when the decision is "sync" (or mode 1) every worker
 // applies the mean gradient to its own parameters and momentum, otherwise its own gradient.
-hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
+hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
                             const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
                             hipStream_t s);
 

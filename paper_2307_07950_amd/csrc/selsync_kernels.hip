@@ -104,392 +104,297 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
-// One element of the fused pass.  gh = fl(gs*g); x += gh^2 in fp64 (the product of two
-// fp32 values is exact in fp64); d = fl(gh + fl(wd*w)); m = first ? d : fl(fl(mu*m) + d);
-// w = fl(w - fl(lr*m)).
-template <bool UPD, bool NORM>
-__device__ __forceinline__ void elem(float g, float &w, float &m, const SgdArgs &a, double &acc)
-{
-    const float gh = a.gs * g;
-    if (NORM)
-        acc = __builtin_fma((double)gh, (double)gh, acc);
-    if (UPD) {
-        const float dec = a.wd * w;
-        const float d = gh + dec;
-        float mom = d;
-        if (!a.first) {
-            const float mm = a.mu * m;
-            mom = mm + d;
+// ---------------------------------------------------------------- optimiser policies
+
+// Local SGD with momentum and weight decay (Alg. 1 line 9), one rounding per operation:
+//   gh = fl(gs*g); x += gh^2 in fp64 (the product of two fp32 values is exact in fp64);
+//   d = fl(gh + fl(wd*w)); m = first ? d : fl(fl(mu*m) + d); w = fl(w - fl(lr*m)).
+struct SgdOpt {
+    typedef SgdArgs Args;
+    static constexpr bool kSecondMoment = false;
+    template <bool UPD, bool NORM>
+    static __device__ __forceinline__ void elem(float g, float &w, float &m, float &, const Args &a, double &acc)
+    {
+        const float gh = a.gs * g;
+        if (NORM)
+            acc = __builtin_fma((double)gh, (double)gh, acc);
+        if (UPD) {
+            const float dec = a.wd * w;
+            const float d = gh + dec;
+            float mom = d;
+            if (!a.first) {
+                const float mm = a.mu * m;
+                mom = mm + d;
+            }
+            const float stepv = a.lr * mom;
+            m = mom;
+            w = w - stepv;
         }
-        const float stepv = a.lr * mom;
-        m = mom;
-        w = w - stepv;
     }
-}
+};
+
+// Adam (optimiser of the AlexNet recipe, Sec. IV-A), fp32, one rounding per operation;
+// division and square root are the correctly rounded ones:
+//   gh = gs*g; gd = gh + wd*w; m = b1*m + omb1*gd; v = b2*v + (omb2*gd)*gd;
+//   w = w - (lr*(m/bc1)) / (sqrt(v/bc2) + eps)
+// On the first step the moment buffers are not read (taken as zero).
+struct AdamOpt {
+    typedef AdamArgs Args;
+    static constexpr bool kSecondMoment = true;
+    template <bool UPD, bool NORM>
+    static __device__ __forceinline__ void elem(float g, float &w, float &m, float &v, const Args &a, double &acc)
+    {
+        const float gh = a.gs * g;
+        if (NORM)
+            acc = __builtin_fma((double)gh, (double)gh, acc);
+        const float dec = a.wd * w;
+        const float gd = gh + dec;
+        const float t1 = a.b1 * m;
+        const float t2 = a.omb1 * gd;
+        const float mn = t1 + t2;
+        const float t3 = a.b2 * v;
+        const float t4 = a.omb2 * gd;
+        const float t5 = t4 * gd;
+        const float vn = t3 + t5;
+        const float mh = mn / a.bc1;
+        const float vh = vn / a.bc2;
+        const float num = a.lr * mh;
+        const float den = __builtin_sqrtf(vh) + a.eps;
+        const float q = num / den;
+        m = mn;
+        v = vn;
+        w = w - q;
+    }
+};
 
 // Four consecutive elements held in 128-bit registers.
-template <bool UPD, bool NORM>
-__device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, const SgdArgs &a, double &acc)
+template <class OPT, bool UPD, bool NORM>
+__device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, f32x4 &v, const typename OPT::Args &a,
+                                      double &acc)
 {
     float w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
     float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
-    elem<UPD, NORM>(g.x, w0, m0, a, acc);
-    elem<UPD, NORM>(g.y, w1, m1, a, acc);
-    elem<UPD, NORM>(g.z, w2, m2, a, acc);
-    elem<UPD, NORM>(g.w, w3, m3, a, acc);
+    float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
+    OPT::template elem<UPD, NORM>(g.x, w0, m0, v0, a, acc);
+    OPT::template elem<UPD, NORM>(g.y, w1, m1, v1, a, acc);
+    OPT::template elem<UPD, NORM>(g.z, w2, m2, v2, a, acc);
+    OPT::template elem<UPD, NORM>(g.w, w3, m3, v3, a, acc);
     w.x = w0; w.y = w1; w.z = w2; w.w = w3;
     m.x = m0; m.y = m1; m.z = m2; m.w = m3;
+    v.x = v0; v.y = v1; v.z = v2; v.w = v3;
+}
+
+// SGD forms without a second-moment operand (used by the gradient-aggregation update).
+template <bool UPD, bool NORM>
+__device__ __forceinline__ void elem(float g, float &w, float &m, const SgdArgs &a, double &acc)
+{
+    float unused = 0.f;
+    SgdOpt::elem<UPD, NORM>(g, w, m, unused, a, acc);
+}
+
+template <bool UPD, bool NORM>
+__device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, const SgdArgs &a, double &acc)
+{
+    f32x4 unused = 0.f;
+    elem4<SgdOpt, UPD, NORM>(g, w, m, unused, a, acc);
 }
 
 // ---------------------------------------------------------------- k_stream
 
-// One tile of BLOCK*U vectors of an aligned fp32 chunk.
-template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
-__device__ __forceinline__ void tile_f32(const SELSYNC_GLOBAL f32x4 *__restrict__ g4,
-                                         SELSYNC_GLOBAL f32x4 *__restrict__ w4,
-                                         SELSYNC_GLOBAL f32x4 *__restrict__ m4, uint32_t base, uint32_t nvec,
-                                         uint32_t tid, const SgdArgs &a, double &acc)
+// What a wavefront knows about one chunk (all of it wave-uniform, i.e. in scalar registers).
+// An aligned chunk is `head` single elements, `nvec` groups of 4 elements starting at element
+// off + head (every stream vector-aligned there), and a ragged tail; an unaligned one has
+// nvec = 0 and is walked element by element.  n = 0 marks a padding slot.
+struct Chunk {
+    TensorRec r;
+    uint64_t off;
+    uint32_t n, head, nvec;
+};
+
+__device__ __forceinline__ Chunk lookup_chunk(const TensorRec *__restrict__ recs, const ChunkRec *__restrict__ slots,
+                                              int slot, int nslots, uint32_t chunk_elems)
 {
-    f32x4 gv[U], wv[U], mv[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * BLOCK + tid;
-        gv[u] = 0.f;
-        wv[u] = 0.f;
-        mv[u] = 0.f;
-        if (!GUARD || i < nvec) {
-            gv[u] = ld<NT>(g4 + i);
-            if (UPD) {
-                wv[u] = ld<NT>(w4 + i);
-                if (!a.first)
-                    mv[u] = ld<NT>(m4 + i);
-            }
-        }
+    Chunk ck;
+    ChunkRec cr;
+    cr.rec = kNoChunk;
+    cr.j = 0;
+    if (slot < nslots)
+        cr = slots[slot];
+    const bool real = cr.rec != kNoChunk;
+    ck.r = recs[real ? cr.rec : 0u];
+    ck.off = (uint64_t)cr.j * chunk_elems;
+    const uint64_t rest = real ? (uint64_t)ck.r.numel - ck.off : 0u;
+    ck.n = rest < chunk_elems ? (uint32_t)rest : chunk_elems;
+    ck.head = 0;
+    ck.nvec = 0;
+    if (ck.r.flags & kChunkAligned) {
+        const uint32_t h = (ck.r.flags >> kChunkHeadShift) & 3u;
+        ck.head = h < ck.n ? h : ck.n;
+        ck.nvec = (ck.n - ck.head) / 4;
     }
+    return ck;
+}
+
+// 128-bit registers of one tile: U groups of 4 elements per lane and stream.
+template <int U>
+struct TileRegs {
+    f32x4 g[U], w[U], m[U], v[U];
+};
+
+// Issue the loads of tile [base, base + 64*U) of the chunk's vector body.  Every stream is read
+// with consecutive lanes on consecutive addresses (bf16 gradients: 8 bytes per lane).
+template <class OPT, int U, bool MIXED, bool UPD, bool NT>
+__device__ __forceinline__ void load_tile(const Chunk &ck, uint32_t base, uint32_t tid, int first, TileRegs<U> &t)
+{
+    const uint64_t e0 = ck.off + ck.head;
+    const SELSYNC_GLOBAL f32x4 *g4 = as_global<const f32x4>(reinterpret_cast<const float *>(ck.r.g) + e0);
+    const SELSYNC_GLOBAL u32x2 *gb4 = as_global<const u32x2>(reinterpret_cast<const uint16_t *>(ck.r.g) + e0);
+    const SELSYNC_GLOBAL f32x4 *w4 = as_global<const f32x4>(ck.r.w + e0);
+    const SELSYNC_GLOBAL f32x4 *m4 = as_global<const f32x4>(ck.r.m + e0);
+    const SELSYNC_GLOBAL f32x4 *v4 = as_global<const f32x4>(ck.r.v + e0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * BLOCK + tid;
-        if (!GUARD || i < nvec) {
-            elem4<UPD, NORM>(gv[u], wv[u], mv[u], a, acc);
+        const uint32_t i = base + u * 64 + tid;
+        t.g[u] = 0.f;
+        t.w[u] = 0.f;
+        t.m[u] = 0.f;
+        t.v[u] = 0.f;
+        if (i < ck.nvec) {
+            if (MIXED)
+                t.g[u] = widen4(ld<NT>(gb4 + i));
+            else
+                t.g[u] = ld<NT>(g4 + i);
             if (UPD) {
-                st<NT>(w4 + i, wv[u]);
-                st<NT>(m4 + i, mv[u]);
+                t.w[u] = ld<NT>(w4 + i);
+                if (!first) {
+                    t.m[u] = ld<NT>(m4 + i);
+                    if (OPT::kSecondMoment)
+                        t.v[u] = ld<NT>(v4 + i);
+                }
             }
         }
     }
 }
 
-// One tile of BLOCK*U groups of 4 elements of an aligned mixed-precision chunk: 4 bf16
-// gradients (8 B), 4 fp32 masters and 4 fp32 momenta (16 B each), 4 bf16 copies out (8 B).
-// Every stream is read and written with consecutive lanes on consecutive addresses.
-template <int BLOCK, int U, bool UPD, bool NORM, bool NT, bool GUARD>
-__device__ __forceinline__ void tile_mixed(const SELSYNC_GLOBAL u32x2 *__restrict__ g4,
-                                           SELSYNC_GLOBAL f32x4 *__restrict__ w4,
-                                           SELSYNC_GLOBAL f32x4 *__restrict__ m4,
-                                           SELSYNC_GLOBAL u32x2 *__restrict__ c4, uint32_t base, uint32_t nvec,
-                                           uint32_t tid, const SgdArgs &a, double &acc)
+// Arithmetic and stores of the tile loaded by load_tile.
+template <class OPT, int U, bool MIXED, bool UPD, bool NORM, bool NT>
+__device__ __forceinline__ void finish_tile(const Chunk &ck, uint32_t base, uint32_t tid, const typename OPT::Args &a,
+                                            TileRegs<U> &t, double &acc)
 {
-    u32x2 gv[U];
-    f32x4 wv[U], mv[U];
+    const uint64_t e0 = ck.off + ck.head;
+    SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(ck.r.w + e0);
+    SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(ck.r.m + e0);
+    SELSYNC_GLOBAL f32x4 *v4 = as_global<f32x4>(ck.r.v + e0);
+    SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(ck.r.lowp + e0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * BLOCK + tid;
-        gv[u] = 0u;
-        wv[u] = 0.f;
-        mv[u] = 0.f;
-        if (!GUARD || i < nvec) {
-            gv[u] = ld<NT>(g4 + i);
+        const uint32_t i = base + u * 64 + tid;
+        if (i < ck.nvec) {
+            elem4<OPT, UPD, NORM>(t.g[u], t.w[u], t.m[u], t.v[u], a, acc);
             if (UPD) {
-                wv[u] = ld<NT>(w4 + i);
-                if (!a.first)
-                    mv[u] = ld<NT>(m4 + i);
-            }
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * BLOCK + tid;
-        if (!GUARD || i < nvec) {
-            f32x4 g;
-            g.x = bf16_lo(gv[u].x);
-            g.y = bf16_hi(gv[u].x);
-            g.z = bf16_lo(gv[u].y);
-            g.w = bf16_hi(gv[u].y);
-            elem4<UPD, NORM>(g, wv[u], mv[u], a, acc);
-            if (UPD) {
-                st<NT>(w4 + i, wv[u]);
-                st<NT>(m4 + i, mv[u]);
-                u32x2 cv;
-                cv.x = bf16_pack(wv[u].x, wv[u].y);
-                cv.y = bf16_pack(wv[u].z, wv[u].w);
-                st<NT>(c4 + i, cv);
+                st<NT>(w4 + i, t.w[u]);
+                st<NT>(m4 + i, t.m[u]);
+                if (OPT::kSecondMoment)
+                    st<NT>(v4 + i, t.v[u]);
+                if (MIXED) {
+                    u32x2 cv;
+                    cv.x = bf16_pack(t.w[u].x, t.w[u].y);
+                    cv.y = bf16_pack(t.w[u].z, t.w[u].w);
+                    st<NT>(c4 + i, cv);
+                }
             }
         }
     }
 }
 
-// Element-at-a-time processing of elements [begin, n) of a chunk (unaligned tensors
-// and the ragged tail of aligned ones).  Still coalesced: lane i takes element i.
-template <int BLOCK, bool MIXED, bool UPD, bool NORM>
-__device__ __forceinline__ void scalar_range(const TensorRec &r, uint64_t off, uint32_t begin, uint32_t n,
-                                             uint32_t tid, const SgdArgs &a, double &acc)
+// Elements [begin, end) of a chunk one at a time (peeled head, ragged tail, or all of an
+// unaligned chunk).  Still coalesced: lane i takes element begin + i.
+template <class OPT, bool MIXED, bool UPD, bool NORM>
+__device__ __forceinline__ void scalar_range(const Chunk &ck, uint32_t begin, uint32_t end, uint32_t tid,
+                                             const typename OPT::Args &a, double &acc)
 {
-    const SELSYNC_GLOBAL float *gf = as_global<const float>(r.g);
-    const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(r.g);
-    SELSYNC_GLOBAL float *wp = as_global<float>(r.w);
-    SELSYNC_GLOBAL float *mp = as_global<float>(r.m);
-    SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(r.lowp);
-    for (uint32_t i = begin + tid; i < n; i += BLOCK) {
-        const uint64_t e = off + i;
+    const SELSYNC_GLOBAL float *gf = as_global<const float>(ck.r.g);
+    const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(ck.r.g);
+    SELSYNC_GLOBAL float *wp = as_global<float>(ck.r.w);
+    SELSYNC_GLOBAL float *mp = as_global<float>(ck.r.m);
+    SELSYNC_GLOBAL float *vp = as_global<float>(ck.r.v);
+    SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(ck.r.lowp);
+    for (uint32_t i = begin + tid; i < end; i += 64) {
+        const uint64_t e = ck.off + i;
         float g;
         if (MIXED)
             g = __uint_as_float(((uint32_t)gh[e]) << 16);
         else
             g = gf[e];
-        float w = 0.f, m = 0.f;
+        float w = 0.f, m = 0.f, v = 0.f;
         if (UPD) {
             w = wp[e];
-            if (!a.first)
+            if (!a.first) {
                 m = mp[e];
+                if (OPT::kSecondMoment)
+                    v = vp[e];
+            }
         }
-        elem<UPD, NORM>(g, w, m, a, acc);
+        OPT::template elem<UPD, NORM>(g, w, m, v, a, acc);
         if (UPD) {
             wp[e] = w;
             mp[e] = m;
+            if (OPT::kSecondMoment)
+                vp[e] = v;
             if (MIXED)
                 cp[e] = (uint16_t)bf16_bits(w);
         }
     }
 }
 
-// WPB > 1 packs that many independent single-wave units (BLOCK must be 64) into one workgroup:
-// same memory behaviour per wave, fewer workgroups for the dispatcher.
-template <int BLOCK, int U, bool MIXED, int MODE, bool NT, int WPB = 1>
-__global__ __launch_bounds__(BLOCK *WPB) void k_stream(const TensorRec *__restrict__ recs,
-                                                       const ChunkRec *__restrict__ chunks, int nchunks,
-                                                       double *__restrict__ partials, SgdArgs a, int xcd_per)
+// Multi-tensor streaming kernel.  Workgroups are single wavefronts (no LDS, no barrier); a
+// wavefront takes C table slots that are adjacent in memory, issues the first-tile loads of
+// all C chunks before it uses any of them, updates and stores, then (only for chunks larger
+// than one tile) walks the remaining tiles.  Per chunk it leaves one fp64 partial sum of
+// squared scaled gradients in that chunk's slot: fixed place, fixed order, no atomics.
+//   per > 0: striped table, workgroup b takes slots (b%8)*per + (b/8)*C + [0, C)
+//   per = 0: linear table, workgroup b takes slots b*C + [0, C)
+template <class OPT, int U, int C, bool MIXED, int MODE, bool NT>
+__global__ __launch_bounds__(64) void k_stream(const TensorRec *__restrict__ recs, const ChunkRec *__restrict__ slots,
+                                               int nslots, int nwg, int per, uint32_t chunk_elems,
+                                               double *__restrict__ partials, typename OPT::Args a)
 {
-    static_assert(WPB == 1 || BLOCK == 64, "wave packing needs single-wave units");
     constexpr bool UPD = MODE != kNormOnly;
     constexpr bool NORM = MODE != kUpdateOnly;
-    constexpr uint32_t VEC = 4;
-    __shared__ double red[BLOCK / 64];
-    const uint32_t tid = WPB > 1 ? (threadIdx.x & 63u) : threadIdx.x;
-    const int unit0 = WPB > 1 ? (int)(blockIdx.x * WPB + (threadIdx.x >> 6)) : (int)blockIdx.x;
-    const int unit_stride = (int)gridDim.x * WPB;
-
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    for (int v = unit0; v < vtotal; v += unit_stride) {
-        const int c = chunk_of_workgroup(v, xcd_per);
-        if (c >= nchunks)
-            continue;
-        const ChunkRec ch = chunks[c];
-        const TensorRec r = recs[ch.rec];
-        const uint32_t n = ch.n_flags & kChunkCountMask;
-        double acc = 0.0;
-
-        if (ch.n_flags & kChunkAligned) {
-            // all streams share one phase relative to 16-byte alignment: peel `head` elements,
-            // run 128-bit vectors over the aligned body, finish the ragged tail element-wise
-            const uint32_t head = chunk_head(ch.n_flags, n);
-            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, head, tid, a, acc);
-            const uint64_t off = ch.off + head;
-            const uint32_t nb = n - head;
-            const uint32_t nvec = nb / VEC;
-            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + off);
-            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + off);
-            if (MIXED) {
-                const SELSYNC_GLOBAL u32x2 *g4 =
-                    as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + off);
-                SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + off);
-                uint32_t base = 0;
-                for (; base + BLOCK * U <= nvec; base += BLOCK * U)
-                    tile_mixed<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, c4, base, nvec, tid, a, acc);
-                if (base < nvec)
-                    tile_mixed<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, c4, base, nvec, tid, a, acc);
-            } else {
-                const SELSYNC_GLOBAL f32x4 *g4 =
-                    as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + off);
-                uint32_t base = 0;
-                for (; base + BLOCK * U <= nvec; base += BLOCK * U)
-                    tile_f32<BLOCK, U, UPD, NORM, NT, false>(g4, w4, m4, base, nvec, tid, a, acc);
-                if (base < nvec)
-                    tile_f32<BLOCK, U, UPD, NORM, NT, true>(g4, w4, m4, base, nvec, tid, a, acc);
-            }
-            scalar_range<BLOCK, MIXED, UPD, NORM>(r, off, nvec * VEC, nb, tid, a, acc);
-        } else {
-            scalar_range<BLOCK, MIXED, UPD, NORM>(r, ch.off, 0, n, tid, a, acc);
-        }
-
-        if (NORM) {
-            // wavefront shuffle first; a multi-wave workgroup then combines its waves
-            // through LDS in wave order.  Either way: one fixed slot per chunk.
-            const double s = wave_sum(acc);
-            if constexpr (BLOCK == 64) {
-                if (tid == 0)
-                    partials[c] = s;
-            } else {
-                if ((threadIdx.x & 63) == 0)
-                    red[threadIdx.x >> 6] = s;
-                __syncthreads();
-                if (threadIdx.x == 0) {
-                    double t = 0.0;
-#pragma unroll
-                    for (int w = 0; w < BLOCK / 64; ++w)
-                        t += red[w];
-                    partials[c] = t;
-                }
-                __syncthreads();
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------- k_stream_adam
-
-// One element of the Adam variant (optimiser of the AlexNet recipe, Sec. IV-A), fp32, one
-// rounding per operation; division and square root are the correctly rounded ones:
-//   gh = gs*g; gd = gh + wd*w; m = b1*m + omb1*gd; v = b2*v + (omb2*gd)*gd;
-//   w = w - (lr*(m/bc1)) / (sqrt(v/bc2) + eps)
-template <bool NORM>
-__device__ __forceinline__ void elem_adam(float g, float &w, float &m, float &v, const AdamArgs &a, double &acc)
-{
-    const float gh = a.gs * g;
-    if (NORM)
-        acc = __builtin_fma((double)gh, (double)gh, acc);
-    const float dec = a.wd * w;
-    const float gd = gh + dec;
-    const float t1 = a.b1 * m;
-    const float t2 = a.omb1 * gd;
-    const float mn = t1 + t2;
-    const float t3 = a.b2 * v;
-    const float t4 = a.omb2 * gd;
-    const float t5 = t4 * gd;
-    const float vn = t3 + t5;
-    const float mh = mn / a.bc1;
-    const float vh = vn / a.bc2;
-    const float num = a.lr * mh;
-    const float den = __builtin_sqrtf(vh) + a.eps;
-    const float q = num / den;
-    m = mn;
-    v = vn;
-    w = w - q;
-}
-
-template <bool NORM>
-__device__ __forceinline__ void elem4_adam(const f32x4 &g, f32x4 &w, f32x4 &m, f32x4 &v, const AdamArgs &a,
-                                           double &acc)
-{
-    float w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
-    float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
-    float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
-    elem_adam<NORM>(g.x, w0, m0, v0, a, acc);
-    elem_adam<NORM>(g.y, w1, m1, v1, a, acc);
-    elem_adam<NORM>(g.z, w2, m2, v2, a, acc);
-    elem_adam<NORM>(g.w, w3, m3, v3, a, acc);
-    w.x = w0; w.y = w1; w.z = w2; w.w = w3;
-    m.x = m0; m.y = m1; m.z = m2; m.w = m3;
-    v.x = v0; v.y = v1; v.z = v2; v.w = v3;
-}
-
-// Same chunk table, same one-wave workgroup shape as k_stream; four streams read (g, w, m, v),
-// three written (w, m, v) plus the bf16 copy in mixed mode: 28 algorithmic bytes per element.
-template <int BLOCK, int U, bool MIXED, bool NORM>
-__global__ __launch_bounds__(BLOCK) void k_stream_adam(const TensorRec *__restrict__ recs,
-                                                       const ChunkRec *__restrict__ chunks, int nchunks,
-                                                       double *__restrict__ partials, AdamArgs a, int xcd_per)
-{
-    static_assert(BLOCK == 64, "single-wave workgroups only");
     const uint32_t tid = threadIdx.x;
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    for (int vv = blockIdx.x; vv < vtotal; vv += gridDim.x) {
-        const int c = chunk_of_workgroup(vv, xcd_per);
-        if (c >= nchunks)
-            continue;
-        const ChunkRec ch = chunks[c];
-        const TensorRec r = recs[ch.rec];
-        const uint32_t n = ch.n_flags & kChunkCountMask;
-        double acc = 0.0;
-        uint32_t done = 0;
-        uint32_t head = 0;
-        if (ch.n_flags & kChunkAligned) {
-            head = chunk_head(ch.n_flags, n);
-            const uint64_t off = ch.off + head;
-            const uint32_t nvec = (n - head) / 4;
-            SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(r.w + off);
-            SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(r.m + off);
-            SELSYNC_GLOBAL f32x4 *v4 = as_global<f32x4>(r.v + off);
-            const SELSYNC_GLOBAL f32x4 *g4 = as_global<const f32x4>(reinterpret_cast<const float *>(r.g) + off);
-            const SELSYNC_GLOBAL u32x2 *gb4 = as_global<const u32x2>(reinterpret_cast<const uint16_t *>(r.g) + off);
-            SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(r.lowp + off);
-            for (uint32_t base = 0; base < nvec; base += BLOCK * U) {
-                f32x4 gv[U], wv[U], mv[U], vv4[U];
+
+    for (int b = blockIdx.x; b < nwg; b += gridDim.x) {
+        const int s0 = per > 0 ? (b & 7) * per + (b >> 3) * C : b * C;
+        Chunk ck[C];
+        TileRegs<U> t[C];
+        double acc[C];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t i = base + u * BLOCK + tid;
-                    gv[u] = 0.f;
-                    wv[u] = 0.f;
-                    mv[u] = 0.f;
-                    vv4[u] = 0.f;
-                    if (i < nvec) {
-                        if (MIXED)
-                            gv[u] = widen4(ld<true>(gb4 + i));
-                        else
-                            gv[u] = ld<true>(g4 + i);
-                        wv[u] = ld<true>(w4 + i);
-                        if (!a.first) {
-                            mv[u] = ld<true>(m4 + i);
-                            vv4[u] = ld<true>(v4 + i);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t i = base + u * BLOCK + tid;
-                    if (i < nvec) {
-                        elem4_adam<NORM>(gv[u], wv[u], mv[u], vv4[u], a, acc);
-                        st<true>(w4 + i, wv[u]);
-                        st<true>(m4 + i, mv[u]);
-                        st<true>(v4 + i, vv4[u]);
-                        if (MIXED) {
-                            u32x2 cv;
-                            cv.x = bf16_pack(wv[u].x, wv[u].y);
-                            cv.y = bf16_pack(wv[u].z, wv[u].w);
-                            st<true>(c4 + i, cv);
-                        }
-                    }
-                }
-            }
-            done = nvec * 4;
+        for (int i = 0; i < C; ++i) {
+            ck[i] = lookup_chunk(recs, slots, s0 + i, nslots, chunk_elems);
+            acc[i] = 0.0;
         }
-        {
-            // element-wise: the peeled head, the ragged tail, or the whole chunk when unaligned
-            const SELSYNC_GLOBAL float *gf = as_global<const float>(r.g);
-            const SELSYNC_GLOBAL uint16_t *gh = as_global<const uint16_t>(r.g);
-            SELSYNC_GLOBAL float *wp = as_global<float>(r.w);
-            SELSYNC_GLOBAL float *mp = as_global<float>(r.m);
-            SELSYNC_GLOBAL float *vp = as_global<float>(r.v);
-            SELSYNC_GLOBAL uint16_t *cp = as_global<uint16_t>(r.lowp);
-            const uint32_t rest = n - head - done;          // elements after the vector body
-            for (uint32_t j = tid; j < head + rest; j += BLOCK) {
-                const uint32_t i = j < head ? j : j + done;
-                const uint64_t e = ch.off + i;
-                const float g = MIXED ? __uint_as_float(((uint32_t)gh[e]) << 16) : gf[e];
-                float w = wp[e];
-                float m = a.first ? 0.f : mp[e];
-                float v = a.first ? 0.f : vp[e];
-                elem_adam<NORM>(g, w, m, v, a, acc);
-                wp[e] = w;
-                mp[e] = m;
-                vp[e] = v;
-                if (MIXED)
-                    cp[e] = (uint16_t)bf16_bits(w);
+#pragma unroll
+        for (int i = 0; i < C; ++i)
+            load_tile<OPT, U, MIXED, UPD, NT>(ck[i], 0, tid, a.first, t[i]);
+#pragma unroll
+        for (int i = 0; i < C; ++i)
+            finish_tile<OPT, U, MIXED, UPD, NORM, NT>(ck[i], 0, tid, a, t[i], acc[i]);
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            for (uint32_t base = 64 * U; base < ck[i].nvec; base += 64 * U) {
+                load_tile<OPT, U, MIXED, UPD, NT>(ck[i], base, tid, a.first, t[i]);
+                finish_tile<OPT, U, MIXED, UPD, NORM, NT>(ck[i], base, tid, a, t[i], acc[i]);
             }
+            scalar_range<OPT, MIXED, UPD, NORM>(ck[i], 0, ck[i].head, tid, a, acc[i]);
+            scalar_range<OPT, MIXED, UPD, NORM>(ck[i], ck[i].head + 4 * ck[i].nvec, ck[i].n, tid, a, acc[i]);
         }
         if (NORM) {
-            const double s = wave_sum(acc);
-            if (tid == 0)
-                partials[c] = s;
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                const double s = wave_sum(acc[i]);
+                if (tid == 0 && ck[i].n > 0)
+                    partials[s0 + i] = s;
+            }
         }
     }
 }
@@ -500,9 +405,10 @@ constexpr int kReduceBlock = 256;
 
 // Intermediate level of the deterministic norm reduction: workgroup j sums the per-chunk
 // partials of segment j (a fixed range inside one worker's chunks) and writes one value.
-// Sum of partials[b, e) by one workgroup, fixed order: thread-strided accumulation with 8
+// Sum of the partials of chunks b .. e-1 (each in its slot, see chunk_slot) by one workgroup, fixed order: thread-strided accumulation with 8
 // independent loads in flight, wavefront shuffle, then the four wave results in wave order.
-__device__ __forceinline__ double block_range_sum(const double *__restrict__ partials, int b, int e, double *red)
+__device__ __forceinline__ double block_range_sum(const double *__restrict__ partials, int slot_per, int b, int e,
+                                                  double *red)
 {
     double a8[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
     for (int i = b + (int)threadIdx.x; i < e; i += 8 * kReduceBlock) {
@@ -510,7 +416,7 @@ __device__ __forceinline__ double block_range_sum(const double *__restrict__ par
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int idx = i + j * kReduceBlock;
-            v[j] = idx < e ? partials[idx] : 0.0;
+            v[j] = idx < e ? partials[chunk_slot(idx, slot_per)] : 0.0;
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j)
@@ -526,23 +432,23 @@ __device__ __forceinline__ double block_range_sum(const double *__restrict__ par
 
 // Per-tensor squared norms from the per-chunk partials of the last tracking pass: workgroup i
 // sums the chunk range of one (worker, tensor) pair.
-__global__ __launch_bounds__(kReduceBlock) void k_tensor_norms(const double *__restrict__ partials,
+__global__ __launch_bounds__(kReduceBlock) void k_tensor_norms(const double *__restrict__ partials, int slot_per,
                                                                const int32_t *__restrict__ range_begin,
                                                                double *__restrict__ out)
 {
     __shared__ double red[kReduceBlock / 64];
-    const double s = block_range_sum(partials, range_begin[blockIdx.x], range_begin[blockIdx.x + 1], red);
+    const double s = block_range_sum(partials, slot_per, range_begin[blockIdx.x], range_begin[blockIdx.x + 1], red);
     if (threadIdx.x == 0)
         out[blockIdx.x] = s;
 }
 
-__global__ __launch_bounds__(kReduceBlock) void k_reduce(const double *__restrict__ partials,
+__global__ __launch_bounds__(kReduceBlock) void k_reduce(const double *__restrict__ partials, int slot_per,
                                                          const int2 *__restrict__ segs,
                                                          double *__restrict__ seg_sums)
 {
     __shared__ double red[kReduceBlock / 64];
     const int2 sg = segs[blockIdx.x];
-    const double s = block_range_sum(partials, sg.x, sg.y, red);
+    const double s = block_range_sum(partials, slot_per, sg.x, sg.y, red);
     if (threadIdx.x == 0)
         seg_sums[blockIdx.x] = s;
 }
@@ -560,7 +466,7 @@ constexpr int kTrackWaves = kTrackBlock / 64;
 // Afterwards thread 0 ORs the flags (the all-gather of Alg. 1 collapses to this on one
 // GPU) and advances the local/sync counters of Eq. 4.
 __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const double *__restrict__ partials,
-                                                       const int32_t *__restrict__ chunk_begin)
+                                                       int slot_per, const int32_t *__restrict__ chunk_begin)
 {
     __shared__ double s_part[kTrackWaves][kTrackWaves];   // [worker in round][wave]
     __shared__ int32_t s_flag[kTrackWaves];
@@ -586,7 +492,7 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const int idx = i + j * kTrackBlock;
-                        v[j] = idx < e ? partials[idx] : 0.0;
+                        v[j] = idx < e ? partials[chunk_slot(idx, slot_per)] : 0.0;
                     }
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
@@ -1041,52 +947,64 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
 
 constexpr int kBlock = 256;
 
-template <int BLOCK, int U, bool MIXED, int MODE, bool NT, int WPB = 1>
-hipError_t launch_stream_bu(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
-                            const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
+// Launch k_stream with the (U, C) shape named by `variant` = 10*C + U.
+template <class OPT, bool MIXED, int MODE, bool NT>
+hipError_t launch_stream_t(const StreamTable &tab, const typename OPT::Args &args, int grid_cap, int variant,
+                           hipStream_t s)
 {
-    const int wgs = (grid + WPB - 1) / WPB;
-    hipLaunchKernelGGL((k_stream<BLOCK, U, MIXED, MODE, NT, WPB>), dim3(wgs), dim3(BLOCK * WPB), 0, s, recs, chunks,
-                       nchunks, partials, sgd, xcd_per);
-    return hipGetLastError();
-}
-
-template <bool MIXED, int MODE, bool NT>
-hipError_t launch_stream_t(const TensorRec *recs, const ChunkRec *chunks, int nchunks, double *partials,
-                           const SgdArgs &sgd, int grid, int variant, int xcd_per, hipStream_t s)
-{
-    // (workgroup size, 4-element groups per thread)
-#define SELSYNC_V(B, UF) \
-    return launch_stream_bu<B, UF, MIXED, MODE, NT>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s)
+#define SELSYNC_SHAPE(UU, CC)                                                                                       \
+    do {                                                                                                            \
+        const int nwg = tab.per > 0 ? 8 * (tab.per / (CC)) : (tab.nslots + (CC)-1) / (CC);                          \
+        const int grid = grid_cap < nwg ? grid_cap : nwg;                                                           \
+        hipLaunchKernelGGL((k_stream<OPT, UU, CC, MIXED, MODE, NT>), dim3(grid), dim3(64), 0, s, tab.recs, tab.slots, \
+                           tab.nslots, nwg, tab.per, tab.chunk_elems, tab.partials, args);                          \
+        return hipGetLastError();                                                                                   \
+    } while (0)
     switch (variant) {
-    case 1: SELSYNC_V(256, 2);
-    case 2: SELSYNC_V(256, 1);
-    case 3: SELSYNC_V(128, 4);
-    case 4: SELSYNC_V(128, 2);
-    case 5: SELSYNC_V(64, 4);
-    case 7: SELSYNC_V(64, 1);
-    case 8: SELSYNC_V(128, 1);
-    case 9: SELSYNC_V(256, 4);
-    case 10: return launch_stream_bu<64, 2, MIXED, MODE, NT, 2>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s);
-    case 11: return launch_stream_bu<64, 2, MIXED, MODE, NT, 4>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s);
-    case 12: return launch_stream_bu<64, 2, MIXED, MODE, NT, 8>(recs, chunks, nchunks, partials, sgd, grid, xcd_per, s);
-    default: SELSYNC_V(64, 2);   // 0 and 6: single-wave workgroups, 512 elements each (measured best)
+    case 11: SELSYNC_SHAPE(1, 1);
+    case 12: SELSYNC_SHAPE(2, 1);
+    case 14: SELSYNC_SHAPE(4, 1);
+    case 21: SELSYNC_SHAPE(1, 2);
+    case 22: SELSYNC_SHAPE(2, 2);
+    case 41: SELSYNC_SHAPE(1, 4);
+    case 42: SELSYNC_SHAPE(2, 4);
+    case 81: SELSYNC_SHAPE(1, 8);
+    default:
+        break;
     }
-#undef SELSYNC_V
+    // defaults (measured on the 133M-parameter fp32 workload): updates do best with the least
+    // work per wavefront; the read-only norm pass wants more bytes in flight per wavefront
+    if (MODE == kNormOnly)
+        SELSYNC_SHAPE(1, 4);
+    SELSYNC_SHAPE(1, 1);
+#undef SELSYNC_SHAPE
 }
 
-template <bool MIXED, bool NT>
-hipError_t launch_stream_m(StreamMode mode, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                           double *partials, const SgdArgs &sgd, int grid, int variant, int xcd_per, hipStream_t s)
+template <class OPT, bool MIXED, bool NT>
+hipError_t launch_stream_m(StreamMode mode, const StreamTable &tab, const typename OPT::Args &args, int grid_cap,
+                           int variant, hipStream_t s)
 {
     switch (mode) {
     case kNormOnly:
-        return launch_stream_t<MIXED, kNormOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, xcd_per, s);
+        return launch_stream_t<OPT, MIXED, kNormOnly, NT>(tab, args, grid_cap, variant, s);
     case kUpdateOnly:
-        return launch_stream_t<MIXED, kUpdateOnly, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, xcd_per, s);
+        return launch_stream_t<OPT, MIXED, kUpdateOnly, NT>(tab, args, grid_cap, variant, s);
     default:
-        return launch_stream_t<MIXED, kUpdateAndNorm, NT>(recs, chunks, nchunks, partials, sgd, grid, variant, xcd_per, s);
+        return launch_stream_t<OPT, MIXED, kUpdateAndNorm, NT>(tab, args, grid_cap, variant, s);
     }
+}
+
+template <class OPT>
+hipError_t launch_stream_o(StreamMode mode, bool mixed, const StreamTable &tab, const typename OPT::Args &args,
+                           const LaunchCfg &cfg, hipStream_t s)
+{
+    if (tab.nchunks <= 0)
+        return hipSuccess;
+    if (mixed)
+        return cfg.nontemporal ? launch_stream_m<OPT, true, true>(mode, tab, args, cfg.grid, cfg.variant, s)
+                               : launch_stream_m<OPT, true, false>(mode, tab, args, cfg.grid, cfg.variant, s);
+    return cfg.nontemporal ? launch_stream_m<OPT, false, true>(mode, tab, args, cfg.grid, cfg.variant, s)
+                           : launch_stream_m<OPT, false, false>(mode, tab, args, cfg.grid, cfg.variant, s);
 }
 
 template <int KC, bool MIXED, bool NT>
@@ -1122,67 +1040,39 @@ hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables 
 
 // ---------------------------------------------------------------- launchers
 
-hipError_t launch_stream(StreamMode mode, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                         double *partials, const SgdArgs &sgd, const LaunchCfg &cfg, hipStream_t s)
+hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
+                         hipStream_t s)
 {
-    if (nchunks <= 0)
-        return hipSuccess;
-    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
-    if (mixed)
-        return cfg.nontemporal ? launch_stream_m<true, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s)
-                               : launch_stream_m<true, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s);
-    return cfg.nontemporal ? launch_stream_m<false, true>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s)
-                           : launch_stream_m<false, false>(mode, recs, chunks, nchunks, partials, sgd, grid, cfg.variant, xcd_per, s);
+    return launch_stream_o<SgdOpt>(mode, mixed, tab, sgd, cfg, s);
 }
 
-hipError_t launch_stream_adam(bool with_norm, bool mixed, const TensorRec *recs, const ChunkRec *chunks, int nchunks,
-                              double *partials, const AdamArgs &a, const LaunchCfg &cfg, hipStream_t s)
+hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a,
+                              const LaunchCfg &cfg, hipStream_t s)
 {
-    if (nchunks <= 0)
-        return hipSuccess;
-    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
-#define SELSYNC_ADAM(MX, NM) \
-    hipLaunchKernelGGL((k_stream_adam<64, 2, MX, NM>), dim3(grid), dim3(64), 0, s, recs, chunks, nchunks, partials, a, \
-                       xcd_per)
-    if (mixed) {
-        if (with_norm)
-            SELSYNC_ADAM(true, true);
-        else
-            SELSYNC_ADAM(true, false);
-    } else {
-        if (with_norm)
-            SELSYNC_ADAM(false, true);
-        else
-            SELSYNC_ADAM(false, false);
-    }
-#undef SELSYNC_ADAM
-    return hipGetLastError();
+    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, cfg, s);
 }
 
-hipError_t launch_reduce(const double *partials, const int2 *segs, int nsegs, double *seg_sums, hipStream_t s)
+hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs, int nsegs, double *seg_sums,
+                         hipStream_t s)
 {
     if (nsegs <= 0)
         return hipSuccess;
-    hipLaunchKernelGGL(k_reduce, dim3(nsegs), dim3(kReduceBlock), 0, s, partials, segs, seg_sums);
+    hipLaunchKernelGGL(k_reduce, dim3(nsegs), dim3(kReduceBlock), 0, s, partials, slot_per, segs, seg_sums);
     return hipGetLastError();
 }
 
-hipError_t launch_tensor_norms(const double *partials, const int32_t *range_begin, int nranges, double *out,
-                               hipStream_t s)
+hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32_t *range_begin, int nranges,
+                               double *out, hipStream_t s)
 {
     if (nranges <= 0)
         return hipSuccess;
-    hipLaunchKernelGGL(k_tensor_norms, dim3(nranges), dim3(kReduceBlock), 0, s, partials, range_begin, out);
+    hipLaunchKernelGGL(k_tensor_norms, dim3(nranges), dim3(kReduceBlock), 0, s, partials, slot_per, range_begin, out);
     return hipGetLastError();
 }
 
-hipError_t launch_track(const TrackerDev &td, const double *partials, const int32_t *chunk_begin, hipStream_t s)
+hipError_t launch_track(const TrackerDev &td, const double *values, int slot_per, const int32_t *begin, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_track, dim3(1), dim3(kTrackBlock), 0, s, td, partials, chunk_begin);
+    hipLaunchKernelGGL(k_track, dim3(1), dim3(kTrackBlock), 0, s, td, values, slot_per, begin);
     return hipGetLastError();
 }
 
@@ -1203,35 +1093,39 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
 
 namespace {
 template <int KC, bool MIXED, bool NT>
-hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                       int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
+hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
+                       const int32_t *flag, int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
-    hipLaunchKernelGGL((k_update_ga<kBlock, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs, K,
-                       1.0 / (double)K, pow2, flag, mode, sgd, xcd_per);
+    if (block == 64)
+        hipLaunchKernelGGL((k_update_ga<64, KC, MIXED, NT>), dim3(grid), dim3(64), 0, s, chunks, nchunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode, sgd, xcd_per);
+    else
+        hipLaunchKernelGGL((k_update_ga<kBlock, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs,
+                           K, 1.0 / (double)K, pow2, flag, mode, sgd, xcd_per);
     return hipGetLastError();
 }
 
 template <bool MIXED, bool NT>
-hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                       int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
+hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
+                       const int32_t *flag, int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
 {
     switch (K) {
     case 1:
-        return launch_ga_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+        return launch_ga_t<1, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
     case 2:
-        return launch_ga_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+        return launch_ga_t<2, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
     case 4:
-        return launch_ga_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+        return launch_ga_t<4, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
     case 8:
-        return launch_ga_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+        return launch_ga_t<8, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
     default:
-        return launch_ga_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, sgd, grid, xcd_per, s);
+        return launch_ga_t<0, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
     }
 }
 }  // namespace
 
-hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
+hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
                             const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
                             hipStream_t s)
 {
@@ -1241,10 +1135,10 @@ hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, 
     const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
     const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
     if (mixed)
-        return cfg.nontemporal ? launch_ga_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
-                               : launch_ga_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
-    return cfg.nontemporal ? launch_ga_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
-                           : launch_ga_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
+        return cfg.nontemporal ? launch_ga_k<true, true>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
+                               : launch_ga_k<true, false>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
+    return cfg.nontemporal ? launch_ga_k<false, true>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
+                           : launch_ga_k<false, false>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
 }
 
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

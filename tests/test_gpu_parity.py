@@ -29,7 +29,7 @@ def rng(seed):
     return np.random.default_rng(seed)
 
 
-SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2, stream_variant=9)   # persistent grid, multi-pass chunks
+SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2, stream_variant=14)   # persistent grid, multi-pass chunks
 
 # tensor-size sets: tiny / ragged tails / several tiles / empty tensors / exactly one chunk
 SIZE_SETS = {
@@ -180,11 +180,12 @@ def test_local_step_automatic_first_step(B):
 
 
 @pytest.mark.parametrize("mixed", [False, True])
-def test_many_chunks_take_the_segment_reduction_level(B, mixed):
+@pytest.mark.parametrize("layout", [0, 1, 2])
+def test_many_chunks_take_the_segment_reduction_level(B, mixed, layout):
     # more than 16384 chunks: per-chunk partials -> per-segment sums -> tracker
     numel = [4_200_000 + 13, 77]
     K = 2
-    ls = PU.LockStep(B, numel, K, delta=float("inf"), mixed=mixed, seed=3)
+    ls = PU.LockStep(B, numel, K, delta=float("inf"), mixed=mixed, seed=3, tuning=dict(table_layout=layout))
     r = rng(23)
     grads = []
     for k in range(K):
@@ -198,13 +199,15 @@ def test_many_chunks_take_the_segment_reduction_level(B, mixed):
     ls.close()
 
 
-@pytest.mark.parametrize("variant,chunk", [(0, 512), (0, 1024), (1, 2048), (2, 1024), (3, 2048), (4, 1024), (5, 1024),
-                                           (7, 256), (8, 512), (9, 4096), (9, 65536), (10, 512), (11, 512), (12, 1024)])
+@pytest.mark.parametrize("variant,chunk", [(0, 0), (0, 1024), (11, 256), (11, 768), (12, 512), (12, 2048), (14, 1024),
+                                           (14, 65536), (21, 256), (22, 512), (22, 1536), (41, 256), (42, 512),
+                                           (81, 256), (81, 512)])
+@pytest.mark.parametrize("layout", [0, 1, 2])
 @pytest.mark.parametrize("persistent", [0, 2])
-def test_every_workgroup_shape_gives_the_same_results(B, variant, chunk, persistent):
+def test_every_kernel_shape_and_table_layout_gives_the_same_results(B, variant, chunk, layout, persistent):
     numel = [100003, 513, 4096, 255]
     K = 2
-    tuning = dict(chunk_elems=chunk, blocks_per_cu=persistent, stream_variant=variant)
+    tuning = dict(chunk_elems=chunk, blocks_per_cu=persistent, stream_variant=variant, table_layout=layout)
     for mixed in (False, True):
         ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, tuning=tuning, seed=4)
         r = rng(24)
@@ -364,11 +367,12 @@ def test_reset_clears_tracker_and_counters(B):
     ls.close()
 
 
-def test_per_tensor_norms_match_oracle(B):
+@pytest.mark.parametrize("layout", [0, 1, 2])
+def test_per_tensor_norms_match_oracle(B, layout):
     numel = [70001, 0, 5, 4096, 513]
     K = 3
     for mixed in (False, True):
-        ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, seed=17)
+        ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, seed=17, tuning=dict(table_layout=layout))
         r = rng(97)
         grads = []
         for k in range(K):
