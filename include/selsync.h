@@ -132,7 +132,7 @@ typedef struct selsync_tuning {
     int32_t blocks_per_cu;     /* > 0: persistent grid of this many workgroups per compute unit;
                                   <= 0 (default): one workgroup per chunk                               */
     int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
-    int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 1024)        */
+    int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 256)         */
     int32_t stream_variant;    /* shape of the update/norm kernel, 10*C + U: each 64-lane wavefront takes C
                                   chunks at once with U 128-bit accesses per lane, stream and pass.
                                   One of 11 12 14 21 22 41 42 81; 0 = default (11 for updates, 41 for
@@ -143,6 +143,8 @@ typedef struct selsync_tuning {
     int32_t table_layout;      /* chunk table and partial sums of the update/norm kernel:
                                   0 (default) striped by XCD, chunks dispatched in model order;
                                   1 linear; 2 striped, each XCD walks a contiguous eighth of the model   */
+    int32_t agg_shape;         /* aggregation kernel: 10 * workgroup size + 128-bit accesses per lane, stream
+                                  and pass; one of 641 642 2561 2562 2564 5121 5122 10241; 0 = default   */
 } selsync_tuning;
 
 typedef struct selsync_ctx  selsync_ctx;    /* opaque: tracker state, counters, workspace owner */

@@ -44,7 +44,7 @@ struct selsync_ctx {
     selsync_config cfg;
     int device = 0;
     int num_cus = 256;
-    selsync_tuning tuning{0, 0, -1, 0, 0, -1, 0, 0};
+    selsync_tuning tuning{0, 0, -1, 0, 0, -1, 0, 0, 0};
     // device state: one allocation, sub-pointers in td
     void *d_state = nullptr;
     size_t state_bytes = 0;        // size of the d_state allocation
@@ -519,11 +519,16 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
         if (std::find(std::begin(shapes), std::end(shapes), t->stream_variant) == std::end(shapes))
             return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be 0 or one of 11 12 14 21 22 41 42 81");
     }
-    if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kAggTileElems != 0 || t->agg_chunk_elems > (1 << 24)))
+    if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kChunkGranule != 0 || t->agg_chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_chunk_elems must be a multiple of %d and <= 2^24",
-                    kAggTileElems);
+                    kChunkGranule);
     if (t->ga_chunk_elems > 0 && (t->ga_chunk_elems % kChunkGranule != 0 || t->ga_chunk_elems > (1 << 24)))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "ga_chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
+    {
+        static const int shapes[] = {0, 641, 642, 2561, 2562, 2564, 5121, 5122, 10241};
+        if (std::find(std::begin(shapes), std::end(shapes), t->agg_shape) == std::end(shapes))
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_shape must be 0 or one of 641 642 2561 2562 2564 5121 5122 10241");
+    }
     if (t->table_layout < 0 || t->table_layout > 2)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "table_layout must be 0, 1 or 2");
     if (t->blocks_per_cu > 64)
@@ -833,6 +838,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->upd_cfg.variant = ctx->tuning.stream_variant;
     plan->upd_cfg.xcd_swizzle = ctx->tuning.xcd_swizzle >= 0 ? ctx->tuning.xcd_swizzle : kDefaultXcdSwizzle;
     plan->agg_cfg = plan->upd_cfg;
+    plan->agg_cfg.agg_shape = ctx->tuning.agg_shape;
 
     ctx->live_plans += 1;
     *out = plan.release();

@@ -119,6 +119,7 @@ struct LaunchCfg {
     int nontemporal;
     int variant = 0;       // streaming kernel: 10*C + U (C chunks per wave, U vectors per lane and tile); 0 = default
     int xcd_swizzle = 0;   // aggregation kernels: 1 = XCD-aware workgroup -> chunk mapping
+    int agg_shape = 0;     // aggregation kernel: 10 * workgroup size + accesses per lane; 0 = default
 };
 
 // Geometry of a plan's chunk table (see TableLayout).

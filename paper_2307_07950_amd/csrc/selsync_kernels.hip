@@ -1009,30 +1009,49 @@ hipError_t launch_stream_o(StreamMode mode, bool mixed, const StreamTable &tab, 
 
 template <int KC, bool MIXED, bool NT>
 hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                        int mode, int grid, int xcd_per, hipStream_t s)
+                        int mode, int grid, int xcd_per, int shape, hipStream_t s)
 {
-    constexpr int U = (KC == 0 || KC > 4) ? 1 : 4;
     const int pow2 = (K & (K - 1)) == 0;
-    hipLaunchKernelGGL((k_aggregate<kBlock, U, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs,
-                       K, 1.0 / (double)K, pow2, flag, mode, xcd_per);
-    return hipGetLastError();
+    // shape = 10 * workgroup size + 128-bit accesses per lane, stream and pass
+#define SELSYNC_AGG(BB, UU)                                                                                       \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((k_aggregate<BB, UU, KC, MIXED, NT>), dim3(grid), dim3(BB), 0, s, chunks, nchunks, tabs, \
+                           K, 1.0 / (double)K, pow2, flag, mode, xcd_per);                                        \
+        return hipGetLastError();                                                                                 \
+    } while (0)
+    switch (shape) {
+    case 641: SELSYNC_AGG(64, 1);
+    case 642: SELSYNC_AGG(64, 2);
+    case 2561: SELSYNC_AGG(256, 1);
+    case 2562: SELSYNC_AGG(256, 2);
+    case 2564: SELSYNC_AGG(256, 4);
+    case 5121: SELSYNC_AGG(512, 1);
+    case 5122: SELSYNC_AGG(512, 2);
+    case 10241: SELSYNC_AGG(1024, 1);
+    default:
+        break;
+    }
+    if (KC == 0 || KC > 4)
+        SELSYNC_AGG(256, 1);
+    SELSYNC_AGG(256, 4);
+#undef SELSYNC_AGG
 }
 
 template <bool MIXED, bool NT>
 hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                        int mode, int grid, int xcd_per, hipStream_t s)
+                        int mode, int grid, int xcd_per, int shape, hipStream_t s)
 {
     switch (K) {
     case 1:
-        return launch_agg_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
+        return launch_agg_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
     case 2:
-        return launch_agg_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
+        return launch_agg_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
     case 4:
-        return launch_agg_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
+        return launch_agg_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
     case 8:
-        return launch_agg_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
+        return launch_agg_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
     default:
-        return launch_agg_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, s);
+        return launch_agg_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
     }
 }
 
@@ -1085,10 +1104,10 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
     const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
     const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
     if (mixed)
-        return cfg.nontemporal ? launch_agg_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s)
-                               : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s);
-    return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s)
-                           : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, s);
+        return cfg.nontemporal ? launch_agg_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s)
+                               : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s);
+    return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s)
+                           : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s);
 }
 
 namespace {

@@ -61,7 +61,7 @@ def test_tensor_beyond_2_to_31_elements_uses_64_bit_offsets():
     glob = torch.zeros(n, dtype=torch.float32, device="cuda")
     ctx = B.SelSync(1, 0.0)                               # delta 0: the step also aggregates (copies w to global)
     plan = ctx.plan([[g]], [[w]], [[m]], [glob])
-    assert plan.info()["update_chunks"] == -(-n // 512)
+    assert plan.info()["update_chunks"] == -(-n // 256)
     dec = ctx.step(plan, 0.1, 0.9, 5e-4, 2.0, first_step=0, blocking=True)
     assert dec.norm_sq == [float(n)]                      # (2*0.5)^2 * n, exact in fp64
     hw, hm, hg = np.array([1.25], np.float32), np.array([-0.75], np.float32), np.array([0.5], np.float32)

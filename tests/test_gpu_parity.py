@@ -253,6 +253,34 @@ def test_aggregate_matches_oracle(B, K, mixed):
     ls.close()
 
 
+@pytest.mark.parametrize("shape,chunk", [(641, 256), (642, 512), (2561, 1024), (2562, 2048), (2564, 4096), (5121, 2048),
+                                         (5122, 4096), (10241, 4096), (2564, 1024), (641, 8192)])
+@pytest.mark.parametrize("K", [3, 4])
+def test_aggregate_kernel_shapes_give_identical_results(B, shape, chunk, K):
+    numel = [70001, 5, 8192, 0, 33333]
+    for mixed in (False, True):
+        ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, seed=7,
+                         tuning=dict(agg_shape=shape, agg_chunk_elems=chunk, xcd_swizzle=K % 2))
+        r = rng(300 + K)
+        for k in range(K):
+            for t, n in enumerate(numel):
+                ls.h_w[k][t] += (r.standard_normal(n) * 1e-3).astype(np.float32)
+                ls.d_w[k][t].copy_(torch.from_numpy(ls.h_w[k][t]))
+        ls.bind_grads(0, [[W.round_to_bf16_bits(np.zeros(n, np.float32)) if mixed else np.zeros(n, np.float32)
+                           for n in numel] for _ in range(K)])
+        ls.ctx.aggregate_params(ls.plans[0], always=True)
+        O.average_params(ls.h_w, ls.h_glob, ls.h_c, ls.h_gc)
+        for t in range(len(numel)):
+            assert PU.to_host(ls.d_glob[t]).tobytes() == ls.h_glob[t].tobytes()
+            if mixed:
+                assert PU.to_host(ls.d_gc[t]).tobytes() == ls.h_gc[t].tobytes()
+            for k in range(K):
+                assert PU.to_host(ls.d_w[k][t]).tobytes() == ls.h_w[k][t].tobytes()
+                if mixed:
+                    assert PU.to_host(ls.d_c[k][t]).tobytes() == ls.h_c[k][t].tobytes()
+        ls.close()
+
+
 def test_aggregate_identical_replicas_is_identity_and_misaligned(B):
     numel = [10001, 64, 3]
     K = 4
