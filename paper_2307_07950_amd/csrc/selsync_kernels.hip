@@ -10,9 +10,11 @@
 //                replica (Alg. 1 lines 14-15), predicated on the device-side decision.
 //
 // All three are HBM-bandwidth bound (<= 0.4 flop/byte), so there is no MFMA use:
-// the design is 128-bit coalesced accesses, many independent loads in flight per
-// lane, a persistent grid sized to the CU count, and no atomics (every partial has
-// a fixed slot and every sum a fixed order, so results are run-to-run identical).
+// the design is 128-bit coalesced non-temporal accesses, one-shot grids of single-wave
+// workgroups that each carry as little work as one vector per lane and stream (the
+// hardware dispatcher then streams through the model in order, one retired wave at a
+// time), tables laid out per XCD, and no atomics (every partial has a fixed slot and
+// every sum a fixed order, so results are run-to-run identical).
 //
 // fp32 arithmetic of the update is written to round once per operation; the file
 // is compiled with -ffp-contract=off and the pragma below so no multiply-add is fused.
