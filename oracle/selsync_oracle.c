@@ -127,6 +127,86 @@ void selsync_oracle_sgd_bf16(float *master, float *m, const uint16_t *g, uint16_
     }
 }
 
+/*
+ * Momentum-free SGD (the Transformer recipe of Sec. IV-A names plain SGD with a decaying
+ * learning rate and no momentum): no buffer at all,
+ *     gh = fl(grad_scale * g);  d = fl(gh + fl(wd * w));  w = fl(w - fl(lr * d)).
+ */
+void selsync_oracle_sgd_plain_f32(float *w, const float *g, int64_t n, float lr, float wd, float grad_scale)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = grad_scale * g[j];
+        float dec = wd * w[j];
+        float d = gh + dec;
+        float stepv = lr * d;
+        w[j] = w[j] - stepv;
+    }
+}
+
+void selsync_oracle_sgd_plain_bf16(float *master, const uint16_t *g, uint16_t *copy, int64_t n,
+                                   float lr, float wd, float grad_scale)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = grad_scale * selsync_oracle_bf16_to_f32(g[j]);
+        float dec = wd * master[j];
+        float d = gh + dec;
+        float stepv = lr * d;
+        master[j] = master[j] - stepv;
+        copy[j] = selsync_oracle_f32_to_bf16(master[j]);
+    }
+}
+
+/*
+ * Nesterov momentum (named among the optimisers in Sec. II-A; the paper gives no formula,
+ * so this is the common look-ahead form): the buffer is updated as in plain momentum and
+ * the step direction is the gradient plus mu times the NEW buffer,
+ *     m = first ? d : fl(fl(mu * m) + d);  dir = fl(d + fl(mu * m));  w = fl(w - fl(lr * dir)).
+ */
+void selsync_oracle_sgd_nesterov_f32(float *w, float *m, const float *g, int64_t n,
+                                     float lr, float mu, float wd, float grad_scale, int first)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = grad_scale * g[j];
+        float dec = wd * w[j];
+        float d = gh + dec;
+        float mom;
+        if (first) {
+            mom = d;
+        } else {
+            float mm = mu * m[j];
+            mom = mm + d;
+        }
+        float look = mu * mom;
+        float dir = d + look;
+        float stepv = lr * dir;
+        m[j] = mom;
+        w[j] = w[j] - stepv;
+    }
+}
+
+void selsync_oracle_sgd_nesterov_bf16(float *master, float *m, const uint16_t *g, uint16_t *copy, int64_t n,
+                                      float lr, float mu, float wd, float grad_scale, int first)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float gh = grad_scale * selsync_oracle_bf16_to_f32(g[j]);
+        float dec = wd * master[j];
+        float d = gh + dec;
+        float mom;
+        if (first) {
+            mom = d;
+        } else {
+            float mm = mu * m[j];
+            mom = mm + d;
+        }
+        float look = mu * mom;
+        float dir = d + look;
+        float stepv = lr * dir;
+        m[j] = mom;
+        master[j] = master[j] - stepv;
+        copy[j] = selsync_oracle_f32_to_bf16(master[j]);
+    }
+}
+
 /* ------------------------------------------------------------------ a4: parameter aggregation */
 
 /*

@@ -56,6 +56,14 @@ def lib() -> ctypes.CDLL:
         L.selsync_oracle_sgd_bf16.restype = None
         L.selsync_oracle_sgd_bf16.argtypes = [f32p, f32p, u16p, u16p, ctypes.c_int64] + [ctypes.c_float] * 4 + [ctypes.c_int]
         L.selsync_oracle_average_f32.restype = None
+        L.selsync_oracle_sgd_plain_f32.argtypes = [f32p, f32p, ctypes.c_int64] + [ctypes.c_float] * 3
+        L.selsync_oracle_sgd_plain_f32.restype = None
+        L.selsync_oracle_sgd_plain_bf16.argtypes = [f32p, u16p, u16p, ctypes.c_int64] + [ctypes.c_float] * 3
+        L.selsync_oracle_sgd_plain_bf16.restype = None
+        L.selsync_oracle_sgd_nesterov_f32.argtypes = [f32p, f32p, f32p, ctypes.c_int64] + [ctypes.c_float] * 4 + [ctypes.c_int]
+        L.selsync_oracle_sgd_nesterov_f32.restype = None
+        L.selsync_oracle_sgd_nesterov_bf16.argtypes = [f32p, f32p, u16p, u16p, ctypes.c_int64] + [ctypes.c_float] * 4 + [ctypes.c_int]
+        L.selsync_oracle_sgd_nesterov_bf16.restype = None
         L.selsync_oracle_average_f32.argtypes = [ctypes.POINTER(f32p), ctypes.c_int, f32p, ctypes.c_int64]
         L.selsync_oracle_average_bf16.restype = None
         L.selsync_oracle_average_bf16.argtypes = [ctypes.POINTER(f32p), ctypes.POINTER(u16p), ctypes.c_int,
@@ -134,23 +142,34 @@ def norm_sq(tensors: Sequence[np.ndarray], grad_scale: float = 1.0) -> float:
 
 # ---------------------------------------------------------------- a3
 
-def sgd_update(params: Sequence[np.ndarray], momenta: Sequence[np.ndarray], grads: Sequence[np.ndarray],
+def sgd_update(params: Sequence[np.ndarray], momenta: Optional[Sequence[np.ndarray]], grads: Sequence[np.ndarray],
                lr: float, momentum: float, weight_decay: float, grad_scale: float = 1.0, first: bool = False,
-               copies: Optional[Sequence[np.ndarray]] = None) -> None:
+               copies: Optional[Sequence[np.ndarray]] = None, nesterov: bool = False) -> None:
     """In-place local update of one replica (Alg. 1 line 9).  With ``copies`` the
     gradients are bf16 bits, ``params`` are the fp32 masters and ``copies`` receive
-    the bf16-rounded parameters."""
+    the bf16-rounded parameters.  ``momenta=None`` is momentum-free SGD (no buffer;
+    ``momentum`` must be 0); ``nesterov`` selects the look-ahead step direction."""
     L = lib()
+    if momenta is None:
+        assert momentum == 0.0 and not nesterov
+        for t, (w, g) in enumerate(zip(params, grads)):
+            assert w.size == g.size
+            if copies is None:
+                L.selsync_oracle_sgd_plain_f32(_f32(w), _f32(g), w.size, lr, weight_decay, grad_scale)
+            else:
+                assert copies[t].size == w.size
+                L.selsync_oracle_sgd_plain_bf16(_f32(w), _u16(g), _u16(copies[t]), w.size, lr, weight_decay, grad_scale)
+        return
+    f32_fn = L.selsync_oracle_sgd_nesterov_f32 if nesterov else L.selsync_oracle_sgd_f32
+    bf16_fn = L.selsync_oracle_sgd_nesterov_bf16 if nesterov else L.selsync_oracle_sgd_bf16
     for t, (w, m, g) in enumerate(zip(params, momenta, grads)):
         assert w.size == m.size == g.size
         if copies is None:
-            L.selsync_oracle_sgd_f32(_f32(w), _f32(m), _f32(g), w.size, lr, momentum, weight_decay, grad_scale,
-                                     int(first))
+            f32_fn(_f32(w), _f32(m), _f32(g), w.size, lr, momentum, weight_decay, grad_scale, int(first))
         else:
             c = copies[t]
             assert c.size == w.size
-            L.selsync_oracle_sgd_bf16(_f32(w), _f32(m), _u16(g), _u16(c), w.size, lr, momentum, weight_decay,
-                                      grad_scale, int(first))
+            bf16_fn(_f32(w), _f32(m), _u16(g), _u16(c), w.size, lr, momentum, weight_decay, grad_scale, int(first))
 
 
 # ---------------------------------------------------------------- a4

@@ -29,6 +29,11 @@ MUT = [
  ("flag strict", "return delta_g >= threshold ? 1 : 0;", "return delta_g > threshold ? 1 : 0;"),
  ("bf16 truncates", "u += 0x7fffu + lsb;", "u += 0;"),
  ("bf16 ties away", "u += 0x7fffu + lsb;", "u += 0x8000u;"),
+ ("plain sgd ignores decay", "float d = gh + dec;\n        float stepv = lr * d;\n        w[j] = w[j] - stepv;", "float d = gh;\n        float stepv = lr * d;\n        w[j] = w[j] - stepv;"),
+ ("plain sgd plus step", "float stepv = lr * d;\n        w[j] = w[j] - stepv;", "float stepv = lr * d;\n        w[j] = w[j] + stepv;"),
+ ("nesterov looks at old buffer", "float look = mu * mom;\n        float dir = d + look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]", "float look = mu * m[j];\n        float dir = d + look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]"),
+ ("nesterov drops gradient term", "float dir = d + look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]", "float dir = look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]"),
+ ("nesterov stores direction", "float stepv = lr * dir;\n        m[j] = mom;\n        w[j]", "float stepv = lr * dir;\n        m[j] = dir;\n        w[j]"),
 ]
 
 

@@ -392,6 +392,94 @@ def test_sgd_matches_torch_optim_sgd_over_several_steps():
         np.testing.assert_allclose(m, buf, rtol=0, atol=4 * np.spacing(np.float32(0.0625)))
 
 
+def test_nesterov_sgd_against_torch_optimizer_over_several_steps():
+    torch = pytest.importorskip("torch")
+    r = rng(123)
+    n, lr, mu, wd = 1000, 0.1, 0.9, 5e-4
+    w = (r.standard_normal(n) * 0.05).astype(np.float32)
+    m = np.zeros(n, np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, weight_decay=wd, dampening=0.0, nesterov=True)
+    for i in range(6):
+        g = (r.standard_normal(n) * 1e-2).astype(np.float32)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        O.sgd_update([w], [m], [g], lr, mu, wd, first=(i == 0), nesterov=True)
+        np.testing.assert_allclose(w, p.detach().numpy(), rtol=0, atol=4 * np.spacing(np.float32(0.25)))
+        np.testing.assert_allclose(m, opt.state[p]["momentum_buffer"].numpy(), rtol=0,
+                                   atol=4 * np.spacing(np.float32(0.0625)))
+
+
+def test_nesterov_closed_forms_and_difference_from_plain_momentum():
+    r = rng(124)
+    n = 500
+    w0 = r.standard_normal(n).astype(np.float32)
+    g = r.standard_normal(n).astype(np.float32)
+    lr, mu = 0.25, 0.5
+    # first step, no decay: m = g, w = w0 - lr*(g + mu*g) = w0 - lr*1.5*g, all exactly representable factors
+    w, m = w0.copy(), np.full(n, 7.0, np.float32)
+    O.sgd_update([w], [m], [g], lr, mu, 0.0, first=True, nesterov=True)
+    assert m.tobytes() == g.tobytes()
+    want = w0 - np.float32(lr) * (g + np.float32(mu) * g)
+    assert w.tobytes() == want.astype(np.float32).tobytes()
+    # with mu = 0 the look-ahead term vanishes: identical to plain momentum SGD with mu = 0
+    wa, ma, wb, mb = w0.copy(), np.zeros(n, np.float32), w0.copy(), np.zeros(n, np.float32)
+    O.sgd_update([wa], [ma], [g], lr, 0.0, 1e-3, nesterov=True)
+    O.sgd_update([wb], [mb], [g], lr, 0.0, 1e-3, nesterov=False)
+    assert wa.tobytes() == wb.tobytes() and ma.tobytes() == mb.tobytes()
+    # the buffer follows plain momentum exactly; the parameter steps further along the buffer
+    wa, ma, wb, mb = w0.copy(), g.copy(), w0.copy(), g.copy()
+    O.sgd_update([wa], [ma], [g], lr, mu, 0.0, nesterov=True)
+    O.sgd_update([wb], [mb], [g], lr, mu, 0.0, nesterov=False)
+    assert ma.tobytes() == mb.tobytes()
+    np.testing.assert_allclose(wa - wb, -lr * (g + mu * mb - mb), rtol=0, atol=1e-6)
+
+
+def test_momentum_free_sgd_against_torch_general_oracle_and_closed_form():
+    torch = pytest.importorskip("torch")
+    r = rng(125)
+    n, lr, wd = 1000, 2.0, 1e-4          # the Transformer recipe uses lr 2.0 (Sec. IV-A)
+    w = (r.standard_normal(n) * 0.05).astype(np.float32)
+    w_gen, m_gen = w.copy(), np.zeros(n, np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.SGD([p], lr=lr, momentum=0.0, weight_decay=wd)
+    for i in range(5):
+        g = (r.standard_normal(n) * 1e-3).astype(np.float32)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        O.sgd_update([w], None, [g], lr, 0.0, wd)
+        O.sgd_update([w_gen], [m_gen], [g], lr, 0.0, wd, first=(i == 0))
+        assert w.tobytes() == w_gen.tobytes()            # the momentum form at mu = 0 takes the same roundings
+        np.testing.assert_allclose(w, p.detach().numpy(), rtol=0, atol=4 * np.spacing(np.float32(0.25)))
+    # closed form with exactly representable numbers: w - 0.5 * (0.25*g + 0) for power-of-two inputs
+    wq = np.array([1.0, -2.0, 0.5], np.float32)
+    gq = np.array([4.0, 8.0, -16.0], np.float32)
+    O.sgd_update([wq], None, [gq], 0.5, 0.0, 0.0, grad_scale=0.25)
+    assert wq.tolist() == [0.5, -3.0, 2.5]
+    # mixed precision: master follows the fp32 path on the widened gradient, copy is the rounded master
+    master = (r.standard_normal(n) * 0.02).astype(np.float32)
+    gbits = O.f32_to_bf16((r.standard_normal(n) * 1e-3).astype(np.float32))
+    w2 = master.copy()
+    copy = np.zeros(n, np.uint16)
+    O.sgd_update([master], None, [gbits], 0.05, 0.0, 1e-3, copies=[copy])
+    O.sgd_update([w2], None, [O.bf16_to_f32(gbits)], 0.05, 0.0, 1e-3)
+    assert master.tobytes() == w2.tobytes() and copy.tobytes() == O.f32_to_bf16(master).tobytes()
+
+
+def test_nesterov_bf16_mode_master_matches_f32_path():
+    r = rng(126)
+    n = 1200
+    master = (r.standard_normal(n) * 0.02).astype(np.float32)
+    m = (r.standard_normal(n) * 1e-3).astype(np.float32)
+    gbits = O.f32_to_bf16((r.standard_normal(n) * 1e-3).astype(np.float32))
+    w2, m2 = master.copy(), m.copy()
+    copy = np.zeros(n, np.uint16)
+    O.sgd_update([master], [m], [gbits], 0.05, 0.9, 1e-3, grad_scale=0.5, copies=[copy], nesterov=True)
+    O.sgd_update([w2], [m2], [O.bf16_to_f32(gbits)], 0.05, 0.9, 1e-3, grad_scale=0.5, nesterov=True)
+    assert master.tobytes() == w2.tobytes() and m.tobytes() == m2.tobytes()
+    assert copy.tobytes() == O.f32_to_bf16(master).tobytes()
+
+
 def test_sgd_agrees_with_fp64_recomputation_and_is_elementwise():
     r = rng(24)
     n = 2000
