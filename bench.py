@@ -47,10 +47,11 @@ def parse_args():
     ap.add_argument("--stream-shape", type=int, default=0,
                     help="update/norm kernel shape 10*C + U (C chunks per wavefront, U 128-bit accesses per lane)")
     ap.add_argument("--table-layout", type=int, default=0, help="0 striped by XCD (default), 1 linear, 2 XCD-contiguous")
-    ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga", "adam"],
+    ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga", "adam", "plain", "nesterov"],
                     help="pa: fused selsync_step (default, the headline); unfused: the three primitives in Alg. 1 "
                          "order; ga: gradient-aggregation variant (selsync_step_ga); adam: Adam as the local update "
-                         "(selsync_step_adam, 28 B per parameter)")
+                         "(selsync_step_adam, 28 B per parameter); plain: momentum-free SGD on plans without momentum buffers "
+                         "(12 B per parameter); nesterov: selsync_step with the Nesterov step direction")
     ap.add_argument("--window", type=int, default=0, help="EWMA window (default: the workload's, 25)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -176,12 +177,13 @@ def main():
                        stream_variant=args.stream_shape, ga_chunk_elems=args.ga_chunk_elems,
                        table_layout=args.table_layout)
     plans = []
+    momenta = None if args.variant == "plain" else st["m"]
     for slot in range(wl.pool):
         if wl.mixed_bf16:
-            plans.append(ctx.plan(st["grads"][slot], st["copy"], st["m"], st["glob"], master=st["w"],
+            plans.append(ctx.plan(st["grads"][slot], st["copy"], momenta, st["glob"], master=st["w"],
                                   global_lowp=st["gcopy"]))
         else:
-            plans.append(ctx.plan(st["grads"][slot], st["w"], st["m"], st["glob"]))
+            plans.append(ctx.plan(st["grads"][slot], st["w"], momenta, st["glob"]))
     info = plans[0].info()
     if args.variant == "adam":
         st["v"] = [[torch.zeros_like(x) for x in st["w"][k]] for k in range(K)]
@@ -196,6 +198,10 @@ def main():
             plan = plans[t % wl.pool]
             if args.variant == "pa":
                 ctx.step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
+            elif args.variant == "plain":
+                ctx.step(plan, wl.lr, 0.0, wl.weight_decay, sig[t])
+            elif args.variant == "nesterov":
+                ctx.step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0), nesterov=True)
             elif args.variant == "unfused":
                 ctx.track_grad_change(plan, sig[t], blocking=False)
                 ctx.local_step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
@@ -241,6 +247,8 @@ def main():
         b_local, b_sync = b_local + K * (2 if wl.mixed_bf16 else 4) * P, 0
     if args.variant == "adam":
         b_local += K * 8 * P                 # second-moment buffer read and written
+    if args.variant == "plain":
+        b_local -= K * 8 * P                 # no momentum buffer read or written
     total_bytes = args.steps * b_local + n_sync * b_sync
     eff_gbps = total_bytes / elapsed / 1e9
     ms_per_step = elapsed / args.steps * 1e3

@@ -90,7 +90,10 @@ typedef struct selsync_config {
 
 /* Hyper-parameters of the local update (Alg. 1 line 9 with the Sec. IV-A recipes):
  *   gh = grad_scale*g;  d = gh + weight_decay*w;  m = first ? d : momentum*m + d;  w = w - lr*m
- * evaluated in fp32 with one rounding per operation (no fused multiply-add). */
+ * evaluated in fp32 with one rounding per operation (no fused multiply-add).
+ * With nesterov = 1 the step direction is d + momentum*m (m the NEW buffer) instead of m.
+ * On a plan created without momentum buffers the update is w = w - lr*d (plain SGD, the
+ * Transformer recipe): momentum must be 0 and nesterov 0 there. */
 typedef struct selsync_sgd {
     float   lr;
     float   momentum;
@@ -98,6 +101,7 @@ typedef struct selsync_sgd {
     float   grad_scale;    /* multiplies every gradient element before use (also in the norm); 1 = none */
     int32_t first_step;    /* 1: momentum buffers are uninitialised (m = d); 0: they are valid;
                               -1: decide automatically (first local update since create/reset)        */
+    int32_t nesterov;      /* 0 or 1; 1 needs momentum > 0                                             */
 } selsync_sgd;
 
 /* Hyper-parameters of the Adam variant of the local update (the AlexNet recipe of Sec. IV-A
@@ -186,7 +190,10 @@ const char *selsync_status_string(int32_t status);
  *   grads   [K] gradients g_k.           F32, or BF16 in mixed mode.  May be NULL: then only
  *                                         selsync_aggregate_params is valid on the plan.
  *   params  [K] worker replicas w_k.     F32; in mixed mode the BF16 working copies.
- *   momenta [K] momentum buffers m_k.    F32.  NULL together with grads.
+ *   momenta [K] momentum buffers m_k.    F32.  NULL when grads is NULL.  NULL with grads given makes a
+ *                                         momentum-free plan: 12 instead of 20 bytes move per
+ *                                         parameter; SGD entry points then require momentum = 0, and
+ *                                         the Adam and gradient-aggregation entry points return STATE.
  *   master  [K] fp32 master parameters.  NULL in fp32 mode; required in mixed mode.
  *   global      the global model.        F32 (the fp32 master in mixed mode).
  *   global_lowp BF16 copy of the global model; NULL in fp32 mode, required in mixed mode.

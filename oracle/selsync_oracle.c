@@ -322,7 +322,9 @@ void selsync_oracle_adam_bf16(float *master, float *m, float *v, const uint16_t 
  * gradients instead of parameters and every worker applies the same averaged gradient
  *     gbar_j = fl32( (sum_{k=0..K-1} (double)fl32(grad_scale * g_{k,j})) / K )
  * to its OWN parameters and momentum.  This only forms gbar; the update itself is
- * selsync_oracle_sgd_f32 with gbar as the gradient and grad_scale 1.
+ * selsync_oracle_sgd_f32 (or its Nesterov form) with gbar as the gradient and grad_scale 1;
+ * in mixed precision it acts on the fp32 masters and the bf16 copies are then refreshed
+ * by rounding the masters.
  */
 void selsync_oracle_average_grads_f32(const float *const *grads, int K, float grad_scale, float *gbar, int64_t n)
 {
@@ -345,28 +347,6 @@ void selsync_oracle_average_grads_bf16(const uint16_t *const *grads, int K, floa
             s += (double)gh;
         }
         gbar[j] = (float)(s / (double)K);
-    }
-}
-
-/* Mixed-precision update driven by an fp32 gradient (the averaged one). */
-void selsync_oracle_sgd_mixed_f32grad(float *master, float *m, const float *g, uint16_t *copy, int64_t n,
-                                      float lr, float mu, float wd, int first)
-{
-    for (int64_t j = 0; j < n; ++j) {
-        float gh = g[j];
-        float dec = wd * master[j];
-        float d = gh + dec;
-        float mom;
-        if (first) {
-            mom = d;
-        } else {
-            float mm = mu * m[j];
-            mom = mm + d;
-        }
-        float stepv = lr * mom;
-        m[j] = mom;
-        master[j] = master[j] - stepv;
-        copy[j] = selsync_oracle_f32_to_bf16(master[j]);
     }
 }
 

@@ -74,8 +74,6 @@ def lib() -> ctypes.CDLL:
         L.selsync_oracle_average_grads_bf16.restype = None
         L.selsync_oracle_average_grads_bf16.argtypes = [ctypes.POINTER(u16p), ctypes.c_int, ctypes.c_float, f32p,
                                                         ctypes.c_int64]
-        L.selsync_oracle_sgd_mixed_f32grad.restype = None
-        L.selsync_oracle_sgd_mixed_f32grad.argtypes = [f32p, f32p, f32p, u16p, ctypes.c_int64] + [ctypes.c_float] * 3 + [ctypes.c_int]
         L.selsync_oracle_adam_f32.restype = None
         L.selsync_oracle_adam_f32.argtypes = [f32p, f32p, f32p, f32p, ctypes.c_int64] + [ctypes.c_float] * 10 + [ctypes.c_int]
         L.selsync_oracle_adam_bf16.restype = None
@@ -244,7 +242,7 @@ def average_grads(grads: Sequence[Sequence[np.ndarray]], grad_scale: float = 1.0
 
 
 def ga_update(grads, params, momenta, lr, momentum, weight_decay, grad_scale=1.0, first=False, sync=True,
-              copies=None) -> None:
+              copies=None, nesterov=False) -> None:
     """Update of all K workers under gradient aggregation: on a synchronising step every
     worker applies the averaged gradient to its own state, otherwise its own gradient."""
     L = lib()
@@ -252,17 +250,17 @@ def ga_update(grads, params, momenta, lr, momentum, weight_decay, grad_scale=1.0
     if not sync:
         for k in range(K):
             sgd_update(params[k], momenta[k], grads[k], lr, momentum, weight_decay, grad_scale, first,
-                       None if copies is None else copies[k])
+                       None if copies is None else copies[k], nesterov=nesterov)
         return
     gbar = average_grads(grads, grad_scale)
     for k in range(K):
         if copies is None:
-            sgd_update(params[k], momenta[k], gbar, lr, momentum, weight_decay, 1.0, first)
+            sgd_update(params[k], momenta[k], gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)
         else:
+            # fp32 averaged gradient applied to the fp32 masters, then the bf16 copies are refreshed
+            sgd_update(params[k], momenta[k], gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)
             for t in range(len(gbar)):
-                L.selsync_oracle_sgd_mixed_f32grad(_f32(params[k][t]), _f32(momenta[k][t]), _f32(gbar[t]),
-                                                   _u16(copies[k][t]), gbar[t].size, lr, momentum, weight_decay,
-                                                   int(first))
+                copies[k][t][...] = f32_to_bf16(params[k][t])
 
 
 # ---------------------------------------------------------------- a2

@@ -58,7 +58,7 @@ class selsync_config(ctypes.Structure):
 
 class selsync_sgd(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float),
-                ("grad_scale", ctypes.c_float), ("first_step", ctypes.c_int32)]
+                ("grad_scale", ctypes.c_float), ("first_step", ctypes.c_int32), ("nesterov", ctypes.c_int32)]
 
 
 class selsync_adam(ctypes.Structure):
@@ -285,7 +285,8 @@ class SelSync:
         self._check(selsync_set_delta(self._h, delta, _vp(_stream_handle(stream))))
 
     def plan(self, grads, params, momenta, global_model, master=None, global_lowp=None) -> Plan:
-        """grads/params/momenta/master: K lists of tensors; global_model/global_lowp: one list."""
+        """grads/params/momenta/master: K lists of tensors; global_model/global_lowp: one list.
+        ``momenta=None`` with gradients given makes a momentum-free plan (plain SGD only)."""
         for name, lists in (("grads", grads), ("params", params), ("momenta", momenta), ("master", master)):
             if lists is not None and len(lists) != self.num_workers:
                 raise ValueError("%s: expected %d lists (one per worker), got %d"
@@ -313,16 +314,17 @@ class SelSync:
         return self._decision(rc, n, d, f, s) if blocking else None
 
     def local_step(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
-                   grad_scale: float = 1.0, first_step: int = -1, stream=None):
-        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step)
+                   grad_scale: float = 1.0, first_step: int = -1, stream=None, nesterov: bool = False):
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step, int(nesterov))
         self._check(selsync_local_step(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream))))
 
     def aggregate_params(self, plan: Plan, always: bool = False, stream=None):
         self._check(selsync_aggregate_params(self._h, plan._h, 1 if always else 0, _vp(_stream_handle(stream))))
 
     def step(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
-             grad_scale: float = 1.0, first_step: int = -1, blocking: bool = False, stream=None):
-        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step)
+             grad_scale: float = 1.0, first_step: int = -1, blocking: bool = False, stream=None,
+             nesterov: bool = False):
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step, int(nesterov))
         n, d, f, s = self._outs()
         rc = self._check(selsync_step(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
                                       int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
@@ -352,14 +354,16 @@ class SelSync:
 
     # -- variant: gradient aggregation
     def ga_update(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
-                  grad_scale: float = 1.0, first_step: int = -1, always: bool = False, stream=None):
-        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step)
+                  grad_scale: float = 1.0, first_step: int = -1, always: bool = False, stream=None,
+                  nesterov: bool = False):
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step, int(nesterov))
         self._check(selsync_ga_update(self._h, plan._h, ctypes.byref(sgd), 1 if always else 0,
                                       _vp(_stream_handle(stream))))
 
     def step_ga(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
-                grad_scale: float = 1.0, first_step: int = -1, blocking: bool = False, stream=None):
-        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step)
+                grad_scale: float = 1.0, first_step: int = -1, blocking: bool = False, stream=None,
+                nesterov: bool = False):
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step, int(nesterov))
         n, d, f, s = self._outs()
         rc = self._check(selsync_step_ga(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
                                          int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)

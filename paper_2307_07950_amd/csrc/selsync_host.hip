@@ -70,6 +70,7 @@ struct selsync_plan {
     int64_t P = 0;
     bool mixed = false;
     bool has_grads = false;
+    bool has_momenta = false;      // false with has_grads: momentum-free plan (plain SGD only)
     int n_upd_chunks = 0, n_agg_chunks = 0, n_ga_chunks = 0;
     void *d_blob = nullptr;        // all tables in one allocation
     TensorRec *d_recs = nullptr;
@@ -300,12 +301,20 @@ int32_t fetch_decision(selsync_ctx *ctx, hipStream_t s, double *norm_sq_out, dou
     return hdr->nonfinite_now ? SELSYNC_WARN_NONFINITE : SELSYNC_OK;
 }
 
-int32_t resolve_sgd(selsync_ctx *ctx, const selsync_sgd *sgd, SgdArgs *out)
+int32_t resolve_sgd(selsync_ctx *ctx, const selsync_plan *plan, const selsync_sgd *sgd, SgdArgs *out)
 {
     if (!sgd)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "sgd is NULL");
     if (sgd->first_step < -1 || sgd->first_step > 1)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "sgd.first_step must be -1, 0 or 1");
+    if (sgd->nesterov != 0 && sgd->nesterov != 1)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "sgd.nesterov must be 0 or 1");
+    if (sgd->nesterov && !(sgd->momentum > 0.f))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "sgd.nesterov needs momentum > 0");
+    if (!plan->has_momenta && (sgd->momentum != 0.f || sgd->nesterov))
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG,
+                    "the plan has no momentum buffers: momentum must be 0 and nesterov 0");
+    out->nesterov = sgd->nesterov;
     out->lr = sgd->lr;
     out->mu = sgd->momentum;
     out->wd = sgd->weight_decay;
@@ -329,7 +338,7 @@ int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
     return SELSYNC_OK;
 }
 
-int32_t check_plan(selsync_ctx *ctx, selsync_plan *plan, bool need_grads)
+int32_t check_plan(selsync_ctx *ctx, selsync_plan *plan, bool need_grads, bool need_momenta = false)
 {
     if (!ctx)
         return SELSYNC_ERR_INVALID_ARG;
@@ -338,7 +347,9 @@ int32_t check_plan(selsync_ctx *ctx, selsync_plan *plan, bool need_grads)
     if (plan->ctx != ctx)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "plan belongs to a different context");
     if (need_grads && !plan->has_grads)
-        return fail(ctx, SELSYNC_ERR_STATE, "plan was created without gradients/momenta");
+        return fail(ctx, SELSYNC_ERR_STATE, "plan was created without gradients");
+    if (need_momenta && !plan->has_momenta)
+        return fail(ctx, SELSYNC_ERR_STATE, "plan was created without momentum buffers");
     return check_device(ctx);
 }
 
@@ -568,8 +579,8 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
         return rc;
     if (!params || !global)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "params and global are required");
-    if ((grads == nullptr) != (momenta == nullptr))
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "grads and momenta must be given together");
+    if (momenta != nullptr && grads == nullptr)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "momenta given without grads");
     const bool mixed = master != nullptr;
     if (mixed != (global_lowp != nullptr))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "master and global_lowp must be given together (mixed mode)");
@@ -597,7 +608,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     if (grads) {
         if ((rc = check_lists(ctx, "grads", grads, K, T, numel, mixed ? lowp : SELSYNC_F32, false, ivals)))
             return rc;
-        if ((rc = check_lists(ctx, "momenta", momenta, K, T, numel, SELSYNC_F32, true, ivals)))
+        if (momenta && (rc = check_lists(ctx, "momenta", momenta, K, T, numel, SELSYNC_F32, true, ivals)))
             return rc;
     }
     if (mixed) {
@@ -630,7 +641,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             for (int t = 0; t < T; ++t) {
                 TensorRec r{};
                 r.g = grads[k].tensors[t].data;
-                r.m = static_cast<float *>(momenta[k].tensors[t].data);
+                r.m = momenta ? static_cast<float *>(momenta[k].tensors[t].data) : nullptr;
                 if (mixed) {
                     r.w = static_cast<float *>(master[k].tensors[t].data);
                     r.lowp = static_cast<uint16_t *>(params[k].tensors[t].data);
@@ -640,7 +651,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
                 }
                 tensor_chunk_begin[(size_t)k * T + t] = (int32_t)chunks.size();
                 const int ph = stream_phase(r.w, 4);
-                const bool al = stream_phase(r.g, mixed ? 2 : 4) == ph && stream_phase(r.m, 4) == ph &&
+                const bool al = stream_phase(r.g, mixed ? 2 : 4) == ph && (!r.m || stream_phase(r.m, 4) == ph) &&
                                 (!mixed || stream_phase(r.lowp, 2) == ph);
                 r.numel = numel[t];
                 r.flags = al ? (kChunkAligned | head_bits(ph)) : 0u;
@@ -692,7 +703,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     std::vector<float *> agg_g(T);
     std::vector<uint16_t *> agg_gc(mixed ? T : 0);
     std::vector<const void *> agg_grad(grads ? (size_t)T * K : 0);
-    std::vector<float *> agg_m(grads ? (size_t)T * K : 0);
+    std::vector<float *> agg_m(momenta ? (size_t)T * K : 0);
     for (int t = 0; t < T; ++t) {
         agg_g[t] = static_cast<float *>(global[0].tensors[t].data);
         const int ph = stream_phase(agg_g[t], 4);
@@ -707,8 +718,8 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             }
             al = al && stream_phase(agg_w[(size_t)t * K + k], 4) == ph;
         }
-        bool al_grads = grads != nullptr;
-        if (grads) {
+        bool al_grads = momenta != nullptr;
+        if (momenta) {
             for (int k = 0; k < K; ++k) {
                 agg_grad[(size_t)t * K + k] = grads[k].tensors[t].data;
                 agg_m[(size_t)t * K + k] = static_cast<float *>(momenta[k].tensors[t].data);
@@ -727,7 +738,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             c.off = (uint64_t)off;
             agg_chunks.push_back(c);
         });
-        if (grads)
+        if (momenta)
             split_tensor(numel[t], ga_chunk, [&](int64_t off, int64_t n) {
                 AggChunkRec c;
                 c.t = (uint32_t)t;
@@ -747,6 +758,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->P = P;
     plan->mixed = mixed;
     plan->has_grads = grads != nullptr;
+    plan->has_momenta = momenta != nullptr;
     plan->h_recs = recs;
     plan->numel = numel;
     plan->ivals = ivals;
@@ -817,6 +829,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->tab.per = per;
     plan->tab.slot_per = slot_per;
     plan->tab.chunk_elems = (uint32_t)chunk;
+    plan->tab.has_momentum = momenta != nullptr;
     plan->d_chunk_begin = reinterpret_cast<int32_t *>(b + o_begin);
     plan->n_segs = (int)segs.size();
     plan->d_segs = reinterpret_cast<int2 *>(b + o_segs);
@@ -932,7 +945,7 @@ extern "C" int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, cons
     if (rc)
         return rc;
     SgdArgs a;
-    if ((rc = resolve_sgd(ctx, sgd, &a)))
+    if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
@@ -967,7 +980,7 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
     if (rc)
         return rc;
     SgdArgs a;
-    if ((rc = resolve_sgd(ctx, sgd, &a)))
+    if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
@@ -1075,7 +1088,7 @@ extern "C" int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const sel
         if (!plan || !plan->ctx)
             return SELSYNC_ERR_INVALID_ARG;
         selsync_ctx *ctx = plan->ctx;
-        int32_t rc = check_plan(ctx, plan, true);
+        int32_t rc = check_plan(ctx, plan, true, true);
         if (rc)
             return rc;
         if (!v)
@@ -1117,7 +1130,7 @@ extern "C" int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const sel
 extern "C" int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam,
                                            void *stream)
 {
-    int32_t rc = check_plan(ctx, plan, true);
+    int32_t rc = check_plan(ctx, plan, true, true);
     if (rc)
         return rc;
     AdamArgs a;
@@ -1136,7 +1149,7 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
                                      int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                                      int32_t *sync_out)
 {
-    int32_t rc = check_plan(ctx, plan, true);
+    int32_t rc = check_plan(ctx, plan, true, true);
     if (rc)
         return rc;
     AdamArgs a;
@@ -1165,13 +1178,13 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
 extern "C" int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, int32_t mode,
                                      void *stream)
 {
-    int32_t rc = check_plan(ctx, plan, true);
+    int32_t rc = check_plan(ctx, plan, true, true);
     if (rc)
         return rc;
     if (mode != 0 && mode != 1)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "mode must be 0 (follow the decision) or 1 (always aggregate)");
     SgdArgs a;
-    if ((rc = resolve_sgd(ctx, sgd, &a)))
+    if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
@@ -1187,11 +1200,11 @@ extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const s
                                    int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                                    int32_t *sync_out)
 {
-    int32_t rc = check_plan(ctx, plan, true);
+    int32_t rc = check_plan(ctx, plan, true, true);
     if (rc)
         return rc;
     SgdArgs a;
-    if ((rc = resolve_sgd(ctx, sgd, &a)))
+    if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     {

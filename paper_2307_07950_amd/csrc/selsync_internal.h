@@ -111,6 +111,7 @@ struct AdamArgs {
 struct SgdArgs {
     float lr, mu, wd, gs;
     int32_t first;
+    int32_t nesterov;
 };
 
 // Launch shape for the streaming kernels.
@@ -132,6 +133,7 @@ struct StreamTable {
     int per = 0;                   // slots per stripe; 0 in the linear layout
     int slot_per = 0;              // `per` for chunk_slot(): > 0 only when chunks are stored striped (layout 0)
     uint32_t chunk_elems = 0;
+    bool has_momentum = true;      // false: momentum-free plan (no m buffers bound)
 };
 
 enum StreamMode { kNormOnly = 0, kUpdateOnly = 1, kUpdateAndNorm = 2 };

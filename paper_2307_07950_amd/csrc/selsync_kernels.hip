@@ -111,8 +111,10 @@ __device__ __forceinline__ double wave_sum(double v)
 // Local SGD with momentum and weight decay (Alg. 1 line 9), one rounding per operation:
 //   gh = fl(gs*g); x += gh^2 in fp64 (the product of two fp32 values is exact in fp64);
 //   d = fl(gh + fl(wd*w)); m = first ? d : fl(fl(mu*m) + d); w = fl(w - fl(lr*m)).
+// Nesterov form: the step direction is fl(d + fl(mu*m)) with the new m instead of m.
 struct SgdOpt {
     typedef SgdArgs Args;
+    static constexpr bool kMomentum = true;
     static constexpr bool kSecondMoment = false;
     template <bool UPD, bool NORM>
     static __device__ __forceinline__ void elem(float g, float &w, float &m, float &, const Args &a, double &acc)
@@ -128,8 +130,34 @@ struct SgdOpt {
                 const float mm = a.mu * m;
                 mom = mm + d;
             }
-            const float stepv = a.lr * mom;
+            float dir = mom;
+            if (a.nesterov) {
+                const float look = a.mu * mom;
+                dir = d + look;
+            }
+            const float stepv = a.lr * dir;
             m = mom;
+            w = w - stepv;
+        }
+    }
+};
+
+// Momentum-free SGD (the Transformer recipe of Sec. IV-A): no buffer is read or written,
+//   gh = fl(gs*g); d = fl(gh + fl(wd*w)); w = fl(w - fl(lr*d)).
+struct PlainSgdOpt {
+    typedef SgdArgs Args;
+    static constexpr bool kMomentum = false;
+    static constexpr bool kSecondMoment = false;
+    template <bool UPD, bool NORM>
+    static __device__ __forceinline__ void elem(float g, float &w, float &, float &, const Args &a, double &acc)
+    {
+        const float gh = a.gs * g;
+        if (NORM)
+            acc = __builtin_fma((double)gh, (double)gh, acc);
+        if (UPD) {
+            const float dec = a.wd * w;
+            const float d = gh + dec;
+            const float stepv = a.lr * d;
             w = w - stepv;
         }
     }
@@ -142,6 +170,7 @@ struct SgdOpt {
 // On the first step the moment buffers are not read (taken as zero).
 struct AdamOpt {
     typedef AdamArgs Args;
+    static constexpr bool kMomentum = true;
     static constexpr bool kSecondMoment = true;
     template <bool UPD, bool NORM>
     static __device__ __forceinline__ void elem(float g, float &w, float &m, float &v, const Args &a, double &acc)
@@ -268,7 +297,7 @@ __device__ __forceinline__ void load_tile(const Chunk &ck, uint32_t base, uint32
                 t.g[u] = ld<NT>(g4 + i);
             if (UPD) {
                 t.w[u] = ld<NT>(w4 + i);
-                if (!first) {
+                if (OPT::kMomentum && !first) {
                     t.m[u] = ld<NT>(m4 + i);
                     if (OPT::kSecondMoment)
                         t.v[u] = ld<NT>(v4 + i);
@@ -295,7 +324,8 @@ __device__ __forceinline__ void finish_tile(const Chunk &ck, uint32_t base, uint
             elem4<OPT, UPD, NORM>(t.g[u], t.w[u], t.m[u], t.v[u], a, acc);
             if (UPD) {
                 st<NT>(w4 + i, t.w[u]);
-                st<NT>(m4 + i, t.m[u]);
+                if (OPT::kMomentum)
+                    st<NT>(m4 + i, t.m[u]);
                 if (OPT::kSecondMoment)
                     st<NT>(v4 + i, t.v[u]);
                 if (MIXED) {
@@ -331,7 +361,7 @@ __device__ __forceinline__ void scalar_range(const Chunk &ck, uint32_t begin, ui
         float w = 0.f, m = 0.f, v = 0.f;
         if (UPD) {
             w = wp[e];
-            if (!a.first) {
+            if (OPT::kMomentum && !a.first) {
                 m = mp[e];
                 if (OPT::kSecondMoment)
                     v = vp[e];
@@ -340,7 +370,8 @@ __device__ __forceinline__ void scalar_range(const Chunk &ck, uint32_t begin, ui
         OPT::template elem<UPD, NORM>(g, w, m, v, a, acc);
         if (UPD) {
             wp[e] = w;
-            mp[e] = m;
+            if (OPT::kMomentum)
+                mp[e] = m;
             if (OPT::kSecondMoment)
                 vp[e] = v;
             if (MIXED)
@@ -1064,6 +1095,8 @@ hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables 
 hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
                          hipStream_t s)
 {
+    if (!tab.has_momentum)
+        return launch_stream_o<PlainSgdOpt>(mode, mixed, tab, sgd, cfg, s);
     return launch_stream_o<SgdOpt>(mode, mixed, tab, sgd, cfg, s);
 }
 

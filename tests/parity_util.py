@@ -75,15 +75,17 @@ class LockStep:
 
     def __init__(self, B, shapes_numel: Sequence[int], K: int, delta: float, window: int = 25, alpha: float = -1.0,
                  mixed: bool = False, init_params: Optional[List[np.ndarray]] = None, misalign: int = 0,
-                 tuning: Optional[dict] = None, seed: int = 0, misalign_g: Optional[int] = None):
+                 tuning: Optional[dict] = None, seed: int = 0, misalign_g: Optional[int] = None,
+                 momentum_free: bool = False):
         self.B, self.K, self.mixed = B, K, mixed
+        self.momentum_free = momentum_free       # no momentum buffers on either side (plain SGD)
         self.numel = list(shapes_numel)
         if init_params is None:
             r = np.random.default_rng(seed)
             init_params = [(r.standard_normal(n) * 0.05).astype(np.float32) for n in self.numel]
         # host state (oracle side)
         self.h_w = [[a.copy() for a in init_params] for _ in range(K)]          # fp32 params / masters
-        self.h_m = [[np.zeros_like(a) for a in init_params] for _ in range(K)]
+        self.h_m = None if momentum_free else [[np.zeros_like(a) for a in init_params] for _ in range(K)]
         self.h_glob = [np.zeros_like(a) for a in init_params]
         if mixed:
             self.h_c = [[W.round_to_bf16_bits(a) for a in init_params] for _ in range(K)]
@@ -93,7 +95,7 @@ class LockStep:
         self.oracle = O.OracleSelSync(K, delta, window, alpha)
         # device state
         self.d_w = [[to_dev(a, misalign) for a in self.h_w[k]] for k in range(K)]
-        self.d_m = [[to_dev(a, misalign) for a in self.h_m[k]] for k in range(K)]
+        self.d_m = None if momentum_free else [[to_dev(a, misalign) for a in self.h_m[k]] for k in range(K)]
         self.d_glob = [to_dev(a, misalign) for a in self.h_glob]
         if mixed:
             self.d_c = [[to_dev(a, misalign) for a in self.h_c[k]] for k in range(K)]
@@ -154,21 +156,21 @@ class LockStep:
 
     # ---- one step on both sides
     def step(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True,
-             compare_tensors: bool = True):
+             compare_tensors: bool = True, nesterov: bool = False):
         B = self.B
         plan = self.plans[slot]
         first = self.steps_done == 0
         if fused:
-            dec = self.ctx.step(plan, lr, mu, wd, gs, first_step=int(first), blocking=True)
+            dec = self.ctx.step(plan, lr, mu, wd, gs, first_step=int(first), blocking=True, nesterov=nesterov)
         else:
             dec = self.ctx.track_grad_change(plan, gs, blocking=True)
-            self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first))
+            self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first), nesterov=nesterov)
             self.ctx.aggregate_params(plan, always=False)
         g = self.h_grads[slot]
         rec = self.oracle.track(g, gs)
         for k in range(self.K):
-            O.sgd_update(self.h_w[k], self.h_m[k], g[k], lr, mu, wd, gs, first,
-                         None if not self.mixed else self.h_c[k])
+            O.sgd_update(self.h_w[k], None if self.momentum_free else self.h_m[k], g[k], lr, mu, wd, gs, first,
+                         None if not self.mixed else self.h_c[k], nesterov=nesterov)
         sync = self._check_decision(dec, rec)
         if sync:
             pre = [np.max(np.abs(np.stack([self.h_w[k][t] for k in range(self.K)])), axis=0).astype(np.float64)
@@ -216,20 +218,21 @@ class LockStep:
                                                                          "second moment[%d][%d]" % (k, i)))
         return dec, rec
 
-    def step_ga(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True):
+    def step_ga(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True,
+                nesterov: bool = False):
         """One iteration under gradient aggregation (Sec. III-C) on both sides."""
         plan = self.plans[slot]
         first = self.steps_done == 0
         glob_before = [to_host(x) for x in self.d_glob]
         if fused:
-            dec = self.ctx.step_ga(plan, lr, mu, wd, gs, first_step=int(first), blocking=True)
+            dec = self.ctx.step_ga(plan, lr, mu, wd, gs, first_step=int(first), blocking=True, nesterov=nesterov)
         else:
             dec = self.ctx.track_grad_change(plan, gs, blocking=True)
-            self.ctx.ga_update(plan, lr, mu, wd, gs, first_step=int(first), always=False)
+            self.ctx.ga_update(plan, lr, mu, wd, gs, first_step=int(first), always=False, nesterov=nesterov)
         g = self.h_grads[slot]
         rec = self.oracle.track(g, gs)
         sync = self._check_decision(dec, rec)
-        O.ga_update(g, self.h_w, self.h_m, lr, mu, wd, gs, first, bool(sync), self.h_c)
+        O.ga_update(g, self.h_w, self.h_m, lr, mu, wd, gs, first, bool(sync), self.h_c, nesterov=nesterov)
         self.steps_done += 1
         self.compare(after_sync=False)
         for t in range(len(self.numel)):        # gradient aggregation never writes the global model
@@ -240,8 +243,11 @@ class LockStep:
         torch.cuda.synchronize()
         for k in range(self.K):
             for t in range(len(self.numel)):
-                gw, gm = to_host(self.d_w[k][t]), to_host(self.d_m[k][t])
-                self.worst_ulp = max(self.worst_ulp, assert_update_close(gm, self.h_m[k][t], "momentum[%d][%d]" % (k, t)))
+                gw = to_host(self.d_w[k][t])
+                if not self.momentum_free:
+                    gm = to_host(self.d_m[k][t])
+                    self.worst_ulp = max(self.worst_ulp,
+                                         assert_update_close(gm, self.h_m[k][t], "momentum[%d][%d]" % (k, t)))
                 if after_sync:
                     assert_average_close(gw, self.h_w[k][t], self._pre_scale[t], "averaged params[%d][%d]" % (k, t))
                 else:
@@ -271,7 +277,8 @@ class LockStep:
         for k in range(self.K):
             for t in range(len(self.numel)):
                 self.h_w[k][t][...] = to_host(self.d_w[k][t])
-                self.h_m[k][t][...] = to_host(self.d_m[k][t])
+                if not self.momentum_free:
+                    self.h_m[k][t][...] = to_host(self.d_m[k][t])
                 if self.mixed:
                     self.h_c[k][t][...] = to_host(self.d_c[k][t])
 

@@ -45,7 +45,7 @@ def test_struct_layouts_are_plain_c(B):
     assert ctypes.sizeof(B.selsync_tensor) == 24
     assert ctypes.sizeof(B.selsync_tensor_list) == 16
     assert ctypes.sizeof(B.selsync_config) == 24
-    assert ctypes.sizeof(B.selsync_sgd) == 20
+    assert ctypes.sizeof(B.selsync_sgd) == 24
     assert ctypes.sizeof(B.selsync_stats) == 40
     assert ctypes.sizeof(B.selsync_tuning) == 36
 

@@ -619,6 +619,103 @@ def test_gradient_aggregation_always_mode_and_bsp_equivalence(B):
     ls.close()
 
 
+# ================================================================= variants: momentum-free SGD, Nesterov momentum
+
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 3])
+@pytest.mark.parametrize("tuning", [None, dict(chunk_elems=1024, stream_variant=22, table_layout=1)])
+def test_momentum_free_sgd_matches_oracle(B, mixed, misalign, tuning):
+    # plain SGD of the Transformer recipe (Sec. IV-A): plans without momentum buffers
+    numel = [70001, 5, 4096, 0, 1023]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=31,
+                     momentum_free=True, tuning=tuning)
+    r = rng(140)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    syncs = 0
+    for t in range(9):
+        dec, rec = ls.step([0, 1, 2, 2, 0, 1, 1, 2, 0][t], 2.0 * 0.8 ** t, 0.0, [0.0, 1e-4][t % 2], [1.0, 0.7][t % 2],
+                           fused=(t % 3 != 1))
+        syncs += rec.sync
+    assert 0 < syncs < 9 and ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+    ls.close()
+
+
+def test_momentum_free_plan_rejects_momentum_adam_and_gradient_aggregation(B):
+    K = 2
+    ctx = B.SelSync(K, 0.3)
+    mk = lambda n: torch.zeros(n, dtype=torch.float32, device="cuda")
+    g, p, glob = [[mk(100)] for _ in range(K)], [[mk(100)] for _ in range(K)], [mk(100)]
+    plan = ctx.plan(g, p, None, glob)
+
+    def status(fn):
+        with pytest.raises(B.SelSyncError) as e:
+            fn()
+        return e.value.status
+
+    ctx.local_step(plan, 0.1, 0.0)
+    assert status(lambda: ctx.local_step(plan, 0.1, 0.9)) == B.SELSYNC_ERR_INVALID_ARG
+    assert status(lambda: ctx.step(plan, 0.1, 0.0, nesterov=True)) == B.SELSYNC_ERR_INVALID_ARG
+    assert status(lambda: ctx.ga_update(plan, 0.1, 0.0)) == B.SELSYNC_ERR_STATE
+    assert status(lambda: ctx.step_ga(plan, 0.1, 0.0)) == B.SELSYNC_ERR_STATE
+    assert status(lambda: ctx.bind_second_moment(plan, [[mk(100)] for _ in range(K)])) == B.SELSYNC_ERR_STATE
+    # momenta without gradients make no sense
+    assert status(lambda: ctx.plan(None, p, [[mk(100)] for _ in range(K)], glob)) == B.SELSYNC_ERR_INVALID_ARG
+    # Nesterov needs momentum > 0 on an ordinary plan too
+    full = ctx.plan(g, p, [[mk(100)] for _ in range(K)], glob)
+    assert status(lambda: ctx.local_step(full, 0.1, 0.0, nesterov=True)) == B.SELSYNC_ERR_INVALID_ARG
+    sgd = B.selsync_sgd(0.1, 0.9, 0.0, 1.0, 0, 2)
+    assert B.selsync_local_step(ctx._h, full._h, ctypes.byref(sgd), None) == B.SELSYNC_ERR_INVALID_ARG
+    ctx.close()
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 2])
+def test_nesterov_momentum_matches_oracle(B, mixed, misalign):
+    numel = [70001, 5, 4096, 0, 1023]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=32)
+    r = rng(150)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    syncs = 0
+    for t in range(9):
+        dec, rec = ls.step([0, 1, 2, 2, 0, 1, 1, 2, 0][t], 0.05, 0.9, 1e-4, [1.0, 0.7][t % 2], fused=(t % 3 != 1),
+                           nesterov=True)
+        syncs += rec.sync
+    assert 0 < syncs < 9 and ls.worst_ulp == 0
+    ls.close()
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+def test_nesterov_under_gradient_aggregation_matches_oracle(B, mixed):
+    numel = [33333, 7, 2048]
+    K = 4
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, seed=33)
+    r = rng(160)
+    for slot in range(2):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 3 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    syncs = 0
+    for t in range(6):
+        dec, rec = ls.step_ga([0, 1, 1, 0, 1, 0][t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0), nesterov=True)
+        syncs += rec.sync
+    assert 0 < syncs < 6 and ls.worst_ulp == 0
+    ls.close()
+
+
 # ================================================================= the five workloads, lock step
 
 @pytest.mark.parametrize("name,shrink,steps,compare_every", [
