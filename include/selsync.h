@@ -221,21 +221,27 @@ int32_t selsync_plan_info(const selsync_plan *plan, int32_t *num_tensors, int64_
 
 /*
  * Pure host helper (no GPU needed): the chunking rule of the multi-tensor chunk table
- * for ONE replica.  Every tensor is cut from element 0 into pieces of chunk_elems
- * (<= 0: the default) with one shorter last piece; empty tensors produce no chunk.
- * Writes up to `capacity` entries of (tensor index, first element, element count) to
- * the HOST arrays (each may be NULL) and the total number of chunks to *num_chunks.
+ * for ONE replica.  Tensors are cut where their ADDRESSES cross multiples of the chunk size
+ * (chunk_elems elements; <= 0: the default): lead_elems[t] in [0, chunk_elems) says how many
+ * elements past such an address tensor t starts (NULL: all 0, i.e. cutting from element 0),
+ * so the first piece has up to chunk_elems - lead elements, then full pieces, then one
+ * shorter last piece; empty tensors produce no chunk.  (A plan takes the lead from the
+ * device addresses of the bound tensors.)  Writes up to `capacity` entries of
+ * (tensor index, first element, element count) to the HOST arrays (each may be NULL) and
+ * the total number of chunks to *num_chunks.
  */
-int32_t selsync_chunk_table_preview(const int64_t *numel, int32_t num_tensors, int32_t chunk_elems,
-                                    int32_t capacity, int32_t *tensor_out, int64_t *offset_out,
-                                    int32_t *count_out, int32_t *num_chunks);
+int32_t selsync_chunk_table_preview(const int64_t *numel, const int32_t *lead_elems, int32_t num_tensors,
+                                    int32_t chunk_elems, int32_t capacity, int32_t *tensor_out,
+                                    int64_t *offset_out, int32_t *count_out, int32_t *num_chunks);
 
 /* ---- the per-step path ---------------------------------------------------------- */
 
 /*
  * RelativeGradChange for all K workers (Alg. 1 lines 8, 10-13; Eq. 2; Sec. III-A/B):
- * x_k = ||grad_scale*g_k||^2 over every tensor of worker k (fp64 accumulation,
- * deterministic), pushed into worker k's window; S_k = weight-normalised EWMA over the
+ * x_k = ||grad_scale*g_k||^2 over every tensor of worker k (fp64 accumulation in a fixed
+ * order: the same bits on every run for tensors at the same addresses modulo the chunk
+ * size; another placement regroups the sum, a difference of about 1e-16 relative),
+ * pushed into worker k's window; S_k = weight-normalised EWMA over the
  * window; Delta_k = |S_k - S_k_prev| / S_k_prev; flag_k = Delta_k >= delta;
  * sync = OR_k flag_k; the local/sync counters advance.  The decision stays on the
  * device for selsync_aggregate_params.  If `blocking` != 0 the call waits for the

@@ -96,7 +96,7 @@ PROTOTYPES = {
     "selsync_plan_create": (_i32, [_vp, _tl, _tl, _tl, _tl, _tl, _tl, ctypes.POINTER(_vp)]),
     "selsync_plan_destroy": (_i32, [_vp]),
     "selsync_plan_info": (_i32, [_vp, _ip, ctypes.POINTER(ctypes.c_int64), _ip, _ip]),
-    "selsync_chunk_table_preview": (_i32, [ctypes.POINTER(ctypes.c_int64), _i32, _i32, _i32, _ip,
+    "selsync_chunk_table_preview": (_i32, [ctypes.POINTER(ctypes.c_int64), _ip, _i32, _i32, _i32, _ip,
                                            ctypes.POINTER(ctypes.c_int64), _ip, _ip]),
     "selsync_track_grad_change": (_i32, [_vp, _vp, ctypes.c_float, _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_local_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp]),

@@ -257,13 +257,54 @@ int stream_phase(const void *p, size_t elem_size)
 
 uint32_t head_bits(int phase) { return (uint32_t)((4 - phase) & 3) << kChunkHeadShift; }
 
-// The chunking rule of the multi-tensor tables: every tensor is cut, from element 0,
-// into pieces of `chunk` elements with one shorter last piece; empty tensors give none.
+// The chunking rule of the multi-tensor tables.  A tensor whose first element lies `lead`
+// elements past a chunk-size-aligned address (0 <= lead < chunk) is cut where its ADDRESSES
+// cross multiples of the chunk size: a first piece of up to chunk - lead elements, full
+// pieces, one shorter last piece.  Piece j covers elements [j*chunk - lead, (j+1)*chunk - lead)
+// clipped to [0, numel); empty tensors give none.  With lead = 0 this is plain cutting
+// from element 0.  A wavefront's 1 KiB accesses then never straddle cache lines or DRAM
+// interleave boundaries, wherever in an arena the tensor starts.
 template <typename Emit>
-void split_tensor(int64_t numel, int chunk, Emit emit)
+void split_tensor(int64_t numel, int chunk, int lead, Emit emit)
 {
-    for (int64_t off = 0; off < numel; off += chunk)
-        emit(off, std::min<int64_t>(chunk, numel - off));
+    if (numel <= 0)
+        return;
+    const int64_t vend = (int64_t)lead + numel;
+    for (int64_t j = 0; j * chunk < vend; ++j) {
+        const int64_t b = std::max<int64_t>(j * chunk, lead) - lead;
+        const int64_t e = std::min<int64_t>((j + 1) * chunk, vend) - lead;
+        emit(b, e - b, j);
+    }
+}
+
+// One stream of a chunk (address, element size, bytes it moves per element).
+struct StreamRef {
+    const void *p;
+    int elem_size;
+    int weight;
+};
+
+// The lead (see split_tensor) that aligns the most traffic: every stream proposes
+// (address / element size) mod chunk; the proposal backed by the most bytes wins, the
+// first stream breaking ties.
+int vote_lead(const std::vector<StreamRef> &streams, int chunk)
+{
+    int best = 0, best_w = -1;
+    for (size_t i = 0; i < streams.size(); ++i) {
+        if (!streams[i].p)
+            continue;
+        const int li = (int)((reinterpret_cast<uintptr_t>(streams[i].p) / (uintptr_t)streams[i].elem_size) % (uintptr_t)chunk);
+        int w = 0;
+        for (size_t j = 0; j < streams.size(); ++j)
+            if (streams[j].p &&
+                (int)((reinterpret_cast<uintptr_t>(streams[j].p) / (uintptr_t)streams[j].elem_size) % (uintptr_t)chunk) == li)
+                w += streams[j].weight;
+        if (w > best_w) {
+            best_w = w;
+            best = li;
+        }
+    }
+    return best;
 }
 
 // Elements per aggregation chunk.  Each thread keeps K*U 128-bit loads in flight; up to
@@ -655,11 +696,14 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
                                 (!mixed || stream_phase(r.lowp, 2) == ph);
                 r.numel = numel[t];
                 r.flags = al ? (kChunkAligned | head_bits(ph)) : 0u;
+                // bytes per element: w and m are read and written, g is read, the bf16 copy written
+                r.lead = (uint32_t)vote_lead({{r.w, 4, 8}, {r.m, 4, 8}, {r.g, mixed ? 2 : 4, mixed ? 2 : 4},
+                                              {r.lowp, 2, 2}}, chunk);
                 recs[(size_t)k * T + t] = r;
-                split_tensor(numel[t], chunk, [&](int64_t off, int64_t) {
+                split_tensor(numel[t], chunk, (int)r.lead, [&](int64_t, int64_t, int64_t j) {
                     ChunkRec c;
                     c.rec = (uint32_t)((size_t)k * T + t);
-                    c.j = (uint32_t)(off / chunk);
+                    c.j = (uint32_t)j;
                     chunks.push_back(c);
                 });
             }
@@ -731,22 +775,36 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             agg_gc[t] = static_cast<uint16_t *>(global_lowp[0].tensors[t].data);
             al = al && stream_phase(agg_gc[t], 2) == ph;
         }
-        split_tensor(numel[t], agg_chunk, [&](int64_t off, int64_t n) {
+        // only a tensor's first piece can start off vector alignment: later pieces start on
+        // chunk-size-aligned addresses of the streams that share the phase
+        std::vector<StreamRef> refs;
+        refs.push_back({agg_g[t], 4, 4});
+        for (int k = 0; k < K; ++k)
+            refs.push_back({agg_w[(size_t)t * K + k], 4, 8});
+        split_tensor(numel[t], agg_chunk, vote_lead(refs, agg_chunk), [&](int64_t off, int64_t n, int64_t j) {
             AggChunkRec c;
             c.t = (uint32_t)t;
-            c.n_flags = (uint32_t)n | (al ? (kChunkAligned | head_bits(ph)) : 0u) | (al_grads ? kChunkAlignedGrads : 0u);
+            c.n_flags = (uint32_t)n | (al ? (kChunkAligned | (j == 0 ? head_bits(ph) : 0u)) : 0u) |
+                        (al_grads ? kChunkAlignedGrads : 0u);
             c.off = (uint64_t)off;
             agg_chunks.push_back(c);
         });
-        if (momenta)
-            split_tensor(numel[t], ga_chunk, [&](int64_t off, int64_t n) {
+        if (momenta) {
+            refs.clear();
+            for (int k = 0; k < K; ++k) {
+                refs.push_back({agg_w[(size_t)t * K + k], 4, 8});
+                refs.push_back({agg_m[(size_t)t * K + k], 4, 8});
+                refs.push_back({agg_grad[(size_t)t * K + k], mixed ? 2 : 4, mixed ? 2 : 4});
+            }
+            split_tensor(numel[t], ga_chunk, vote_lead(refs, ga_chunk), [&](int64_t off, int64_t n, int64_t j) {
                 AggChunkRec c;
                 c.t = (uint32_t)t;
-                c.n_flags = (uint32_t)n | (al ? (kChunkAligned | head_bits(ph)) : 0u) |
+                c.n_flags = (uint32_t)n | (al ? (kChunkAligned | (j == 0 ? head_bits(ph) : 0u)) : 0u) |
                             (al_grads ? kChunkAlignedGrads : 0u);
                 c.off = (uint64_t)off;
                 ga_chunks.push_back(c);
             });
+        }
     }
     if (agg_chunks.size() > (size_t)INT32_MAX || ga_chunks.size() > (size_t)INT32_MAX)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan");
@@ -886,9 +944,9 @@ extern "C" int32_t selsync_plan_info(const selsync_plan *plan, int32_t *num_tens
     return SELSYNC_OK;
 }
 
-extern "C" int32_t selsync_chunk_table_preview(const int64_t *numel, int32_t num_tensors, int32_t chunk_elems,
-                                               int32_t capacity, int32_t *tensor_out, int64_t *offset_out,
-                                               int32_t *count_out, int32_t *num_chunks)
+extern "C" int32_t selsync_chunk_table_preview(const int64_t *numel, const int32_t *lead_elems, int32_t num_tensors,
+                                               int32_t chunk_elems, int32_t capacity, int32_t *tensor_out,
+                                               int64_t *offset_out, int32_t *count_out, int32_t *num_chunks)
 {
     if (!num_chunks || num_tensors < 0 || (num_tensors > 0 && !numel))
         return SELSYNC_ERR_INVALID_ARG;
@@ -899,7 +957,10 @@ extern "C" int32_t selsync_chunk_table_preview(const int64_t *numel, int32_t num
     for (int t = 0; t < num_tensors; ++t) {
         if (numel[t] < 0)
             return SELSYNC_ERR_INVALID_ARG;
-        split_tensor(numel[t], chunk, [&](int64_t off, int64_t n) {
+        const int lead = lead_elems ? lead_elems[t] : 0;
+        if (lead < 0 || lead >= chunk)
+            return SELSYNC_ERR_INVALID_ARG;
+        split_tensor(numel[t], chunk, lead, [&](int64_t off, int64_t n, int64_t) {
             if (total < capacity) {
                 if (tensor_out)
                     tensor_out[total] = t;

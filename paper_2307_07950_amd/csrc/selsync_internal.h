@@ -20,12 +20,13 @@ struct alignas(64) TensorRec {
     float *v;        // fp32 second-moment buffer (Adam variant only, else null)
     int64_t numel;   // elements of the tensor
     uint32_t flags;  // kChunkAligned | head bits (same meaning as in AggChunkRec::n_flags)
-    uint32_t pad_;
+    uint32_t lead;   // elements between the last chunk-size-aligned address and the first element
 };
 
-// One unit of work of the multi-tensor streaming kernel: chunk j of one tensor of one
-// worker, i.e. elements [j*chunk_elems, min((j+1)*chunk_elems, numel)).  8 bytes: at 256
-// elements per chunk the table is 1/128 of one fp32 stream.
+// One unit of work of the multi-tensor streaming kernel: piece j of one tensor of one
+// worker, i.e. elements [j*chunk_elems - lead, (j+1)*chunk_elems - lead) clipped to
+// [0, numel): pieces are cut where the tensor's addresses cross multiples of the chunk
+// size.  8 bytes: at 256 elements per chunk the table is 1/128 of one fp32 stream.
 struct ChunkRec {
     uint32_t rec;   // index into the TensorRec table; kNoChunk marks a padding slot
     uint32_t j;     // chunk index inside the tensor

@@ -14,7 +14,8 @@
 // workgroups that each carry as little work as one vector per lane and stream (the
 // hardware dispatcher then streams through the model in order, one retired wave at a
 // time), tables laid out per XCD, and no atomics (every partial has a fixed slot and
-// every sum a fixed order, so results are run-to-run identical).
+// every sum a fixed order, so results are run-to-run identical for tensors at the same
+// addresses modulo the chunk size -- the cutting of tensors into pieces follows addresses).
 //
 // fp32 arithmetic of the update is written to round once per operation; the file
 // is compiled with -ffp-contract=off and the pragma below so no multiply-add is fused.
@@ -253,13 +254,20 @@ __device__ __forceinline__ Chunk lookup_chunk(const TensorRec *__restrict__ recs
         cr = slots[slot];
     const bool real = cr.rec != kNoChunk;
     ck.r = recs[real ? cr.rec : 0u];
-    ck.off = (uint64_t)cr.j * chunk_elems;
-    const uint64_t rest = real ? (uint64_t)ck.r.numel - ck.off : 0u;
-    ck.n = rest < chunk_elems ? (uint32_t)rest : chunk_elems;
+    // piece j in "virtual" element indices (lead + element): [j*chunk, (j+1)*chunk) clipped to
+    // [lead, lead + numel)
+    const uint64_t lead = ck.r.lead;
+    const uint64_t vb = (uint64_t)cr.j * chunk_elems;
+    const uint64_t vlast = lead + (uint64_t)ck.r.numel;
+    const uint64_t ve = vb + chunk_elems < vlast ? vb + chunk_elems : vlast;
+    ck.off = vb > lead ? vb - lead : 0u;
+    ck.n = real ? (uint32_t)(ve - lead - ck.off) : 0u;
     ck.head = 0;
     ck.nvec = 0;
     if (ck.r.flags & kChunkAligned) {
-        const uint32_t h = (ck.r.flags >> kChunkHeadShift) & 3u;
+        // only the first piece can start off vector alignment; later ones start on a
+        // chunk-size-aligned address
+        const uint32_t h = cr.j == 0 ? (ck.r.flags >> kChunkHeadShift) & 3u : 0u;
         ck.head = h < ck.n ? h : ck.n;
         ck.nvec = (ck.n - ck.head) / 4;
     }

@@ -18,17 +18,22 @@ AVG_RTOL = 1e-6         # averaged parameters, relative to max(|mean|, max_k |w_
 UPDATE_ULP = 1          # updated parameters / momenta, fp32 ulps
 
 
+ARENA_ALIGN = 1 << 16
+
+
 def to_dev(a: np.ndarray, misalign: int = 0) -> torch.Tensor:
-    """Upload a host array.  uint16 arrays are bf16 bit patterns.  `misalign` > 0
-    places the tensor that many ELEMENTS past a 256-byte aligned address."""
+    """Upload a host array.  uint16 arrays are bf16 bit patterns.  The tensor is placed
+    `misalign` ELEMENTS past a 64 KiB aligned address: the library cuts tensors where
+    their addresses cross multiples of the chunk size, so a reproducible placement makes
+    the fp64 grouping of the norm -- and with it every bit of a run -- reproducible."""
     if a.dtype == np.uint16:
         t = torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16)
     else:
         t = torch.from_numpy(a.copy())
-    if misalign == 0:
-        return t.cuda()
-    buf = torch.empty(t.numel() + misalign + 64, dtype=t.dtype, device="cuda")
-    view = buf[misalign:misalign + t.numel()]
+    es = t.element_size()
+    buf = torch.empty(t.numel() + misalign + ARENA_ALIGN // es + 64, dtype=t.dtype, device="cuda")
+    skip = ((-buf.data_ptr()) % ARENA_ALIGN) // es + misalign
+    view = buf[skip:skip + t.numel()]
     view.copy_(t)
     return view
 

@@ -93,15 +93,16 @@ def test_null_arguments_are_errors_not_crashes(B):
     assert B.selsync_profile_enable(None, 1, 10) == B.SELSYNC_ERR_INVALID_ARG
 
 
-def chunk_preview(B, numel, chunk):
+def chunk_preview(B, numel, chunk, lead=None):
     arr = (ctypes.c_int64 * max(1, len(numel)))(*numel)
+    la = None if lead is None else (ctypes.c_int32 * max(1, len(numel)))(*lead)
     n = ctypes.c_int32()
-    assert B.selsync_chunk_table_preview(arr, len(numel), chunk, 0, None, None, None, ctypes.byref(n)) == 0
+    assert B.selsync_chunk_table_preview(arr, la, len(numel), chunk, 0, None, None, None, ctypes.byref(n)) == 0
     cap = n.value
     t = (ctypes.c_int32 * max(1, cap))()
     o = (ctypes.c_int64 * max(1, cap))()
     c = (ctypes.c_int32 * max(1, cap))()
-    assert B.selsync_chunk_table_preview(arr, len(numel), chunk, cap, t, o, c, ctypes.byref(n)) == 0
+    assert B.selsync_chunk_table_preview(arr, la, len(numel), chunk, cap, t, o, c, ctypes.byref(n)) == 0
     assert n.value == cap
     return list(t)[:cap], list(o)[:cap], list(c)[:cap]
 
@@ -132,15 +133,49 @@ def test_chunk_table_covers_every_element_exactly_once(B, chunk):
         assert t == sorted(t)
 
 
+@pytest.mark.parametrize("chunk", [256, 1024, 4096])
+def test_chunk_pieces_are_cut_at_chunk_aligned_addresses(B, chunk):
+    import numpy as np
+    r = np.random.default_rng(chunk)
+    numel = [0, 1, 3, chunk - 1, chunk, chunk + 1, 5 * chunk + 7, 100003, 2, chunk // 2]
+    lead = [int(x) for x in r.integers(0, chunk, len(numel))]
+    lead[4], lead[6] = 0, chunk - 1
+    t, o, c = chunk_preview(B, numel, chunk, lead)
+    seen = {}
+    for ti, oi, ci in zip(t, o, c):
+        assert 0 < ci <= chunk
+        seen.setdefault(ti, []).append((oi, ci))
+    for ti, n in enumerate(numel):
+        pieces = sorted(seen.get(ti, []))
+        pos = 0
+        for idx, (oi, ci) in enumerate(pieces):
+            assert oi == pos                               # no gap, no overlap
+            if idx > 0:
+                assert (lead[ti] + oi) % chunk == 0        # every later piece starts on an aligned address
+            if idx < len(pieces) - 1:
+                assert (lead[ti] + oi + ci) % chunk == 0   # and every piece but the last ends on one
+            pos += ci
+        assert pos == n
+        assert len(pieces) == (-(-(lead[ti] + n) // chunk) if n else 0)
+    assert t == sorted(t)
+    # a lead outside [0, chunk) is refused
+    n_out = ctypes.c_int32()
+    arr = (ctypes.c_int64 * 1)(10)
+    for bad in (-1, chunk):
+        la = (ctypes.c_int32 * 1)(bad)
+        assert B.selsync_chunk_table_preview(arr, la, 1, chunk, 0, None, None, None,
+                                             ctypes.byref(n_out)) == B.SELSYNC_ERR_INVALID_ARG
+
+
 def test_chunk_table_preview_rejects_bad_arguments(B):
     n = ctypes.c_int32()
     arr = (ctypes.c_int64 * 2)(10, -1)
-    assert B.selsync_chunk_table_preview(arr, 2, 8192, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(arr, None, 2, 8192, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
     arr = (ctypes.c_int64 * 2)(10, 5)
-    assert B.selsync_chunk_table_preview(arr, 2, 1000, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
-    assert B.selsync_chunk_table_preview(arr, 2, 8192, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
-    assert B.selsync_chunk_table_preview(None, 2, 8192, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
-    assert B.selsync_chunk_table_preview(arr, 2, 0, 0, None, None, None, ctypes.byref(n)) == 0 and n.value == 2
+    assert B.selsync_chunk_table_preview(arr, None, 2, 1000, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(arr, None, 2, 8192, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(None, None, 2, 8192, 0, None, None, None, ctypes.byref(n)) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_chunk_table_preview(arr, None, 2, 0, 0, None, None, None, ctypes.byref(n)) == 0 and n.value == 2
 
 
 def test_product_path_has_no_cpu_fallback_and_never_imports_the_oracle():

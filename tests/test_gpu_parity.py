@@ -619,6 +619,40 @@ def test_gradient_aggregation_always_mode_and_bsp_equivalence(B):
     ls.close()
 
 
+# ================================================================= tensors anywhere in an arena
+
+@pytest.mark.parametrize("off_w,off_g", [(37, 37), (37, 41), (100, 4), (255, 255), (260, 0), (64, 192), (129, 2)])
+@pytest.mark.parametrize("mixed", [False, True])
+def test_tensors_at_arbitrary_offsets_inside_larger_buffers(B, off_w, off_g, mixed):
+    # pieces are cut where addresses cross multiples of the chunk size, whatever the tensor's start address is;
+    # parameters/momenta and gradients may sit at different offsets (equal or different vector phase)
+    numel = [70001, 5, 4096, 0, 1023, 255, 257]
+    K = 2
+    for tuning in (None, dict(chunk_elems=1024, stream_variant=22, agg_chunk_elems=512, agg_shape=642, ga_chunk_elems=256)):
+        ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=off_w, misalign_g=off_g,
+                         seed=41, tuning=tuning)
+        r = rng(170)
+        for slot in range(2):
+            grads = []
+            for k in range(K):
+                gk = [(r.standard_normal(n) * 1e-2 * (1 + 3 * slot)).astype(np.float32) for n in numel]
+                grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+            ls.bind_grads(slot, grads)
+        syncs = 0
+        for t in range(6):
+            dec, rec = ls.step([0, 1, 1, 0, 1, 0][t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0))
+            syncs += rec.sync
+        for t in range(3):
+            dec, rec = ls.step_ga([1, 0, 1][t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0))
+            syncs += rec.sync
+        assert 0 < syncs < 9 and ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+        got = ls.ctx.read_tensor_norms(ls.plans[1])
+        for k in range(K):
+            for t in range(len(numel)):
+                assert got[k][t] == pytest.approx(O.norm_sq([ls.h_grads[1][k][t]], 1.0), rel=1e-12, abs=0.0)
+        ls.close()
+
+
 # ================================================================= variants: momentum-free SGD, Nesterov momentum
 
 @pytest.mark.parametrize("mixed", [False, True])
