@@ -22,7 +22,7 @@ namespace {
 
 constexpr int kDefaultChunkElems = kChunkGranule;   // one 128-bit access per lane and stream: a one-shot grid
 constexpr int kDefaultXcdSwizzle = 0;
-constexpr int kDefaultGaChunkElems = 1024;
+constexpr int kDefaultGaChunkElems = 4096;   // few waves: on "local" decisions this launch only reads the decision
 constexpr int kMaxWorkers = 1024;
 constexpr int kSegChunks = 2048;          // chunks per segment of the intermediate reduction
 constexpr int kDirectChunkLimit = 16384;  // up to this many chunks the tracker sums them directly
@@ -1236,6 +1236,24 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
 
 // =============================================================================== variant: gradient aggregation
 
+namespace {
+// The update of a gradient-aggregation step.  Following the decision (mode 0) takes two
+// predicated launches, of which exactly one does work: on "local" the streaming kernel in its
+// fastest shape (each worker applies its own gradient), on "sync" the K-way kernel (every worker
+// applies the mean gradient).  Mode 1 always aggregates.
+int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a, int mode, hipStream_t s)
+{
+    if (mode == 0) {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s, &ctx->td.out->sync, 0));
+    }
+    ProfScope p(ctx, 2, s);
+    HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg, plan->K,
+                                  &ctx->td.out->sync, mode, a, plan->agg_cfg, s));
+    return SELSYNC_OK;
+}
+}  // namespace
+
 extern "C" int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, int32_t mode,
                                      void *stream)
 {
@@ -1248,11 +1266,8 @@ extern "C" int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const
     if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    {
-        ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg, plan->K,
-                                      &ctx->td.out->sync, mode, a, plan->agg_cfg, s));
-    }
+    if ((rc = enqueue_ga_update(ctx, plan, a, mode, s)))
+        return rc;
     ctx->local_steps += 1;
     return SELSYNC_OK;
 }
@@ -1274,11 +1289,8 @@ extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const s
     }
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
-    {
-        ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg, plan->K,
-                                      &ctx->td.out->sync, 0, a, plan->agg_cfg, s));
-    }
+    if ((rc = enqueue_ga_update(ctx, plan, a, 0, s)))
+        return rc;
     ctx->local_steps += 1;
     if (blocking)
         return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);

@@ -171,8 +171,9 @@ constexpr int kStripeGranule = 16;
 // Smallest aggregation tile: 256 threads x one 128-bit vector.
 constexpr int kAggTileElems = 1024;
 
+// With `pred` the launch only works while *pred == pred_want (device-side word), else it exits.
 hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
-                         hipStream_t s);
+                         hipStream_t s, const int32_t *pred = nullptr, int pred_want = 0);
 
 // Adam variant of the streaming kernel: update (+ norm partials when with_norm).
 hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a,
@@ -194,8 +195,9 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
 hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32_t *range_begin, int nranges,
                                double *out, hipStream_t s);
 
-// Gradient-aggregation update (Sec. III-C): when the decision is "sync" (or mode 1) every worker
-// applies the mean gradient to its own parameters and momentum, otherwise its own gradient.
+// Synchronising update of gradient aggregation (Sec. III-C): when the decision is "sync" (or
+// mode 1) every worker applies the mean gradient to its own parameters and momentum; on a
+// "local" decision the launch does nothing (the caller runs the plain local update instead).
 hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
                             const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
                             hipStream_t s);

@@ -395,13 +395,18 @@ __device__ __forceinline__ void scalar_range(const Chunk &ck, uint32_t begin, ui
 // squared scaled gradients in that chunk's slot: fixed place, fixed order, no atomics.
 //   per > 0: striped table, workgroup b takes slots (b%8)*per + (b/8)*C + [0, C)
 //   per = 0: linear table, workgroup b takes slots b*C + [0, C)
+// With `pred` set the launch is predicated on a device-side word: it does its work only
+// while *pred == pred_want (the gradient-aggregation step runs this kernel on "local" decisions).
 template <class OPT, int U, int C, bool MIXED, int MODE, bool NT>
 __global__ __launch_bounds__(64) void k_stream(const TensorRec *__restrict__ recs, const ChunkRec *__restrict__ slots,
                                                int nslots, int nwg, int per, uint32_t chunk_elems,
-                                               double *__restrict__ partials, typename OPT::Args a)
+                                               double *__restrict__ partials, typename OPT::Args a,
+                                               const int32_t *__restrict__ pred, int32_t pred_want)
 {
     constexpr bool UPD = MODE != kNormOnly;
     constexpr bool NORM = MODE != kUpdateOnly;
+    if (pred != nullptr && *pred != pred_want)
+        return;
     const uint32_t tid = threadIdx.x;
 
     for (int b = blockIdx.x; b < nwg; b += gridDim.x) {
@@ -859,18 +864,21 @@ __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, dou
     return r;
 }
 
-// Update of all K workers under gradient aggregation.  One workgroup walks one chunk of
-// one tensor across the K workers: with the decision "sync" the mean gradient is applied
-// to every worker's own (w, m); otherwise each worker applies its own gradient (the plain
-// local update).  K compile-time (KC > 0) keeps all 3K loads of a vector in flight.
+// The synchronising update of gradient aggregation (Sec. III-C): one workgroup walks one
+// piece of one tensor across the K workers and applies the mean gradient to every worker's
+// own (w, m).  Launched on every step of that variant: unless `always`, it does this only
+// when the device-side decision says "sync" and otherwise exits at once (the plain local
+// update of such a step is the streaming kernel's job).  K compile-time (KC > 0) keeps all
+// 3K loads of a vector in flight.
 template <int BLOCK, int KC, bool MIXED, bool NT>
 __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, int nchunks,
                                                      AggTables tabs, int K, double invK, int pow2,
-                                                     const int32_t *__restrict__ sync_flag, int mode, SgdArgs a,
+                                                     const int32_t *__restrict__ sync_flag, int always, SgdArgs a,
                                                      int xcd_per)
 {
     constexpr int KM = KC > 0 ? KC : 1;
-    const bool sync = mode == 1 || *sync_flag != 0;
+    if (!always && *sync_flag == 0)
+        return;
     SgdArgs a1 = a;   // applied to the mean gradient, which is already scaled
     a1.gs = 1.f;
     const uint32_t tid = threadIdx.x;
@@ -917,18 +925,10 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                         if (!a.first)
                             mv[k] = ld<NT>(mp[k] + i);
                     }
-                    if (sync) {
-                        const f32x4 gbar = mean_grad4<KC>(gv, KC, a.gs, invK, pow2);
-#pragma unroll
-                        for (int k = 0; k < KC; ++k)
-                            elem4<true, false>(gbar, wv[k], mv[k], a1, unused);
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < KC; ++k)
-                            elem4<true, false>(gv[k], wv[k], mv[k], a, unused);
-                    }
+                    const f32x4 gbar = mean_grad4<KC>(gv, KC, a.gs, invK, pow2);
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
+                        elem4<true, false>(gbar, wv[k], mv[k], a1, unused);
                         st<NT>(wp[k] + i, wv[k]);
                         st<NT>(mp[k] + i, mv[k]);
                         if (MIXED) {
@@ -946,35 +946,23 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
         for (uint32_t j = tid; j < n - done; j += BLOCK) {
             const uint32_t i = j < head ? j : j + done;
             const uint64_t e = ch.off + i;
-            float gbar = 0.f;
-            if (sync) {
-                double s = 0.0;
-                for (int k = 0; k < K; ++k) {
-                    float g;
-                    if (MIXED)
-                        g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
-                    else
-                        g = as_global<const float>(tabs.g[row + k])[e];
-                    const float gh = a.gs * g;
-                    s += (double)gh;
-                }
-                gbar = finish_mean(s, K, invK, pow2);
+            double s = 0.0;
+            for (int k = 0; k < K; ++k) {
+                float g;
+                if (MIXED)
+                    g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
+                else
+                    g = as_global<const float>(tabs.g[row + k])[e];
+                const float gh = a.gs * g;
+                s += (double)gh;
             }
+            const float gbar = finish_mean(s, K, invK, pow2);
             for (int k = 0; k < K; ++k) {
                 SELSYNC_GLOBAL float *wq = as_global<float>(tabs.w[row + k]);
                 SELSYNC_GLOBAL float *mq = as_global<float>(tabs.m[row + k]);
                 float w = wq[e];
                 float m = a.first ? 0.f : mq[e];
-                if (sync) {
-                    elem<true, false>(gbar, w, m, a1, unused);
-                } else {
-                    float g;
-                    if (MIXED)
-                        g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
-                    else
-                        g = as_global<const float>(tabs.g[row + k])[e];
-                    elem<true, false>(g, w, m, a, unused);
-                }
+                elem<true, false>(gbar, w, m, a1, unused);
                 wq[e] = w;
                 mq[e] = m;
                 if (MIXED)
@@ -991,14 +979,14 @@ constexpr int kBlock = 256;
 // Launch k_stream with the (U, C) shape named by `variant` = 10*C + U.
 template <class OPT, bool MIXED, int MODE, bool NT>
 hipError_t launch_stream_t(const StreamTable &tab, const typename OPT::Args &args, int grid_cap, int variant,
-                           hipStream_t s)
+                           const int32_t *pred, int pred_want, hipStream_t s)
 {
 #define SELSYNC_SHAPE(UU, CC)                                                                                       \
     do {                                                                                                            \
         const int nwg = tab.per > 0 ? 8 * (tab.per / (CC)) : (tab.nslots + (CC)-1) / (CC);                          \
         const int grid = grid_cap < nwg ? grid_cap : nwg;                                                           \
         hipLaunchKernelGGL((k_stream<OPT, UU, CC, MIXED, MODE, NT>), dim3(grid), dim3(64), 0, s, tab.recs, tab.slots, \
-                           tab.nslots, nwg, tab.per, tab.chunk_elems, tab.partials, args);                          \
+                           tab.nslots, nwg, tab.per, tab.chunk_elems, tab.partials, args, pred, pred_want);         \
         return hipGetLastError();                                                                                   \
     } while (0)
     switch (variant) {
@@ -1023,29 +1011,30 @@ hipError_t launch_stream_t(const StreamTable &tab, const typename OPT::Args &arg
 
 template <class OPT, bool MIXED, bool NT>
 hipError_t launch_stream_m(StreamMode mode, const StreamTable &tab, const typename OPT::Args &args, int grid_cap,
-                           int variant, hipStream_t s)
+                           int variant, const int32_t *pred, int pred_want, hipStream_t s)
 {
     switch (mode) {
     case kNormOnly:
-        return launch_stream_t<OPT, MIXED, kNormOnly, NT>(tab, args, grid_cap, variant, s);
+        return launch_stream_t<OPT, MIXED, kNormOnly, NT>(tab, args, grid_cap, variant, pred, pred_want, s);
     case kUpdateOnly:
-        return launch_stream_t<OPT, MIXED, kUpdateOnly, NT>(tab, args, grid_cap, variant, s);
+        return launch_stream_t<OPT, MIXED, kUpdateOnly, NT>(tab, args, grid_cap, variant, pred, pred_want, s);
     default:
-        return launch_stream_t<OPT, MIXED, kUpdateAndNorm, NT>(tab, args, grid_cap, variant, s);
+        return launch_stream_t<OPT, MIXED, kUpdateAndNorm, NT>(tab, args, grid_cap, variant, pred, pred_want, s);
     }
 }
 
 template <class OPT>
 hipError_t launch_stream_o(StreamMode mode, bool mixed, const StreamTable &tab, const typename OPT::Args &args,
-                           const LaunchCfg &cfg, hipStream_t s)
+                           const LaunchCfg &cfg, const int32_t *pred, int pred_want, hipStream_t s)
 {
     if (tab.nchunks <= 0)
         return hipSuccess;
+    const int g = cfg.grid, v = cfg.variant;
     if (mixed)
-        return cfg.nontemporal ? launch_stream_m<OPT, true, true>(mode, tab, args, cfg.grid, cfg.variant, s)
-                               : launch_stream_m<OPT, true, false>(mode, tab, args, cfg.grid, cfg.variant, s);
-    return cfg.nontemporal ? launch_stream_m<OPT, false, true>(mode, tab, args, cfg.grid, cfg.variant, s)
-                           : launch_stream_m<OPT, false, false>(mode, tab, args, cfg.grid, cfg.variant, s);
+        return cfg.nontemporal ? launch_stream_m<OPT, true, true>(mode, tab, args, g, v, pred, pred_want, s)
+                               : launch_stream_m<OPT, true, false>(mode, tab, args, g, v, pred, pred_want, s);
+    return cfg.nontemporal ? launch_stream_m<OPT, false, true>(mode, tab, args, g, v, pred, pred_want, s)
+                           : launch_stream_m<OPT, false, false>(mode, tab, args, g, v, pred, pred_want, s);
 }
 
 template <int KC, bool MIXED, bool NT>
@@ -1101,17 +1090,17 @@ hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables 
 // ---------------------------------------------------------------- launchers
 
 hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
-                         hipStream_t s)
+                         hipStream_t s, const int32_t *pred, int pred_want)
 {
     if (!tab.has_momentum)
-        return launch_stream_o<PlainSgdOpt>(mode, mixed, tab, sgd, cfg, s);
-    return launch_stream_o<SgdOpt>(mode, mixed, tab, sgd, cfg, s);
+        return launch_stream_o<PlainSgdOpt>(mode, mixed, tab, sgd, cfg, pred, pred_want, s);
+    return launch_stream_o<SgdOpt>(mode, mixed, tab, sgd, cfg, pred, pred_want, s);
 }
 
 hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a,
                               const LaunchCfg &cfg, hipStream_t s)
 {
-    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, cfg, s);
+    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, cfg, nullptr, 0, s);
 }
 
 hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs, int nsegs, double *seg_sums,
