@@ -53,6 +53,8 @@ def parse_args():
                          "(selsync_step_adam, 28 B per parameter); plain: momentum-free SGD on plans without momentum buffers "
                          "(12 B per parameter); nesterov: selsync_step with the Nesterov step direction")
     ap.add_argument("--window", type=int, default=0, help="EWMA window (default: the workload's, 25)")
+    ap.add_argument("--workers", type=int, default=0, help="replicas K held on the GPU (default: the workload's)")
+    ap.add_argument("--delta", type=float, default=-1.0, help="threshold (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events in the timed loop (roofline.achieved becomes null)")
@@ -165,7 +167,9 @@ def main():
     torch.cuda.set_device(0)
     from paper_2307_07950_amd import binding as B, workloads as W
 
-    wl = W.get(args.workload, shrink=args.shrink)
+    wl = W.get(args.workload, shrink=args.shrink, num_workers=args.workers if args.workers > 0 else None)
+    if args.delta >= 0:
+        wl.delta = args.delta
     K, P, T = wl.num_workers, wl.num_params, wl.num_tensors
     st = make_device_state(torch, wl, wl.seed)
     if args.window > 0:
