@@ -338,7 +338,7 @@ class OracleSelSync:
     num_workers: int
     delta: float
     window: int = 25
-    alpha: float = -1.0            # <= 0: num_workers / 100 (smoothing factor N/100, Sec. III-A)
+    alpha: float = -1.0            # <= 0: min(1, num_workers / 100) (smoothing factor N/100, Sec. III-A)
     steps_local: int = 0
     steps_sync: int = 0
     max_delta: float = 0.0
@@ -347,7 +347,8 @@ class OracleSelSync:
 
     def __post_init__(self):
         if self.alpha <= 0:
-            self.alpha = self.num_workers / 100.0
+            # N/100 is stated for N = 16; a smoothing factor lies in (0, 1], so beyond 100 workers it stays 1
+            self.alpha = min(1.0, self.num_workers / 100.0)
         self.trackers = [Tracker(self.window, self.alpha) for _ in range(self.num_workers)]
 
     def track(self, grads: Sequence[Sequence[np.ndarray]], grad_scale: float = 1.0) -> StepRecord:

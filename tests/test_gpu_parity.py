@@ -619,6 +619,36 @@ def test_gradient_aggregation_always_mode_and_bsp_equivalence(B):
     ls.close()
 
 
+# ================================================================= many workers
+
+@pytest.mark.parametrize("K", [17, 40, 130])
+@pytest.mark.parametrize("mixed", [False, True])
+def test_more_workers_than_one_tracker_round(B, K, mixed):
+    # the tracker workgroup handles 16 workers per round; the K-way kernels take the run-time-K path
+    numel = [3001, 64, 0, 7]
+    ls = PU.LockStep(B, numel, K, delta=0.2, window=6, mixed=mixed, seed=50 + K)
+    r = rng(180 + K)
+    for slot in range(2):
+        grads = []
+        for k in range(K):
+            scale = 1e-2 * (1 + 4 * slot) * (1.0 + 0.01 * k)
+            gk = [(r.standard_normal(n) * scale).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    syncs = 0
+    for t in range(6):
+        dec, rec = ls.step([0, 0, 1, 1, 0, 1][t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0))
+        syncs += rec.sync
+        assert len(dec.norm_sq) == K and dec.flags == rec.flags
+    for t in range(3):
+        dec, rec = ls.step_ga([1, 0, 1][t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0))
+        syncs += rec.sync
+    assert 0 < syncs < 9 and ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+    st = ls.ctx.stats()
+    assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
+    ls.close()
+
+
 # ================================================================= tensors anywhere in an arena
 
 @pytest.mark.parametrize("off_w,off_g", [(37, 37), (37, 41), (100, 4), (255, 255), (260, 0), (64, 192), (129, 2)])

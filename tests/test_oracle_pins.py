@@ -480,6 +480,19 @@ def test_nesterov_bf16_mode_master_matches_f32_path():
     assert copy.tobytes() == O.f32_to_bf16(master).tobytes()
 
 
+def test_default_smoothing_factor_is_workers_over_100_capped_at_one():
+    vals, _ = golden()
+    assert O.OracleSelSync(16, 0.3).alpha == pytest.approx(vals["alpha_at_16_workers"])
+    assert O.OracleSelSync(4, 0.3).alpha == 0.04
+    assert O.OracleSelSync(100, 0.3).alpha == 1.0
+    assert O.OracleSelSync(130, 0.3).alpha == 1.0        # never a negative weight (1 - alpha)^j
+    # at alpha = 1 only the newest sample counts: Delta is the relative change of the raw statistic
+    o = O.OracleSelSync(130, 0.3, window=5)
+    tr = o.trackers[0]
+    tr.push(2.0)
+    assert tr.push(3.0) == pytest.approx(0.5) and tr.push(1.5) == pytest.approx(0.5)
+
+
 def test_sgd_agrees_with_fp64_recomputation_and_is_elementwise():
     r = rng(24)
     n = 2000
