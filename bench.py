@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # plain copy kernel of known size (profiles/pmc_hbm_traffic_vgg11like_k4.txt); not measurable from inside this
 # process, so it is quoted for the workload it was measured on and null otherwise.
-MEASURED_TRAFFIC_BYTES = {("vgg11_like", 1): 1.0696e10}
+MEASURED_TRAFFIC_BYTES = {("vgg11_like", 1): 1.0679e10}
 
 
 def parse_args():
