@@ -135,7 +135,8 @@ typedef struct selsync_tuning {
     int32_t chunk_elems;       /* elements per chunk of the update/norm chunk table (multiple of 256)   */
     int32_t blocks_per_cu;     /* > 0: persistent grid of this many workgroups per compute unit;
                                   <= 0 (default): one workgroup per chunk                               */
-    int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default        */
+    int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default:
+                                  streaming when the replicas' working set is 128 MiB or more           */
     int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 256)         */
     int32_t stream_variant;    /* shape of the update/norm kernel, 10*C + U: each 64-lane wavefront takes C
                                   chunks at once with U 128-bit accesses per lane, stream and pass.

@@ -29,7 +29,7 @@ def rng(seed):
     return np.random.default_rng(seed)
 
 
-SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2, stream_variant=14)   # persistent grid, multi-pass chunks
+SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2, stream_variant=14, nontemporal=1)   # persistent grid, multi-pass chunks
 
 # tensor-size sets: tiny / ragged tails / several tiles / empty tensors / exactly one chunk
 SIZE_SETS = {
@@ -204,10 +204,12 @@ def test_many_chunks_take_the_segment_reduction_level(B, mixed, layout):
                                            (81, 256), (81, 512)])
 @pytest.mark.parametrize("layout", [0, 1, 2])
 @pytest.mark.parametrize("persistent", [0, 2])
-def test_every_kernel_shape_and_table_layout_gives_the_same_results(B, variant, chunk, layout, persistent):
+@pytest.mark.parametrize("nt", [0, 1])
+def test_every_kernel_shape_and_table_layout_gives_the_same_results(B, variant, chunk, layout, persistent, nt):
     numel = [100003, 513, 4096, 255]
     K = 2
-    tuning = dict(chunk_elems=chunk, blocks_per_cu=persistent, stream_variant=variant, table_layout=layout)
+    tuning = dict(chunk_elems=chunk, blocks_per_cu=persistent, stream_variant=variant, table_layout=layout,
+                  nontemporal=nt)
     for mixed in (False, True):
         ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, tuning=tuning, seed=4)
         r = rng(24)
@@ -260,7 +262,7 @@ def test_aggregate_kernel_shapes_give_identical_results(B, shape, chunk, K):
     numel = [70001, 5, 8192, 0, 33333]
     for mixed in (False, True):
         ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, seed=7,
-                         tuning=dict(agg_shape=shape, agg_chunk_elems=chunk, xcd_swizzle=K % 2))
+                         tuning=dict(agg_shape=shape, agg_chunk_elems=chunk, xcd_swizzle=K % 2, nontemporal=K % 2))
         r = rng(300 + K)
         for k in range(K):
             for t, n in enumerate(numel):
@@ -524,7 +526,8 @@ def test_partition_order_kernel_matches_oracle(B, D, N):
 def test_adam_variant_matches_oracle(B, mixed, misalign):
     numel = [70001, 5, 4096, 0, 1023]
     K = 3
-    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=21)
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=21,
+                     tuning=dict(nontemporal=int(misalign == 0)))
     r = rng(140)
     for slot in range(3):
         grads = []
@@ -576,7 +579,8 @@ def test_adam_bind_validation(B):
 @pytest.mark.parametrize("misalign", [0, 1])
 def test_gradient_aggregation_matches_oracle(B, K, mixed, misalign):
     numel = [70001, 5, 4096, 0, 1023]
-    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=19)
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=19,
+                     tuning=dict(nontemporal=K % 2))
     r = rng(110 + K)
     for slot in range(3):
         grads = []
