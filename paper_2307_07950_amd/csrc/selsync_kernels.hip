@@ -524,9 +524,36 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
     const double thr = *td.delta_thr;
     int32_t my_flag = 0, my_nonfinite = 0;
     double my_max = 0.0;
+    // counters are fetched up front so the read-modify-write at the end does not wait on memory
+    DecisionHeader hdr{};
+    if (threadIdx.x == 0)
+        hdr = *td.out;
 
     for (int k0 = 0; k0 < td.K; k0 += kTrackWaves) {
         const int kn = (td.K - k0) < kTrackWaves ? (td.K - k0) : kTrackWaves;
+
+        // The wave that owns a worker fetches that worker's tracker state and the newest 64 window
+        // samples now: these loads do not depend on the norm, so they overlap with phase 1.
+        int len = 0, head = 0, len_new = 0, had_prev = 0;
+        double pre_v = 0.0, pre_w = 0.0, sp = 0.0;
+        if (wave < kn) {
+            const int k = k0 + wave;
+            len = td.len[k];
+            head = td.head[k];
+            had_prev = td.has_prev[k];
+            sp = td.s_prev[k];
+            len_new = len < W ? len + 1 : W;
+            if (lane < len_new) {
+                pre_w = td.weights[lane];
+                if (lane > 0) {
+                    int pos = head - lane;
+                    if (pos < 0)
+                        pos += W;
+                    pre_v = td.hist[(size_t)k * W + pos];
+                }
+            }
+        }
+
         for (int r = 0; r < kn; ++r) {
             double acc = 0.0;
             if (partials != nullptr) {
@@ -561,17 +588,17 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
 
             // the window holds the previous `len` samples; the new one has age 0
             double *h = td.hist + (size_t)k * W;
-            const int len = td.len[k];
-            const int head = td.head[k];
-            const int len_new = len < W ? len + 1 : W;
             double num = 0.0, den = 0.0;
-            for (int j = lane; j < len_new; j += 64) {
+            if (lane < len_new) {
+                num = pre_w * (lane == 0 ? x : pre_v);
+                den = pre_w;
+            }
+            for (int j = lane + 64; j < len_new; j += 64) {      // windows longer than one wavefront
                 const double wgt = td.weights[j];
                 int pos = head - j;
                 if (pos < 0)
                     pos += W;
-                const double v = (j == 0) ? x : h[pos];
-                num += wgt * v;
+                num += wgt * h[pos];
                 den += wgt;
             }
             num = wave_sum(num);
@@ -579,10 +606,9 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
             if (lane == 0) {
                 const double s = num / den;
                 double d;
-                if (!td.has_prev[k]) {
+                if (!had_prev) {
                     d = 0.0;
                 } else {
-                    const double sp = td.s_prev[k];
                     if (sp == 0.0 && s == 0.0) {
                         d = 0.0;
                     } else {
@@ -622,21 +648,22 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
     __syncthreads();
     if (threadIdx.x == 0) {
         int32_t any = 0, nf = 0;
-        double mx = td.out->max_delta;
+        double mx = hdr.max_delta;
         for (int w = 0; w < kTrackWaves; ++w) {
             any |= s_flag[w];
             nf |= s_nonfinite[w];
             if (s_max[w] > mx)
                 mx = s_max[w];
         }
-        td.out->sync = any;
-        td.out->nonfinite_now = nf;
-        td.out->max_delta = mx;
-        td.out->nonfinite_steps += nf;
+        hdr.sync = any;
+        hdr.nonfinite_now = nf;
+        hdr.max_delta = mx;
+        hdr.nonfinite_steps += nf;
         if (any)
-            td.out->steps_sync += 1;
+            hdr.steps_sync += 1;
         else
-            td.out->steps_local += 1;
+            hdr.steps_local += 1;
+        *td.out = hdr;
     }
 }
 
