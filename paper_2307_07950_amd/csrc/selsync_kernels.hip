@@ -107,6 +107,30 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+// Sum over the 64 lanes with data-parallel-primitive moves (no LDS crossbar traffic, a few
+// cycles per step); result in lane 63.  Fixed order: inclusive scan inside each row of 16
+// lanes (shifts by 1, 2, 4, 8), then row 0's total is added to row 1 and row 2's to row 3,
+// then the total of rows 0-1 to rows 2-3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double v)
+{
+    // lanes without a valid source (or masked out) receive the `old` operand, 0, i.e. add +0.0
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+    return v + __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_sum_to_last_lane(double v)
+{
+    v = dpp_add<0x111, 0xf>(v);   // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);   // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);   // row_shr:8
+    v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // ---------------------------------------------------------------- optimiser policies
 
 // Local SGD with momentum and weight decay (Alg. 1 line 9), one rounding per operation:
@@ -437,8 +461,8 @@ __global__ __launch_bounds__(64) void k_stream(const TensorRec *__restrict__ rec
         if (NORM) {
 #pragma unroll
             for (int i = 0; i < C; ++i) {
-                const double s = wave_sum(acc[i]);
-                if (tid == 0 && ck[i].n > 0)
+                const double s = wave_sum_to_last_lane(acc[i]);
+                if (tid == 63 && ck[i].n > 0)
                     partials[s0 + i] = s;
             }
         }
