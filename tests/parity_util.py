@@ -81,7 +81,7 @@ class LockStep:
     def __init__(self, B, shapes_numel: Sequence[int], K: int, delta: float, window: int = 25, alpha: float = -1.0,
                  mixed: bool = False, init_params: Optional[List[np.ndarray]] = None, misalign: int = 0,
                  tuning: Optional[dict] = None, seed: int = 0, misalign_g: Optional[int] = None,
-                 momentum_free: bool = False):
+                 momentum_free: bool = False, misalign_m: Optional[int] = None, misalign_glob: Optional[int] = None):
         self.B, self.K, self.mixed = B, K, mixed
         self.momentum_free = momentum_free       # no momentum buffers on either side (plain SGD)
         self.numel = list(shapes_numel)
@@ -100,8 +100,10 @@ class LockStep:
         self.oracle = O.OracleSelSync(K, delta, window, alpha)
         # device state
         self.d_w = [[to_dev(a, misalign) for a in self.h_w[k]] for k in range(K)]
-        self.d_m = None if momentum_free else [[to_dev(a, misalign) for a in self.h_m[k]] for k in range(K)]
-        self.d_glob = [to_dev(a, misalign) for a in self.h_glob]
+        mm = misalign if misalign_m is None else misalign_m
+        mg = misalign if misalign_glob is None else misalign_glob
+        self.d_m = None if momentum_free else [[to_dev(a, mm) for a in self.h_m[k]] for k in range(K)]
+        self.d_glob = [to_dev(a, mg) for a in self.h_glob]
         if mixed:
             self.d_c = [[to_dev(a, misalign) for a in self.h_c[k]] for k in range(K)]
             self.d_gc = [to_dev(a, misalign) for a in self.h_gc]

@@ -687,6 +687,58 @@ def test_tensors_at_arbitrary_offsets_inside_larger_buffers(B, off_w, off_g, mix
         ls.close()
 
 
+# ================================================================= seeded random configurations
+
+@pytest.mark.parametrize("seed", list(range(96)))
+def test_random_configuration_matches_oracle(B, seed):
+    """Random tensor lists, placements, worker counts and launch shapes; fused, three-call and
+    gradient-aggregation steps in one run, everything compared with the oracle."""
+    r = rng(1000 + seed)
+    sizes = [0, 1, 2, 3, 5, 63, 64, 255, 256, 257, 511, 1000, 1024, 4099, 8192, 70001]
+    K = int(r.integers(1, 7))
+    T = int(r.integers(1, 9))
+    numel = [int(r.choice(sizes)) for _ in range(T)]
+    if sum(numel) == 0:
+        numel[0] = 777
+    mixed = bool(r.integers(0, 2))
+    chunk = int(r.choice([256, 512, 1024, 4096]))
+    shapes = [s for s in (11, 12, 14, 21, 22, 41, 42, 81)]
+    tuning = dict(chunk_elems=chunk, stream_variant=int(r.choice([0] + shapes)), table_layout=int(r.integers(0, 3)),
+                  blocks_per_cu=int(r.choice([0, 0, 1])), nontemporal=int(r.integers(0, 2)),
+                  agg_chunk_elems=int(r.choice([0, 256, 1024, 4096])),
+                  agg_shape=int(r.choice([0, 641, 642, 2561, 2562, 2564, 5121, 5122, 10241])),
+                  ga_chunk_elems=int(r.choice([0, 256, 1024])), xcd_swizzle=int(r.integers(0, 2)))
+    off = lambda: int(r.choice([0, 0, 1, 2, 3, 4, 17, 64, 100, 255, 256, 300]))
+    momentum_free = bool(r.integers(0, 4) == 0)
+    ls = PU.LockStep(B, numel, K, delta=float(r.choice([0.0, 0.1, 0.3])), window=int(r.choice([1, 3, 25])),
+                     alpha=float(r.choice([-1.0, 0.5, 1.0])), mixed=mixed, misalign=off(), misalign_g=off(),
+                     misalign_m=off(), misalign_glob=off(), seed=seed, tuning=tuning, momentum_free=momentum_free)
+    for slot in range(2):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 3 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    mu = 0.0 if momentum_free else float(r.choice([0.0, 0.9]))
+    nesterov = bool(mu > 0 and r.integers(0, 2))
+    for t in range(6):
+        ls.step(int(r.integers(0, 2)), 0.05, mu, float(r.choice([0.0, 1e-4])), float(r.choice([1.0, 0.5])),
+                fused=bool(r.integers(0, 2)), nesterov=nesterov)
+    if not momentum_free:
+        for t in range(3):
+            ls.step_ga(int(r.integers(0, 2)), 0.05, mu, 1e-4, 1.0, fused=bool(r.integers(0, 2)), nesterov=nesterov)
+        if r.integers(0, 2):
+            ls.enable_adam()
+            ls.steps_done = 0                      # Adam's bias correction counts its own steps from 1
+            for t in range(3):
+                ls.step_adam(int(r.integers(0, 2)), 1e-3, 0.9, 0.999, 1e-8, float(r.choice([0.0, 1e-4])), 1.0,
+                             fused=bool(r.integers(0, 2)))
+    assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+    st = ls.ctx.stats()
+    assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
+    ls.close()
+
+
 # ================================================================= variants: momentum-free SGD, Nesterov momentum
 
 @pytest.mark.parametrize("mixed", [False, True])
