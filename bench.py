@@ -305,6 +305,10 @@ def main():
             "k_aggregate_avg_ms_over_all_launches": agg_ms_all,      # local steps launch it too (it exits at once)
             "k_aggregate_est_ms_per_sync": (kern[2][1] / n_sync) if n_sync else None,
         }
+    # context only: the paper's end-to-end training results, on its own hardware (not this metric)
+    result["paper_context"] = ("training time vs BSP: up to 14x (abstract); VGG11 6.16x at delta 0.3, 13.75x at 0.5 "
+                               "(Table I) on 16 V100 workers + 1 parameter server over 5 Gbps; its gradient-change "
+                               "tracking takes 3.1 ms per step for VGG11 at window 25 on a V100 (Sec. IV-B)")
     if not args.no_cpu_baseline and args.variant == "pa":
         # release the GPU-side working set first: the oracle needs host memory only
         result["cpu_baseline"] = cpu_baseline(wl, lssr_run, args.cpu_steps)
