@@ -28,7 +28,10 @@
  *     to 16-byte alignment -- always true for 16-byte aligned buffers, and for views at the
  *     same element offset into aligned arenas -- the library peels up to 3 elements and
  *     runs 128-bit accesses over the rest; otherwise that tensor is processed element by
- *     element (same results, lower bandwidth).
+ *     element (same results, lower bandwidth).  Work is cut into pieces where a tensor's
+ *     ADDRESSES cross multiples of the piece size (1 KiB of fp32 by default), so a tensor
+ *     may start anywhere in an arena; it is fastest when the buffers of a tensor also
+ *     share their position relative to that size, as separately allocated tensors do.
  *   - Buffers that are written (params, momenta, masters, global) must not overlap
  *     each other or the gradients; this is checked at plan time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work
