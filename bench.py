@@ -145,12 +145,39 @@ def cpu_baseline(wl, lssr, steps_timed):
     O.average_params(w, glob, c, gc)
     t_sync = time.perf_counter() - t0
     per_step = t_local + (1.0 - lssr) * t_sync
-    return {
+    out = {
         "value": 1.0 / per_step, "unit": "steps/s", "cores": 1, "kind": "oracle",
         "sample": "%d full-size local steps (all K=%d replicas, %d params each) + 1 full-size aggregation, "
                   "combined with the run's LSSR %.3f; single thread, gcc -O2" % (steps_timed, K, sum(numel), lssr),
         "local_step_s": t_local, "aggregation_s": t_sync,
     }
+    # The same oracle calls spread over host threads where that changes no order of arithmetic: one thread
+    # per replica for norm + update (replicas are independent), one task per tensor for the aggregation.
+    from concurrent.futures import ThreadPoolExecutor
+    ncpu = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    nthreads = max(1, min(ncpu, 16))
+
+    def replica_step(k):
+        x = O.norm_sq(g[k], 1.0)
+        O.sgd_update(w[k], m[k], g[k], wl.lr, wl.momentum, wl.weight_decay, 1.0, False, None if c is None else c[k])
+        return x
+
+    def tensor_average(t):
+        O.average_params([[w[k][t]] for k in range(K)], [glob[t]],
+                         None if c is None else [[c[k][t]] for k in range(K)], None if gc is None else [gc[t]])
+
+    with ThreadPoolExecutor(nthreads) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(replica_step, range(K)))
+        tp_local = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        list(pool.map(tensor_average, range(len(numel))))
+        tp_sync = time.perf_counter() - t0
+    out["threaded"] = {"value": 1.0 / (tp_local + (1.0 - lssr) * tp_sync), "unit": "steps/s",
+                       "cores": min(nthreads, max(K, 1)), "local_step_s": tp_local, "aggregation_s": tp_sync,
+                       "how": "one thread per replica (norm + update), one task per tensor (aggregation); "
+                              "the order of every sum is unchanged"}
+    return out
 
 
 def main():
