@@ -53,6 +53,9 @@ def parse_args():
                          "(selsync_step_adam, 28 B per parameter); plain: momentum-free SGD on plans without momentum buffers "
                          "(12 B per parameter); nesterov: selsync_step with the Nesterov step direction")
     ap.add_argument("--window", type=int, default=0, help="EWMA window (default: the workload's, 25)")
+    ap.add_argument("--reps", type=int, default=1,
+                    help="after the timed region, time this many minus one further regions of --steps steps each and "
+                         "report median / min / max of all of them beside the headline figures")
     ap.add_argument("--workers", type=int, default=0, help="replicas K held on the GPU (default: the workload's)")
     ap.add_argument("--delta", type=float, default=-1.0, help="threshold (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -221,7 +224,7 @@ def main():
         for p in plans:
             ctx.bind_second_moment(p, st["v"])
 
-    total = args.warmup + args.steps
+    total = args.warmup + args.steps * max(1, args.reps)
     sig = wl.sigmas(total) if total <= wl.steps else [float(wl.sigma(t)) for t in range(total)]
 
     def run(t0, n):
@@ -267,6 +270,13 @@ def main():
     s1 = ctx.stats()
     kern = [ctx.profile_summary(kind) for kind in range(3)]
     ctx.profile_enable(False)
+    rep_ms = [elapsed / args.steps * 1e3]
+    for rep in range(1, max(1, args.reps)):
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
+        run(args.warmup + rep * args.steps, args.steps)
+        torch.cuda.synchronize()
+        rep_ms.append((time.perf_counter() - r0) / args.steps * 1e3)
 
     n_sync = s1["steps_sync"] - s0["steps_sync"]
     n_local = s1["steps_local"] - s0["steps_local"]
@@ -332,6 +342,9 @@ def main():
             "k_aggregate_avg_ms_over_all_launches": agg_ms_all,      # local steps launch it too (it exits at once)
             "k_aggregate_est_ms_per_sync": (kern[2][1] / n_sync) if n_sync else None,
         }
+    if len(rep_ms) > 1:
+        srt = sorted(rep_ms)
+        result["repeats"] = {"ms_per_step": rep_ms, "median": srt[len(srt) // 2], "min": srt[0], "max": srt[-1]}
     # context only: the paper's end-to-end training results, on its own hardware (not this metric)
     result["paper_context"] = ("training time vs BSP: up to 14x (abstract); VGG11 6.16x at delta 0.3, 13.75x at 0.5 "
                                "(Table I) on 16 V100 workers + 1 parameter server over 5 Gbps; its gradient-change "
