@@ -1112,8 +1112,6 @@ hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, const AggTables 
     default:
         break;
     }
-    if (KC == 0 || KC > 4)
-        SELSYNC_AGG(256, 1);
     SELSYNC_AGG(256, 4);
 #undef SELSYNC_AGG
 }
