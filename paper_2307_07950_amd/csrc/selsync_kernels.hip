@@ -529,8 +529,9 @@ constexpr int kTrackBlock = 1024;
 constexpr int kTrackWaves = kTrackBlock / 64;
 
 // One workgroup handles all K workers, kTrackWaves of them per round.
-//   phase 1 (a1, final pass): the whole block sums one worker's per-chunk partials in a
-//     fixed order (thread-strided, wave butterfly, then the wave results in wave order);
+//   phase 1 (a1, final pass): the waves are split evenly over the workers of the round; each
+//     group sums its worker's partials in a fixed order (thread-strided, wave butterfly, then
+//     the group's wave results in wave order);
 //   phase 2 (a2): wave v owns worker (round*16 + v): one window sample per lane for the
 //     weighted sums, lane 0 applies Eq. 2 and the delta rule.
 // Afterwards thread 0 ORs the flags (the all-gather of Alg. 1 collapses to this on one
@@ -578,17 +579,22 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
             }
         }
 
-        for (int r = 0; r < kn; ++r) {
+        // phase 1: the 16 waves are split evenly over the kn workers of this round, so every worker's
+        // partial sums are read at the same time: group r = waves [r*wpw, (r+1)*wpw) strides over worker r's
+        // values with 8 independent loads in flight per thread; fixed association order
+        const int wpw = kTrackWaves / kn;
+        const int r = wave / wpw, wi = wave - r * wpw;
+        {
             double acc = 0.0;
-            if (partials != nullptr) {
-                // 8 independent loads in flight per thread; fixed association order
+            if (r < kn && partials != nullptr) {
                 const int b = chunk_begin[k0 + r], e = chunk_begin[k0 + r + 1];
+                const int stride = wpw * 64;
                 double a8[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-                for (int i = b + (int)threadIdx.x; i < e; i += 8 * kTrackBlock) {
+                for (int i = b + wi * 64 + lane; i < e; i += 8 * stride) {
                     double v[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const int idx = i + j * kTrackBlock;
+                        const int idx = i + j * stride;
                         v[j] = idx < e ? partials[chunk_slot(idx, slot_per)] : 0.0;
                     }
 #pragma unroll
@@ -598,16 +604,15 @@ __global__ __launch_bounds__(kTrackBlock) void k_track(TrackerDev td, const doub
                 acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
             }
             acc = wave_sum(acc);
-            if (lane == 0)
-                s_part[r][wave] = acc;
+            if (lane == 0 && r < kn)
+                s_part[r][wi] = acc;
         }
         __syncthreads();
 
         if (wave < kn) {
             const int k = k0 + wave;
             double x = 0.0;
-#pragma unroll
-            for (int w = 0; w < kTrackWaves; ++w)
+            for (int w = 0; w < wpw; ++w)
                 x += s_part[wave][w];
 
             // the window holds the previous `len` samples; the new one has age 0
