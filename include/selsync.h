@@ -271,6 +271,9 @@ int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_s
  *   mode 0: only if the device-side decision of the last tracking call is "sync"
  *           (the kernel is launched and exits at once otherwise);
  *   mode 1: always.
+ * The results do not depend on the mode; the launch shape does: a predicated launch is
+ * built to exit cheaply, one that is certain to work (mode 1, or a threshold of 0, under
+ * which every step synchronises) is built for bandwidth.
  */
 int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan, int32_t mode, void *stream);
 

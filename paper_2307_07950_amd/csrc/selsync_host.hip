@@ -90,9 +90,12 @@ struct selsync_plan {
     std::vector<Interval> ivals;     // every bound buffer (checked again when more buffers are bound)
     bool has_second_moment = false;
     AggChunkRec *d_agg_chunks = nullptr;
+    AggChunkRec *d_agg_fine = nullptr;    // 256-element pieces: used when the host knows the launch will work
+    int n_agg_fine = 0;
     AggChunkRec *d_ga_chunks = nullptr;   // finer table for the gradient-aggregation update (always does work)
     AggTables agg{};
     int ga_block = 256;
+    bool agg_tuned = false;        // the caller chose the aggregation shape: no automatic choice
     LaunchCfg upd_cfg{1, 1, 0};
     LaunchCfg agg_cfg{1, 1, 0};
 
@@ -745,7 +748,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
         seg_begin[K] = (int32_t)segs.size();
     }
 
-    std::vector<AggChunkRec> agg_chunks, ga_chunks;
+    std::vector<AggChunkRec> agg_chunks, agg_fine, ga_chunks;
     std::vector<float *> agg_w((size_t)T * K);
     std::vector<uint16_t *> agg_c(mixed ? (size_t)T * K : 0);
     std::vector<float *> agg_g(T);
@@ -793,6 +796,14 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             c.off = (uint64_t)off;
             agg_chunks.push_back(c);
         });
+        split_tensor(numel[t], kChunkGranule, vote_lead(refs, kChunkGranule), [&](int64_t off, int64_t n, int64_t j) {
+            AggChunkRec c;
+            c.t = (uint32_t)t;
+            c.n_flags = (uint32_t)n | (al ? (kChunkAligned | (j == 0 ? head_bits(ph) : 0u)) : 0u) |
+                        (al_grads ? kChunkAlignedGrads : 0u);
+            c.off = (uint64_t)off;
+            agg_fine.push_back(c);
+        });
         if (momenta) {
             refs.clear();
             for (int k = 0; k < K; ++k) {
@@ -810,7 +821,8 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             });
         }
     }
-    if (agg_chunks.size() > (size_t)INT32_MAX || ga_chunks.size() > (size_t)INT32_MAX)
+    if (agg_chunks.size() > (size_t)INT32_MAX || agg_fine.size() > (size_t)INT32_MAX ||
+        ga_chunks.size() > (size_t)INT32_MAX)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan");
 
     std::unique_ptr<selsync_plan> plan(new selsync_plan());     // frees its device tables on any early exit
@@ -826,6 +838,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->ivals = ivals;
     plan->n_upd_chunks = nchunks;
     plan->n_agg_chunks = (int)agg_chunks.size();
+    plan->n_agg_fine = (int)agg_fine.size();
     plan->n_ga_chunks = (int)ga_chunks.size();
     plan->ga_block = ga_chunk < 1024 ? 64 : 256;     // one-wave workgroups for the fine tables
 
@@ -846,6 +859,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     const size_t o_tcb = take(tensor_chunk_begin.size() * sizeof(int32_t));
     const size_t o_tnorm = take((size_t)K * T * sizeof(double));
     const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
+    const size_t o_aggf = take(agg_fine.size() * sizeof(AggChunkRec));
     const size_t o_gac = take(ga_chunks.size() * sizeof(AggChunkRec));
     const size_t o_aw = take(agg_w.size() * sizeof(float *));
     const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
@@ -866,6 +880,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     put(o_segbegin, seg_begin.data(), seg_begin.size() * sizeof(int32_t));
     put(o_tcb, tensor_chunk_begin.data(), tensor_chunk_begin.size() * sizeof(int32_t));
     put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
+    put(o_aggf, agg_fine.data(), agg_fine.size() * sizeof(AggChunkRec));
     put(o_gac, ga_chunks.data(), ga_chunks.size() * sizeof(AggChunkRec));
     put(o_aw, agg_w.data(), agg_w.size() * sizeof(float *));
     put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
@@ -900,6 +915,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->d_tensor_chunk_begin = reinterpret_cast<int32_t *>(b + o_tcb);
     plan->d_tensor_norms = reinterpret_cast<double *>(b + o_tnorm);
     plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
+    plan->d_agg_fine = reinterpret_cast<AggChunkRec *>(b + o_aggf);
     plan->d_ga_chunks = reinterpret_cast<AggChunkRec *>(b + o_gac);
     plan->agg.w = reinterpret_cast<float *const *>(b + o_aw);
     plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
@@ -914,6 +930,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->upd_cfg.xcd_swizzle = ctx->tuning.xcd_swizzle >= 0 ? ctx->tuning.xcd_swizzle : kDefaultXcdSwizzle;
     plan->agg_cfg = plan->upd_cfg;
     plan->agg_cfg.agg_shape = ctx->tuning.agg_shape;
+    plan->agg_tuned = ctx->tuning.agg_shape != 0 || ctx->tuning.agg_chunk_elems > 0;
 
     ctx->live_plans += 1;
     *out = plan.release();
@@ -1004,6 +1021,28 @@ extern "C" int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *pla
     return SELSYNC_OK;
 }
 
+namespace {
+// a4.  mode 0 follows the device-side decision: the launch is shaped for a cheap exit (few, large
+// workgroups), because on most steps it only reads the decision.  When the host already knows that
+// the launch will work -- mode 1, or a threshold of 0, under which every step synchronises -- it
+// takes single-wavefront workgroups of 256 elements instead (75 % against 69 % of HBM peak).
+int32_t enqueue_aggregate(selsync_ctx *ctx, selsync_plan *plan, int mode, hipStream_t s)
+{
+    ProfScope p(ctx, 2, s);
+    const bool certain = mode == 1 || ctx->cfg.delta == 0.0;
+    if (certain && !plan->agg_tuned) {
+        LaunchCfg cfg = plan->agg_cfg;
+        cfg.agg_shape = 641;
+        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, plan->agg, plan->K,
+                                      &ctx->td.out->sync, 1, cfg, s));
+        return SELSYNC_OK;
+    }
+    HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
+                                  &ctx->td.out->sync, mode, plan->agg_cfg, s));
+    return SELSYNC_OK;
+}
+}  // namespace
+
 extern "C" int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream)
 {
     int32_t rc = check_plan(ctx, plan, true);
@@ -1029,11 +1068,8 @@ extern "C" int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan
     if (mode != 0 && mode != 1)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "mode must be 0 (if flagged) or 1 (always)");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    {
-        ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
-                                      &ctx->td.out->sync, mode, plan->agg_cfg, s));
-    }
+    if ((rc = enqueue_aggregate(ctx, plan, mode, s)))
+        return rc;
     return SELSYNC_OK;
 }
 
@@ -1055,11 +1091,8 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
-    {
-        ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
-                                      &ctx->td.out->sync, 0, plan->agg_cfg, s));
-    }
+    if ((rc = enqueue_aggregate(ctx, plan, 0, s)))
+        return rc;
     if (blocking)
         return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
     return SELSYNC_OK;
@@ -1228,11 +1261,8 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
-    {
-        ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
-                                      &ctx->td.out->sync, 0, plan->agg_cfg, s));
-    }
+    if ((rc = enqueue_aggregate(ctx, plan, 0, s)))
+        return rc;
     if (blocking)
         return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
     return SELSYNC_OK;
