@@ -92,10 +92,11 @@ struct selsync_plan {
     AggChunkRec *d_agg_chunks = nullptr;
     AggChunkRec *d_agg_fine = nullptr;    // 256-element pieces: used when the host knows the launch will work
     int n_agg_fine = 0;
-    AggChunkRec *d_ga_chunks = nullptr;   // finer table for the gradient-aggregation update (always does work)
+    AggChunkRec *d_ga_chunks = nullptr;   // table of the K-way gradient-aggregation kernel (predicated launches)
     AggTables agg{};
     int ga_block = 256;
     bool agg_tuned = false;        // the caller chose the aggregation shape: no automatic choice
+    bool ga_tuned = false;         // likewise for the gradient-aggregation kernel
     LaunchCfg upd_cfg{1, 1, 0};
     LaunchCfg agg_cfg{1, 1, 0};
 
@@ -931,6 +932,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->agg_cfg = plan->upd_cfg;
     plan->agg_cfg.agg_shape = ctx->tuning.agg_shape;
     plan->agg_tuned = ctx->tuning.agg_shape != 0 || ctx->tuning.agg_chunk_elems > 0;
+    plan->ga_tuned = ctx->tuning.ga_chunk_elems > 0;
 
     ctx->live_plans += 1;
     *out = plan.release();
@@ -1277,7 +1279,19 @@ namespace {
 // applies the mean gradient).  Mode 1 always aggregates.
 int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a, int mode, hipStream_t s)
 {
-    if (mode == 0) {
+    if (mode == 1 || ctx->cfg.delta == 0.0) {
+        // certain to aggregate (a threshold of 0 synchronises every step): one launch, shaped for bandwidth
+        ProfScope p(ctx, 2, s);
+        if (!plan->ga_tuned) {
+            HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, 64, plan->agg, plan->K,
+                                          &ctx->td.out->sync, 1, a, plan->agg_cfg, s));
+            return SELSYNC_OK;
+        }
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg,
+                                      plan->K, &ctx->td.out->sync, 1, a, plan->agg_cfg, s));
+        return SELSYNC_OK;
+    }
+    {
         ProfScope p(ctx, 0, s);
         HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s, &ctx->td.out->sync, 0));
     }
