@@ -52,6 +52,7 @@ struct selsync_ctx {
     TrackerDev td{};
     void *h_out = nullptr;         // pinned mirror of the decision block
     int64_t local_steps = 0;       // local updates enqueued since create/reset (automatic first-step)
+    bool tracked = false;          // a tracking pass has been enqueued since create/reset (a decision exists)
     int live_plans = 0;
     std::string err;
     // profiling
@@ -373,6 +374,7 @@ int32_t resolve_sgd(selsync_ctx *ctx, const selsync_plan *plan, const selsync_sg
 int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
 {
     plan->partials_valid = true;
+    ctx->tracked = true;
     ProfScope p(ctx, 1, s);
     if (plan->n_segs > 0) {
         HIP_TRY(ctx, launch_reduce(plan->tab.partials, plan->tab.slot_per, plan->d_segs, plan->n_segs,
@@ -548,6 +550,7 @@ extern "C" int32_t selsync_reset(selsync_ctx *ctx, void *stream)
         return rc;
     HIP_TRY(ctx, launch_reset(ctx->td, static_cast<hipStream_t>(stream)));
     ctx->local_steps = 0;
+    ctx->tracked = false;
     return SELSYNC_OK;
 }
 
@@ -1031,7 +1034,8 @@ namespace {
 int32_t enqueue_aggregate(selsync_ctx *ctx, selsync_plan *plan, int mode, hipStream_t s)
 {
     ProfScope p(ctx, 2, s);
-    const bool certain = mode == 1 || ctx->cfg.delta == 0.0;
+    // with a threshold of 0 every tracked step decides "sync" (Delta >= 0 always holds, +inf included)
+    const bool certain = mode == 1 || (ctx->cfg.delta == 0.0 && ctx->tracked);
     if (certain && !plan->agg_tuned) {
         LaunchCfg cfg = plan->agg_cfg;
         cfg.agg_shape = 641;
@@ -1279,7 +1283,7 @@ namespace {
 // applies the mean gradient).  Mode 1 always aggregates.
 int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a, int mode, hipStream_t s)
 {
-    if (mode == 1 || ctx->cfg.delta == 0.0) {
+    if (mode == 1 || (ctx->cfg.delta == 0.0 && ctx->tracked)) {
         // certain to aggregate (a threshold of 0 synchronises every step): one launch, shaped for bandwidth
         ProfScope p(ctx, 2, s);
         if (!plan->ga_tuned) {
