@@ -319,6 +319,35 @@ def test_aggregate_mode0_follows_device_decision(B):
     ls.close()
 
 
+def test_threshold_zero_aggregates_every_tracked_step_but_not_before_the_first_decision(B):
+    # delta = 0 turns SelSync into BSP (Sec. III-B): every tracked step synchronises.  Before any
+    # tracking call there is no decision yet, so a predicated aggregation does nothing.
+    numel = [50000, 7]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=0.0, seed=61)
+    for k in range(K):
+        ls.d_w[k][0].add_(float(k))
+    before = [[PU.to_host(x) for x in ls.d_w[k]] for k in range(K)]
+    ls.bind_grads(0, [[rng(400 + k).standard_normal(n).astype(np.float32) for n in numel] for k in range(K)])
+    ls.ctx.aggregate_params(ls.plans[0], always=False)
+    for k in range(K):
+        for t in range(len(numel)):
+            assert PU.to_host(ls.d_w[k][t]).tobytes() == before[k][t].tobytes()
+    dec = ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True)
+    assert dec.sync == 1
+    ls.ctx.aggregate_params(ls.plans[0], always=False)
+    want = (sum(b[0].astype(np.float64) for b in before) / K).astype(np.float32)
+    for k in range(K):
+        assert PU.to_host(ls.d_w[k][0]).tobytes() == want.tobytes()
+    assert PU.to_host(ls.d_glob[0]).tobytes() == want.tobytes()
+    ls.ctx.reset()
+    ls.d_w[1][1].add_(1.0)
+    snap = PU.to_host(ls.d_w[1][1])
+    ls.ctx.aggregate_params(ls.plans[0], always=False)          # after a reset there is again no decision
+    assert PU.to_host(ls.d_w[1][1]).tobytes() == snap.tobytes()
+    ls.close()
+
+
 # ================================================================= a2 + whole steps
 
 def test_fused_step_is_bit_identical_to_three_calls(B):
