@@ -345,6 +345,21 @@ def main():
     if len(rep_ms) > 1:
         srt = sorted(rep_ms)
         result["repeats"] = {"ms_per_step": rep_ms, "median": srt[len(srt) // 2], "min": srt[0], "max": srt[-1]}
+    if args.variant == "pa" and result.get("roofline"):
+        # context for the roofline fraction: what a plain library copy kernel (1 GiB read + 1 GiB written)
+        # sustains on this very box, measured after the timed region
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            torch.mul(src, 1.0, out=dst)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        e1.record()
+        torch.cuda.synchronize()
+        result["roofline"]["plain_copy_kernel_gbps_same_box"] = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
     # context only: the paper's end-to-end training results, on its own hardware (not this metric)
     result["paper_context"] = ("training time vs BSP: up to 14x (abstract); VGG11 6.16x at delta 0.3, 13.75x at 0.5 "
                                "(Table I) on 16 V100 workers + 1 parameter server over 5 Gbps; its gradient-change "
