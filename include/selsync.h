@@ -103,7 +103,11 @@ typedef struct selsync_sgd {
     float   weight_decay;
     float   grad_scale;    /* multiplies every gradient element before use (also in the norm); 1 = none */
     int32_t first_step;    /* 1: momentum buffers are uninitialised (m = d); 0: they are valid;
-                              -1: decide automatically (first local update since create/reset)        */
+                              -1: decide automatically (first local update since create/reset).  The
+                              automatic choice is made on the host when the call ENQUEUES its work,
+                              from a per-context count of enqueued updates: a launch recorded into a
+                              HIP graph keeps the value it was recorded with on every replay, so
+                              pass 0 or 1 explicitly in code that is captured                          */
     int32_t nesterov;      /* 0 or 1; 1 needs momentum > 0                                             */
 } selsync_sgd;
 
@@ -132,27 +136,18 @@ typedef struct selsync_stats {
     int64_t nonfinite_steps;   /* steps on which some worker's ||g||^2 was not finite */
 } selsync_stats;
 
-/* Launch-shape knobs (all kernels are bandwidth bound; these exist for measurement).
- * A value <= 0 keeps the built-in default. */
+/* Table-geometry knobs (all kernels are bandwidth bound; these exist for measurement and to let
+ * tests reach the multi-tile loops with small inputs).  A value <= 0 keeps the built-in default,
+ * except nontemporal, whose default is a negative value. */
 typedef struct selsync_tuning {
-    int32_t chunk_elems;       /* elements per chunk of the update/norm chunk table (multiple of 256)   */
-    int32_t blocks_per_cu;     /* > 0: persistent grid of this many workgroups per compute unit;
-                                  <= 0 (default): one workgroup per chunk                               */
+    int32_t chunk_elems;       /* elements per piece of the update/norm chunk table (multiple of 256;
+                                  default 256: one 128-bit access per lane and stream)                  */
     int32_t nontemporal;       /* 1: streaming (non-temporal) loads/stores; 0: plain; <0 default:
                                   streaming when the replicas' working set is 128 MiB or more           */
-    int32_t agg_chunk_elems;   /* elements per chunk of the aggregation table (multiple of 256)         */
-    int32_t stream_variant;    /* shape of the update/norm kernel, 10*C + U: each 64-lane wavefront takes C
-                                  chunks at once with U 128-bit accesses per lane, stream and pass.
-                                  One of 11 12 14 21 22 41 42 81; 0 = default (11 for updates, 41 for
-                                  the norm-only pass)                                                    */
-    int32_t xcd_swizzle;       /* aggregation kernels: 1 = each XCD walks a contiguous eighth of the chunk
-                                  table; 0: off; <0 default                                              */
-    int32_t ga_chunk_elems;    /* elements per chunk of the gradient-aggregation update (multiple of 256) */
-    int32_t table_layout;      /* chunk table and partial sums of the update/norm kernel:
-                                  0 (default) striped by XCD, chunks dispatched in model order;
-                                  1 linear; 2 striped, each XCD walks a contiguous eighth of the model   */
-    int32_t agg_shape;         /* aggregation kernel: 10 * workgroup size + 128-bit accesses per lane, stream
-                                  and pass; one of 641 642 2561 2562 2564 5121 5122 10241; 0 = default   */
+    int32_t agg_chunk_elems;   /* elements per piece of the aggregation table used by launches that follow
+                                  the device-side decision (multiple of 256; default 4096).  Pieces under
+                                  1024 elements run on one-wavefront workgroups, larger ones on 256 threads */
+    int32_t ga_chunk_elems;    /* likewise for the gradient-aggregation update (default 4096)             */
 } selsync_tuning;
 
 typedef struct selsync_ctx  selsync_ctx;    /* opaque: tracker state, counters, workspace owner */
@@ -271,9 +266,12 @@ int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_s
  *   mode 0: only if the device-side decision of the last tracking call is "sync"
  *           (the kernel is launched and exits at once otherwise);
  *   mode 1: always.
- * The results do not depend on the mode; the launch shape does: a predicated launch is
- * built to exit cheaply, one that is certain to work (mode 1, or a threshold of 0, under
- * which every step synchronises) is built for bandwidth.
+ * Under mode 0 the kernel reads the decision word on the device every time it runs, also when
+ * replayed from a HIP graph after selsync_set_delta: nothing the host knows about the threshold
+ * is ever baked into whether the launch aggregates.  Only the launch SHAPE follows the host's
+ * expectation: a launch that will usually exit (mode 0 under a positive threshold) is built to
+ * exit cheaply; one expected to work (mode 1, or the last decision was enqueued under a threshold
+ * of 0, where every step synchronises) is built for bandwidth.
  */
 int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan, int32_t mode, void *stream);
 
@@ -365,10 +363,11 @@ int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *plan, void *st
 int32_t selsync_get_stats(selsync_ctx *ctx, void *stream, selsync_stats *out);
 
 /*
- * Checkpoint / resume of the tracker: windows, previous smoothed values, counters, delta and
- * the automatic first-step marker as one opaque blob in HOST memory (tensors are the caller's
- * to save).  A blob can only be restored into a context with the same num_workers, window and
- * alpha.  Both calls block on `stream`.
+ * Checkpoint / resume of the tracker: windows, previous smoothed values, counters, the last
+ * decision, delta (the device's and the host's copy) and the automatic first-step marker as one
+ * opaque blob in HOST memory (tensors are the caller's to save).  A blob can only be restored
+ * into a context with the same num_workers, window and alpha; restoring replaces that context's
+ * delta by the blob's.  Both calls block on `stream`.
  */
 int32_t selsync_tracker_state_size(const selsync_ctx *ctx, int64_t *bytes);
 int32_t selsync_tracker_get_state(selsync_ctx *ctx, void *stream, void *buf, int64_t bytes);

@@ -353,9 +353,13 @@ class OracleSelSync:
 
     def track(self, grads: Sequence[Sequence[np.ndarray]], grad_scale: float = 1.0) -> StepRecord:
         """a1 + a2 for every worker, then the any-worker rule (Sec. III-B)."""
+        return self.track_norms([norm_sq(grads[k], grad_scale) for k in range(self.num_workers)])
+
+    def track_norms(self, norms: Sequence[float]) -> StepRecord:
+        """a2 for every worker from this iteration's ||g_k||^2, then the any-worker rule (Sec. III-B)."""
         xs, ds, fs = [], [], []
         for k in range(self.num_workers):
-            x = norm_sq(grads[k], grad_scale)
+            x = float(norms[k])
             d = self.trackers[k].push(x)
             xs.append(x)
             ds.append(d)

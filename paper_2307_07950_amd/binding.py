@@ -73,9 +73,8 @@ class selsync_stats(ctypes.Structure):
 
 
 class selsync_tuning(ctypes.Structure):
-    _fields_ = [("chunk_elems", ctypes.c_int32), ("blocks_per_cu", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
-                ("agg_chunk_elems", ctypes.c_int32), ("stream_variant", ctypes.c_int32),
-                ("xcd_swizzle", ctypes.c_int32), ("ga_chunk_elems", ctypes.c_int32), ("table_layout", ctypes.c_int32), ("agg_shape", ctypes.c_int32)]
+    _fields_ = [("chunk_elems", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
+                ("agg_chunk_elems", ctypes.c_int32), ("ga_chunk_elems", ctypes.c_int32)]
 
 
 _vp = ctypes.c_void_p
@@ -271,11 +270,9 @@ class SelSync:
         return Decision(list(n), list(d), list(f), s.value, rc == SELSYNC_WARN_NONFINITE)
 
     # -- lifecycle
-    def set_tuning(self, chunk_elems: int = 0, blocks_per_cu: int = 0, nontemporal: int = -1,
-                   agg_chunk_elems: int = 0, stream_variant: int = 0, xcd_swizzle: int = -1,
-                   ga_chunk_elems: int = 0, table_layout: int = 0, agg_shape: int = 0):
-        t = selsync_tuning(chunk_elems, blocks_per_cu, nontemporal, agg_chunk_elems, stream_variant, xcd_swizzle,
-                           ga_chunk_elems, table_layout, agg_shape)
+    def set_tuning(self, chunk_elems: int = 0, nontemporal: int = -1, agg_chunk_elems: int = 0,
+                   ga_chunk_elems: int = 0):
+        t = selsync_tuning(chunk_elems, nontemporal, agg_chunk_elems, ga_chunk_elems)
         self._check(selsync_set_tuning(self._h, ctypes.byref(t)))
 
     def reset(self, stream=None):

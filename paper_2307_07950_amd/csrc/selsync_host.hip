@@ -21,7 +21,6 @@ using namespace selsync;
 namespace {
 
 constexpr int kDefaultChunkElems = kChunkGranule;   // one 128-bit access per lane and stream: a one-shot grid
-constexpr int kDefaultXcdSwizzle = 0;
 constexpr int kDefaultGaChunkElems = 4096;   // few waves: on "local" decisions this launch only reads the decision
 constexpr int kMaxWorkers = 1024;
 constexpr int kSegChunks = 2048;          // chunks per segment of the intermediate reduction
@@ -43,8 +42,7 @@ struct Interval {
 struct selsync_ctx {
     selsync_config cfg;
     int device = 0;
-    int num_cus = 256;
-    selsync_tuning tuning{0, 0, -1, 0, 0, -1, 0, 0, 0};
+    selsync_tuning tuning{0, -1, 0, 0};
     // device state: one allocation, sub-pointers in td
     void *d_state = nullptr;
     size_t state_bytes = 0;        // size of the d_state allocation
@@ -53,6 +51,8 @@ struct selsync_ctx {
     void *h_out = nullptr;         // pinned mirror of the decision block
     int64_t local_steps = 0;       // local updates enqueued since create/reset (automatic first-step)
     bool tracked = false;          // a tracking pass has been enqueued since create/reset (a decision exists)
+    double tracked_delta = -1.0;   // threshold in force (host view) when the last tracking pass was enqueued;
+                                   // only ever used to pick a launch SHAPE, never to decide whether to aggregate
     int live_plans = 0;
     std::string err;
     // profiling
@@ -90,16 +90,14 @@ struct selsync_plan {
     std::vector<int64_t> numel;      // per-tensor element counts
     std::vector<Interval> ivals;     // every bound buffer (checked again when more buffers are bound)
     bool has_second_moment = false;
-    AggChunkRec *d_agg_chunks = nullptr;
-    AggChunkRec *d_agg_fine = nullptr;    // 256-element pieces: used when the host knows the launch will work
+    AggChunkRec *d_agg_chunks = nullptr;  // pieces for launches that follow the device-side decision
+    AggChunkRec *d_agg_fine = nullptr;    // 256-element pieces: for launches that are expected to work
     int n_agg_fine = 0;
     AggChunkRec *d_ga_chunks = nullptr;   // table of the K-way gradient-aggregation kernel (predicated launches)
     AggTables agg{};
-    int ga_block = 256;
-    bool agg_tuned = false;        // the caller chose the aggregation shape: no automatic choice
-    bool ga_tuned = false;         // likewise for the gradient-aggregation kernel
-    LaunchCfg upd_cfg{1, 1, 0};
-    LaunchCfg agg_cfg{1, 1, 0};
+    AggShape agg_shape = kAggCoarse;      // workgroup shape that goes with d_agg_chunks
+    AggShape ga_shape = kAggCoarse;       // workgroup shape that goes with d_ga_chunks
+    bool nontemporal = true;              // streaming (non-temporal) loads and stores
 
     selsync_plan() = default;
     selsync_plan(const selsync_plan &) = delete;
@@ -375,16 +373,21 @@ int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
 {
     plan->partials_valid = true;
     ctx->tracked = true;
+    ctx->tracked_delta = ctx->cfg.delta;
     ProfScope p(ctx, 1, s);
     if (plan->n_segs > 0) {
-        HIP_TRY(ctx, launch_reduce(plan->tab.partials, plan->tab.slot_per, plan->d_segs, plan->n_segs,
-                                   plan->d_seg_sums, s));
+        HIP_TRY(ctx, launch_reduce(plan->tab.partials, plan->tab.per, plan->d_segs, plan->n_segs, plan->d_seg_sums, s));
         HIP_TRY(ctx, launch_track(ctx->td, plan->d_seg_sums, 0, plan->d_seg_begin, s));
     } else {
-        HIP_TRY(ctx, launch_track(ctx->td, plan->tab.partials, plan->tab.slot_per, plan->d_chunk_begin, s));
+        HIP_TRY(ctx, launch_track(ctx->td, plan->tab.partials, plan->tab.per, plan->d_chunk_begin, s));
     }
     return SELSYNC_OK;
 }
+
+// True when the last decision enqueued on this context was taken under a threshold of 0, under which
+// every tracked step decides "sync" (Delta >= 0 always holds, +inf included).  A hint for the launch
+// shape only: launches still follow the device-side decision word.
+bool expect_sync(const selsync_ctx *ctx) { return ctx->tracked && ctx->tracked_delta == 0.0; }
 
 int32_t check_plan(selsync_ctx *ctx, selsync_plan *plan, bool need_grads, bool need_momenta = false)
 {
@@ -462,10 +465,6 @@ extern "C" int32_t selsync_create(const selsync_config *cfg, selsync_ctx **out)
 
     if (hipGetDevice(&ctx->device) != hipSuccess)
         return bail(SELSYNC_ERR_HIP);
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess)
-        return bail(SELSYNC_ERR_HIP);
-    ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
     // layout of the single state allocation
     size_t off = 0;
@@ -551,6 +550,7 @@ extern "C" int32_t selsync_reset(selsync_ctx *ctx, void *stream)
     HIP_TRY(ctx, launch_reset(ctx->td, static_cast<hipStream_t>(stream)));
     ctx->local_steps = 0;
     ctx->tracked = false;
+    ctx->tracked_delta = -1.0;
     return SELSYNC_OK;
 }
 
@@ -572,27 +572,11 @@ extern "C" int32_t selsync_set_tuning(selsync_ctx *ctx, const selsync_tuning *t)
 {
     if (!ctx || !t)
         return SELSYNC_ERR_INVALID_ARG;
-    if (t->chunk_elems > 0 && (t->chunk_elems % kChunkGranule != 0 || t->chunk_elems > (1 << 24)))
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
-    {
-        static const int shapes[] = {0, 11, 12, 14, 21, 22, 41, 42, 81};
-        if (std::find(std::begin(shapes), std::end(shapes), t->stream_variant) == std::end(shapes))
-            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "stream_variant must be 0 or one of 11 12 14 21 22 41 42 81");
-    }
-    if (t->agg_chunk_elems > 0 && (t->agg_chunk_elems % kChunkGranule != 0 || t->agg_chunk_elems > (1 << 24)))
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_chunk_elems must be a multiple of %d and <= 2^24",
-                    kChunkGranule);
-    if (t->ga_chunk_elems > 0 && (t->ga_chunk_elems % kChunkGranule != 0 || t->ga_chunk_elems > (1 << 24)))
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "ga_chunk_elems must be a multiple of %d and <= 2^24", kChunkGranule);
-    {
-        static const int shapes[] = {0, 641, 642, 2561, 2562, 2564, 5121, 5122, 10241};
-        if (std::find(std::begin(shapes), std::end(shapes), t->agg_shape) == std::end(shapes))
-            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "agg_shape must be 0 or one of 641 642 2561 2562 2564 5121 5122 10241");
-    }
-    if (t->table_layout < 0 || t->table_layout > 2)
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "table_layout must be 0, 1 or 2");
-    if (t->blocks_per_cu > 64)
-        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "blocks_per_cu must be <= 64");
+    const struct { const char *name; int32_t v; } sizes[] = {
+        {"chunk_elems", t->chunk_elems}, {"agg_chunk_elems", t->agg_chunk_elems}, {"ga_chunk_elems", t->ga_chunk_elems}};
+    for (const auto &z : sizes)
+        if (z.v > 0 && (z.v % kChunkGranule != 0 || z.v > (1 << 24)))
+            return fail(ctx, SELSYNC_ERR_INVALID_ARG, "%s must be a multiple of %d and <= 2^24", z.name, kChunkGranule);
     ctx->tuning = *t;
     return SELSYNC_OK;
 }
@@ -674,8 +658,6 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     const int chunk = effective_chunk(ctx);
     const int agg_chunk = ctx->tuning.agg_chunk_elems > 0 ? ctx->tuning.agg_chunk_elems : default_agg_chunk(K);
     const int ga_chunk = ctx->tuning.ga_chunk_elems > 0 ? ctx->tuning.ga_chunk_elems : kDefaultGaChunkElems;
-    // blocks_per_cu <= 0: one workgroup per chunk (one-shot grid); > 0: a persistent grid of that many per CU
-    const int grid_cap = ctx->tuning.blocks_per_cu > 0 ? ctx->num_cus * ctx->tuning.blocks_per_cu : INT_MAX;
     // Streaming (non-temporal) accesses pay off once the working set is far beyond the last-level
     // cache (measured: +11 % at 435 MB); below roughly half its 256 MB plain accesses are 3-6 % faster.
     const int64_t working_set = (int64_t)K * P * 12;   // g, w, m: 12 bytes per parameter in either precision
@@ -725,18 +707,14 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     if (chunks.size() > (size_t)INT32_MAX - 8 * kStripeGranule)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan (%zu chunks)", chunks.size());
 
-    // Slot order of the table (and of the partial sums).  Striped layouts hold 8 stripes of `per`
-    // slots, padded with empty slots; workgroup b of the streaming kernel works on stripe b % 8.
-    const int layout = ctx->tuning.table_layout;
+    // Slot order of the table (and of the partial sums): 8 stripes of `per` slots, padded with empty
+    // slots; workgroup b of the streaming kernel works on stripe b % 8.
     const int nchunks = (int)chunks.size();
-    int per = 0;
-    if (layout != kLayoutLinear && nchunks > 0)
-        per = (int)align_up((size_t)(nchunks + 7) / 8, kStripeGranule);
-    const int nslots = per > 0 ? 8 * per : nchunks;
-    const int slot_per = layout == kLayoutStriped ? per : 0;
+    const int per = nchunks > 0 ? (int)align_up((size_t)(nchunks + 7) / 8, kStripeGranule) : 0;
+    const int nslots = 8 * per;
     std::vector<ChunkRec> slots((size_t)nslots, ChunkRec{kNoChunk, 0u});
     for (int c = 0; c < nchunks; ++c)
-        slots[(size_t)chunk_slot(c, slot_per)] = chunks[c];
+        slots[(size_t)chunk_slot(c, per)] = chunks[c];
 
     // With many chunks the per-chunk partials first collapse into fixed segments of
     // kSegChunks consecutive chunks (never crossing a worker boundary); the tracker kernel
@@ -844,7 +822,10 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->n_agg_chunks = (int)agg_chunks.size();
     plan->n_agg_fine = (int)agg_fine.size();
     plan->n_ga_chunks = (int)ga_chunks.size();
-    plan->ga_block = ga_chunk < 1024 ? 64 : 256;     // one-wave workgroups for the fine tables
+    // one-wave workgroups go with pieces of less than one coarse tile
+    plan->agg_shape = agg_chunk < kAggTileElems ? kAggFine : kAggCoarse;
+    plan->ga_shape = ga_chunk < kAggTileElems ? kAggFine : kAggCoarse;
+    plan->nontemporal = nt != 0;
 
     // ---- one device allocation for every table
     size_t off = 0;
@@ -908,7 +889,6 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->tab.nchunks = nchunks;
     plan->tab.nslots = nslots;
     plan->tab.per = per;
-    plan->tab.slot_per = slot_per;
     plan->tab.chunk_elems = (uint32_t)chunk;
     plan->tab.has_momentum = momenta != nullptr;
     plan->d_chunk_begin = reinterpret_cast<int32_t *>(b + o_begin);
@@ -927,15 +907,6 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->agg.glowp = reinterpret_cast<uint16_t *const *>(b + o_agc);
     plan->agg.g = reinterpret_cast<const void *const *>(b + o_agrad);
     plan->agg.m = reinterpret_cast<float *const *>(b + o_am);
-
-    plan->upd_cfg.grid = std::max(1, grid_cap);
-    plan->upd_cfg.nontemporal = nt;
-    plan->upd_cfg.variant = ctx->tuning.stream_variant;
-    plan->upd_cfg.xcd_swizzle = ctx->tuning.xcd_swizzle >= 0 ? ctx->tuning.xcd_swizzle : kDefaultXcdSwizzle;
-    plan->agg_cfg = plan->upd_cfg;
-    plan->agg_cfg.agg_shape = ctx->tuning.agg_shape;
-    plan->agg_tuned = ctx->tuning.agg_shape != 0 || ctx->tuning.agg_chunk_elems > 0;
-    plan->ga_tuned = ctx->tuning.ga_chunk_elems > 0;
 
     ctx->live_plans += 1;
     *out = plan.release();
@@ -1017,7 +988,7 @@ extern "C" int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *pla
     SgdArgs a{0.f, 0.f, 0.f, grad_scale, 0};
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, a, plan->nontemporal, s));
     }
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
@@ -1028,23 +999,22 @@ extern "C" int32_t selsync_track_grad_change(selsync_ctx *ctx, selsync_plan *pla
 
 namespace {
 // a4.  mode 0 follows the device-side decision: the launch is shaped for a cheap exit (few, large
-// workgroups), because on most steps it only reads the decision.  When the host already knows that
-// the launch will work -- mode 1, or a threshold of 0, under which every step synchronises -- it
-// takes single-wavefront workgroups of 256 elements instead (75 % against 69 % of HBM peak).
+// workgroups), because on most steps it only reads the decision.  When the launch is expected to
+// work -- mode 1, or a last decision taken under a threshold of 0, where every step synchronises --
+// it takes single-wavefront workgroups of 256 elements instead (75 % against 69 % of HBM peak).
 int32_t enqueue_aggregate(selsync_ctx *ctx, selsync_plan *plan, int mode, hipStream_t s)
 {
     ProfScope p(ctx, 2, s);
-    // with a threshold of 0 every tracked step decides "sync" (Delta >= 0 always holds, +inf included)
-    const bool certain = mode == 1 || (ctx->cfg.delta == 0.0 && ctx->tracked);
-    if (certain && !plan->agg_tuned) {
-        LaunchCfg cfg = plan->agg_cfg;
-        cfg.agg_shape = 641;
-        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, plan->agg, plan->K,
-                                      &ctx->td.out->sync, 1, cfg, s));
+    // The kernel always gets the caller's mode: under mode 0 it follows the device-side decision word
+    // whatever the host expects, so a launch recorded into a graph stays correct when the threshold
+    // changes between replays.  The expectation only selects the table and workgroup shape.
+    if (mode == 1 || expect_sync(ctx)) {
+        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
+                                      &ctx->td.out->sync, mode, plan->nontemporal, s));
         return SELSYNC_OK;
     }
-    HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg, plan->K,
-                                  &ctx->td.out->sync, mode, plan->agg_cfg, s));
+    HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg_shape, plan->agg,
+                                  plan->K, &ctx->td.out->sync, mode, plan->nontemporal, s));
     return SELSYNC_OK;
 }
 }  // namespace
@@ -1060,7 +1030,7 @@ extern "C" int32_t selsync_local_step(selsync_ctx *ctx, selsync_plan *plan, cons
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->nontemporal, s));
     }
     ctx->local_steps += 1;
     return SELSYNC_OK;
@@ -1092,7 +1062,7 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->tab, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->tab, a, plan->nontemporal, s));
     }
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))
@@ -1243,7 +1213,7 @@ extern "C" int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan,
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->tab, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->tab, a, plan->nontemporal, s));
     }
     ctx->local_steps += 1;
     return SELSYNC_OK;
@@ -1262,7 +1232,7 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream_adam(true, plan->mixed, plan->tab, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream_adam(true, plan->mixed, plan->tab, a, plan->nontemporal, s));
     }
     ctx->local_steps += 1;
     if ((rc = enqueue_track(ctx, plan, s)))
@@ -1283,25 +1253,27 @@ namespace {
 // applies the mean gradient).  Mode 1 always aggregates.
 int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a, int mode, hipStream_t s)
 {
-    if (mode == 1 || (ctx->cfg.delta == 0.0 && ctx->tracked)) {
-        // certain to aggregate (a threshold of 0 synchronises every step): one launch, shaped for bandwidth
+    if (mode == 1) {
+        // always aggregate: one launch, shaped for bandwidth
         ProfScope p(ctx, 2, s);
-        if (!plan->ga_tuned) {
-            HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, 64, plan->agg, plan->K,
-                                          &ctx->td.out->sync, 1, a, plan->agg_cfg, s));
-            return SELSYNC_OK;
-        }
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg,
-                                      plan->K, &ctx->td.out->sync, 1, a, plan->agg_cfg, s));
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
+                                      &ctx->td.out->sync, 1, a, plan->nontemporal, s));
         return SELSYNC_OK;
     }
+    // Both launches follow the device-side decision word, so exactly one of them works whatever the
+    // host expects; the expectation (a last decision under a threshold of 0 synchronises) only gives
+    // the K-way launch its bandwidth shape.
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s, &ctx->td.out->sync, 0));
+        HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->nontemporal, s, &ctx->td.out->sync, 0));
     }
     ProfScope p(ctx, 2, s);
-    HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_block, plan->agg, plan->K,
-                                  &ctx->td.out->sync, mode, a, plan->agg_cfg, s));
+    if (expect_sync(ctx))
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
+                                      &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+    else
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape, plan->agg,
+                                      plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
     return SELSYNC_OK;
 }
 }  // namespace
@@ -1337,7 +1309,7 @@ extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const s
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, a, plan->upd_cfg, s));
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, a, plan->nontemporal, s));
     }
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
@@ -1376,7 +1348,8 @@ extern "C" int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *pla
     if (n == 0)
         return SELSYNC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(ctx, launch_tensor_norms(plan->tab.partials, plan->tab.slot_per, plan->d_tensor_chunk_begin, n, plan->d_tensor_norms, s));
+    HIP_TRY(ctx, launch_tensor_norms(plan->tab.partials, plan->tab.per, plan->d_tensor_chunk_begin, n,
+                                     plan->d_tensor_norms, s));
     HIP_TRY(ctx, hipMemcpyAsync(out, plan->d_tensor_norms, sizeof(double) * n, hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
     return SELSYNC_OK;
@@ -1411,8 +1384,12 @@ struct StateHeader {
     double alpha;
     int64_t local_steps;
     uint64_t payload_bytes;
+    double delta;           // threshold in force (the device copy travels inside the payload)
+    double tracked_delta;   // threshold under which the last decision was taken (-1: none)
+    int32_t tracked;        // a decision exists
+    int32_t reserved;
 };
-constexpr uint64_t kStateMagic = 0x53454c53594e4331ull;   // "SELSYNC1"
+constexpr uint64_t kStateMagic = 0x53454c53594e4332ull;   // "SELSYNC2"
 }  // namespace
 
 extern "C" int32_t selsync_tracker_state_size(const selsync_ctx *ctx, int64_t *bytes)
@@ -1434,7 +1411,7 @@ extern "C" int32_t selsync_tracker_get_state(selsync_ctx *ctx, void *stream, voi
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     StateHeader h{kStateMagic, ctx->cfg.num_workers, ctx->cfg.window, ctx->cfg.alpha, ctx->local_steps,
-                  (uint64_t)ctx->state_bytes};
+                  (uint64_t)ctx->state_bytes, ctx->cfg.delta, ctx->tracked_delta, ctx->tracked ? 1 : 0, 0};
     std::memcpy(buf, &h, sizeof h);
     HIP_TRY(ctx, hipMemcpyAsync(static_cast<char *>(buf) + sizeof h, ctx->d_state, ctx->state_bytes,
                                 hipMemcpyDeviceToHost, s));
@@ -1452,7 +1429,7 @@ extern "C" int32_t selsync_tracker_set_state(selsync_ctx *ctx, void *stream, con
     std::memcpy(&h, buf, sizeof h);
     if (h.magic != kStateMagic || h.num_workers != ctx->cfg.num_workers || h.window != ctx->cfg.window ||
         h.alpha != ctx->cfg.alpha || h.payload_bytes != ctx->state_bytes ||
-        bytes < (int64_t)(sizeof h + h.payload_bytes))
+        bytes < (int64_t)(sizeof h + h.payload_bytes) || !(h.delta >= 0.0))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "state blob does not match this context (workers/window/alpha)");
     int32_t rc = check_device(ctx);
     if (rc)
@@ -1461,7 +1438,12 @@ extern "C" int32_t selsync_tracker_set_state(selsync_ctx *ctx, void *stream, con
     HIP_TRY(ctx, hipMemcpyAsync(ctx->d_state, static_cast<const char *>(buf) + sizeof h, ctx->state_bytes,
                                 hipMemcpyHostToDevice, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
+    // the host's view follows the restored device state: threshold, whether a decision exists, and
+    // the automatic first-step marker
     ctx->local_steps = h.local_steps;
+    ctx->cfg.delta = h.delta;
+    ctx->tracked = h.tracked != 0;
+    ctx->tracked_delta = h.tracked_delta;
     return SELSYNC_OK;
 }
 

@@ -34,18 +34,15 @@ struct ChunkRec {
 constexpr uint32_t kNoChunk = 0xffffffffu;
 
 // Where chunk c's table record and partial sum live.  Workgroups of a launch go to the 8
-// XCDs (each with its own L2) round-robin by workgroup id.  In the striped layout the slots
-// are stored as 8 stripes of `per` slots and workgroup b works on stripe b % 8, so the
-// records and partial sums of one XCD's workgroups are contiguous in memory: every table
-// line is fetched by one L2 instead of eight, every line of partial sums is written by one.
-//   layout 0 (striped, chunk order = dispatch order): chunk c sits in slot (c%8)*per + c/8
-//   layout 1 (linear):                                slot c, workgroup b takes slots b*C..
-//   layout 2 (striped slots, chunks stored linearly): slot c; XCD x walks chunks [x*per, (x+1)*per)
-enum TableLayout { kLayoutStriped = 0, kLayoutLinear = 1, kLayoutXcdContiguous = 2 };
-
-__host__ __device__ inline int64_t chunk_slot(int64_t c, int per_if_striped)
+// XCDs (each with its own L2) round-robin by workgroup id.  The slots are stored as 8 stripes
+// of `per` slots and workgroup b works on stripe b % 8, so the records and partial sums of
+// one XCD's workgroups are contiguous in memory: every table line is fetched by one L2
+// instead of eight, every line of partial sums is written by one, while chunks are still
+// dispatched in model order: chunk c sits in slot (c%8)*per + c/8.  (per = 0: plain index,
+// used for arrays that are not striped, such as the per-segment sums.)
+__host__ __device__ inline int64_t chunk_slot(int64_t c, int per)
 {
-    return per_if_striped > 0 ? (c & 7) * (int64_t)per_if_striped + (c >> 3) : c;
+    return per > 0 ? (c & 7) * (int64_t)per + (c >> 3) : c;
 }
 
 // One unit of work of the aggregation kernel: `n` consecutive elements of tensor t
@@ -115,24 +112,21 @@ struct SgdArgs {
     int32_t nesterov;
 };
 
-// Launch shape for the streaming kernels.
-struct LaunchCfg {
-    int grid;
-    int nontemporal;
-    int variant = 0;       // streaming kernel: 10*C + U (C chunks per wave, U vectors per lane and tile); 0 = default
-    int xcd_swizzle = 0;   // aggregation kernels: 1 = XCD-aware workgroup -> chunk mapping
-    int agg_shape = 0;     // aggregation kernel: 10 * workgroup size + accesses per lane; 0 = default
-};
+// Workgroup shape of the K-way kernels.
+//   kAggCoarse: 256 threads, 4 vectors of 4 elements per lane and replica (made for 4096-element pieces):
+//               few workgroups, so a launch that only reads the decision and exits is cheap;
+//   kAggFine:   one wavefront, one vector per lane and replica (made for 256-element pieces): the
+//               shape with the highest bandwidth when the launch does work.
+enum AggShape { kAggCoarse = 0, kAggFine = 1 };
 
-// Geometry of a plan's chunk table (see TableLayout).
+// Geometry of a plan's chunk table (see chunk_slot).
 struct StreamTable {
     const TensorRec *recs = nullptr;
     const ChunkRec *slots = nullptr;
     double *partials = nullptr;    // one per slot
     int nchunks = 0;               // real chunks
-    int nslots = 0;                // table entries including padding
-    int per = 0;                   // slots per stripe; 0 in the linear layout
-    int slot_per = 0;              // `per` for chunk_slot(): > 0 only when chunks are stored striped (layout 0)
+    int nslots = 0;                // table entries including padding: 8 * per
+    int per = 0;                   // slots per stripe
     uint32_t chunk_elems = 0;
     bool has_momentum = true;      // false: momentum-free plan (no m buffers bound)
 };
@@ -166,18 +160,18 @@ __host__ __device__ inline int64_t partition_index(int64_t D, int64_t N, int64_t
 // Chunk sizes are a multiple of this: one wavefront x one group of 4 elements per lane
 // (128 bits per fp32 stream, 64 bits per bf16 stream).
 constexpr int kChunkGranule = 256;
-// Stripes are padded to a multiple of this many slots (the largest chunks-per-wave count).
+// Stripes are padded to a multiple of this many slots (a multiple of every chunks-per-wave count).
 constexpr int kStripeGranule = 16;
 // Smallest aggregation tile: 256 threads x one 128-bit vector.
 constexpr int kAggTileElems = 1024;
 
 // With `pred` the launch only works while *pred == pred_want (device-side word), else it exits.
-hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
+hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, bool nontemporal,
                          hipStream_t s, const int32_t *pred = nullptr, int pred_want = 0);
 
 // Adam variant of the streaming kernel: update (+ norm partials when with_norm).
-hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a,
-                              const LaunchCfg &cfg, hipStream_t s);
+hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a, bool nontemporal,
+                              hipStream_t s);
 
 // Sums the partials of chunks segs[j].x .. segs[j].y - 1 into seg_sums[j], one workgroup per
 // segment.  slot_per: see chunk_slot().
@@ -188,8 +182,8 @@ hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs,
 // chunk_slot(., slot_per)) or per-segment ones (slot_per = 0).
 hipError_t launch_track(const TrackerDev &td, const double *values, int slot_per, const int32_t *begin, hipStream_t s);
 
-hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
-                            const int32_t *sync_flag, int mode, const LaunchCfg &cfg, hipStream_t s);
+hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
+                            int K, const int32_t *sync_flag, int mode, bool nontemporal, hipStream_t s);
 
 // out[i] = sum of the partials of chunks range_begin[i] .. range_begin[i+1] - 1, one workgroup per range.
 hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32_t *range_begin, int nranges,
@@ -198,8 +192,8 @@ hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32
 // Synchronising update of gradient aggregation (Sec. III-C): when the decision is "sync" (or
 // mode 1) every worker applies the mean gradient to its own parameters and momentum; on a
 // "local" decision the launch does nothing (the caller runs the plain local update instead).
-hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
-                            const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
+hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
+                            int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal,
                             hipStream_t s);
 
 // out[p] = partition_index(D, N, n, scheme, p) for p < count (device array).

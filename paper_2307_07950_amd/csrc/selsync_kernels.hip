@@ -81,16 +81,6 @@ __device__ __forceinline__ f32x4 widen4(u32x2 v)
     return g;
 }
 
-// Workgroup -> chunk mapping.  Workgroups are handed to the 8 XCDs round-robin by
-// linear id, and each XCD has its own L2.  With xcd_per > 0 workgroup v takes chunk
-// (v % 8) * xcd_per + v / 8, so every XCD walks one contiguous eighth of the chunk
-// table (and of the tensors): table lines and address translations are fetched by one
-// L2 instead of eight.  xcd_per == 0 is the identity mapping.
-__device__ __forceinline__ int chunk_of_workgroup(int v, int xcd_per)
-{
-    return xcd_per > 0 ? (v & 7) * xcd_per + (v >> 3) : v;
-}
-
 // Elements to process one by one before the 16-byte aligned body of a chunk starts (0..3).
 __device__ __forceinline__ uint32_t chunk_head(uint32_t n_flags, uint32_t n)
 {
@@ -298,16 +288,15 @@ __device__ __forceinline__ Chunk lookup_chunk(const TensorRec *__restrict__ recs
     return ck;
 }
 
-// 128-bit registers of one tile: U groups of 4 elements per lane and stream.
-template <int U>
+// 128-bit registers of one tile: one group of 4 elements per lane and stream.
 struct TileRegs {
-    f32x4 g[U], w[U], m[U], v[U];
+    f32x4 g, w, m, v;
 };
 
-// Issue the loads of tile [base, base + 64*U) of the chunk's vector body.  Every stream is read
+// Issue the loads of tile [base, base + 64) of the chunk's vector body.  Every stream is read
 // with consecutive lanes on consecutive addresses (bf16 gradients: 8 bytes per lane).
-template <class OPT, int U, bool MIXED, bool UPD, bool NT>
-__device__ __forceinline__ void load_tile(const Chunk &ck, uint32_t base, uint32_t tid, int first, TileRegs<U> &t)
+template <class OPT, bool MIXED, bool UPD, bool NT>
+__device__ __forceinline__ void load_tile(const Chunk &ck, uint32_t base, uint32_t tid, int first, TileRegs &t)
 {
     const uint64_t e0 = ck.off + ck.head;
     const SELSYNC_GLOBAL f32x4 *g4 = as_global<const f32x4>(reinterpret_cast<const float *>(ck.r.g) + e0);
@@ -315,57 +304,51 @@ __device__ __forceinline__ void load_tile(const Chunk &ck, uint32_t base, uint32
     const SELSYNC_GLOBAL f32x4 *w4 = as_global<const f32x4>(ck.r.w + e0);
     const SELSYNC_GLOBAL f32x4 *m4 = as_global<const f32x4>(ck.r.m + e0);
     const SELSYNC_GLOBAL f32x4 *v4 = as_global<const f32x4>(ck.r.v + e0);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * 64 + tid;
-        t.g[u] = 0.f;
-        t.w[u] = 0.f;
-        t.m[u] = 0.f;
-        t.v[u] = 0.f;
-        if (i < ck.nvec) {
-            if (MIXED)
-                t.g[u] = widen4(ld<NT>(gb4 + i));
-            else
-                t.g[u] = ld<NT>(g4 + i);
-            if (UPD) {
-                t.w[u] = ld<NT>(w4 + i);
-                if (OPT::kMomentum && !first) {
-                    t.m[u] = ld<NT>(m4 + i);
-                    if (OPT::kSecondMoment)
-                        t.v[u] = ld<NT>(v4 + i);
-                }
+    const uint32_t i = base + tid;
+    t.g = 0.f;
+    t.w = 0.f;
+    t.m = 0.f;
+    t.v = 0.f;
+    if (i < ck.nvec) {
+        if (MIXED)
+            t.g = widen4(ld<NT>(gb4 + i));
+        else
+            t.g = ld<NT>(g4 + i);
+        if (UPD) {
+            t.w = ld<NT>(w4 + i);
+            if (OPT::kMomentum && !first) {
+                t.m = ld<NT>(m4 + i);
+                if (OPT::kSecondMoment)
+                    t.v = ld<NT>(v4 + i);
             }
         }
     }
 }
 
 // Arithmetic and stores of the tile loaded by load_tile.
-template <class OPT, int U, bool MIXED, bool UPD, bool NORM, bool NT>
+template <class OPT, bool MIXED, bool UPD, bool NORM, bool NT>
 __device__ __forceinline__ void finish_tile(const Chunk &ck, uint32_t base, uint32_t tid, const typename OPT::Args &a,
-                                            TileRegs<U> &t, double &acc)
+                                            TileRegs &t, double &acc)
 {
     const uint64_t e0 = ck.off + ck.head;
     SELSYNC_GLOBAL f32x4 *w4 = as_global<f32x4>(ck.r.w + e0);
     SELSYNC_GLOBAL f32x4 *m4 = as_global<f32x4>(ck.r.m + e0);
     SELSYNC_GLOBAL f32x4 *v4 = as_global<f32x4>(ck.r.v + e0);
     SELSYNC_GLOBAL u32x2 *c4 = as_global<u32x2>(ck.r.lowp + e0);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * 64 + tid;
-        if (i < ck.nvec) {
-            elem4<OPT, UPD, NORM>(t.g[u], t.w[u], t.m[u], t.v[u], a, acc);
-            if (UPD) {
-                st<NT>(w4 + i, t.w[u]);
-                if (OPT::kMomentum)
-                    st<NT>(m4 + i, t.m[u]);
-                if (OPT::kSecondMoment)
-                    st<NT>(v4 + i, t.v[u]);
-                if (MIXED) {
-                    u32x2 cv;
-                    cv.x = bf16_pack(t.w[u].x, t.w[u].y);
-                    cv.y = bf16_pack(t.w[u].z, t.w[u].w);
-                    st<NT>(c4 + i, cv);
-                }
+    const uint32_t i = base + tid;
+    if (i < ck.nvec) {
+        elem4<OPT, UPD, NORM>(t.g, t.w, t.m, t.v, a, acc);
+        if (UPD) {
+            st<NT>(w4 + i, t.w);
+            if (OPT::kMomentum)
+                st<NT>(m4 + i, t.m);
+            if (OPT::kSecondMoment)
+                st<NT>(v4 + i, t.v);
+            if (MIXED) {
+                u32x2 cv;
+                cv.x = bf16_pack(t.w.x, t.w.y);
+                cv.y = bf16_pack(t.w.z, t.w.w);
+                st<NT>(c4 + i, cv);
             }
         }
     }
@@ -415,15 +398,15 @@ __device__ __forceinline__ void scalar_range(const Chunk &ck, uint32_t begin, ui
 // Multi-tensor streaming kernel.  Workgroups are single wavefronts (no LDS, no barrier); a
 // wavefront takes C table slots that are adjacent in memory, issues the first-tile loads of
 // all C chunks before it uses any of them, updates and stores, then (only for chunks larger
-// than one tile) walks the remaining tiles.  Per chunk it leaves one fp64 partial sum of
-// squared scaled gradients in that chunk's slot: fixed place, fixed order, no atomics.
-//   per > 0: striped table, workgroup b takes slots (b%8)*per + (b/8)*C + [0, C)
-//   per = 0: linear table, workgroup b takes slots b*C + [0, C)
+// than one tile of 256 elements) walks the remaining tiles.  Per chunk it leaves one fp64
+// partial sum of squared scaled gradients in that chunk's slot: fixed place, fixed order, no
+// atomics.  The grid is one-shot: workgroup b takes slots (b%8)*per + (b/8)*C + [0, C) of the
+// XCD-striped table, so the hardware dispatcher walks the model in order.
 // With `pred` set the launch is predicated on a device-side word: it does its work only
 // while *pred == pred_want (the gradient-aggregation step runs this kernel on "local" decisions).
-template <class OPT, int U, int C, bool MIXED, int MODE, bool NT>
+template <class OPT, int C, bool MIXED, int MODE, bool NT>
 __global__ __launch_bounds__(64) void k_stream(const TensorRec *__restrict__ recs, const ChunkRec *__restrict__ slots,
-                                               int nslots, int nwg, int per, uint32_t chunk_elems,
+                                               int nslots, int per, uint32_t chunk_elems,
                                                double *__restrict__ partials, typename OPT::Args a,
                                                const int32_t *__restrict__ pred, int32_t pred_want)
 {
@@ -432,39 +415,37 @@ __global__ __launch_bounds__(64) void k_stream(const TensorRec *__restrict__ rec
     if (pred != nullptr && *pred != pred_want)
         return;
     const uint32_t tid = threadIdx.x;
-
-    for (int b = blockIdx.x; b < nwg; b += gridDim.x) {
-        const int s0 = per > 0 ? (b & 7) * per + (b >> 3) * C : b * C;
-        Chunk ck[C];
-        TileRegs<U> t[C];
-        double acc[C];
+    const int b = blockIdx.x;
+    const int s0 = (b & 7) * per + (b >> 3) * C;
+    Chunk ck[C];
+    TileRegs t[C];
+    double acc[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        ck[i] = lookup_chunk(recs, slots, s0 + i, nslots, chunk_elems);
+        acc[i] = 0.0;
+    }
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+        load_tile<OPT, MIXED, UPD, NT>(ck[i], 0, tid, a.first, t[i]);
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+        finish_tile<OPT, MIXED, UPD, NORM, NT>(ck[i], 0, tid, a, t[i], acc[i]);
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        for (uint32_t base = 64; base < ck[i].nvec; base += 64) {
+            load_tile<OPT, MIXED, UPD, NT>(ck[i], base, tid, a.first, t[i]);
+            finish_tile<OPT, MIXED, UPD, NORM, NT>(ck[i], base, tid, a, t[i], acc[i]);
+        }
+        scalar_range<OPT, MIXED, UPD, NORM>(ck[i], 0, ck[i].head, tid, a, acc[i]);
+        scalar_range<OPT, MIXED, UPD, NORM>(ck[i], ck[i].head + 4 * ck[i].nvec, ck[i].n, tid, a, acc[i]);
+    }
+    if (NORM) {
 #pragma unroll
         for (int i = 0; i < C; ++i) {
-            ck[i] = lookup_chunk(recs, slots, s0 + i, nslots, chunk_elems);
-            acc[i] = 0.0;
-        }
-#pragma unroll
-        for (int i = 0; i < C; ++i)
-            load_tile<OPT, U, MIXED, UPD, NT>(ck[i], 0, tid, a.first, t[i]);
-#pragma unroll
-        for (int i = 0; i < C; ++i)
-            finish_tile<OPT, U, MIXED, UPD, NORM, NT>(ck[i], 0, tid, a, t[i], acc[i]);
-#pragma unroll
-        for (int i = 0; i < C; ++i) {
-            for (uint32_t base = 64 * U; base < ck[i].nvec; base += 64 * U) {
-                load_tile<OPT, U, MIXED, UPD, NT>(ck[i], base, tid, a.first, t[i]);
-                finish_tile<OPT, U, MIXED, UPD, NORM, NT>(ck[i], base, tid, a, t[i], acc[i]);
-            }
-            scalar_range<OPT, MIXED, UPD, NORM>(ck[i], 0, ck[i].head, tid, a, acc[i]);
-            scalar_range<OPT, MIXED, UPD, NORM>(ck[i], ck[i].head + 4 * ck[i].nvec, ck[i].n, tid, a, acc[i]);
-        }
-        if (NORM) {
-#pragma unroll
-            for (int i = 0; i < C; ++i) {
-                const double s = wave_sum_to_last_lane(acc[i]);
-                if (tid == 63 && ck[i].n > 0)
-                    partials[s0 + i] = s;
-            }
+            const double s = wave_sum_to_last_lane(acc[i]);
+            if (tid == 63 && ck[i].n > 0)
+                partials[s0 + i] = s;
         }
     }
 }
@@ -742,21 +723,18 @@ __device__ __forceinline__ float finish_mean(double s, int K, double invK, int p
     return (float)mean;
 }
 
+// One workgroup per piece of the aggregation table (one-shot grid).  With mode 0 the launch
+// follows the device-side decision: every workgroup reads it and exits at once on "local".
 template <int BLOCK, int U, int KC, bool MIXED, bool NT>
-__global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restrict__ chunks, int nchunks,
-                                                     AggTables tabs, int K, double invK, int pow2,
-                                                     const int32_t *__restrict__ sync_flag, int mode, int xcd_per)
+__global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restrict__ chunks, AggTables tabs, int K,
+                                                     double invK, int pow2, const int32_t *__restrict__ sync_flag,
+                                                     int mode)
 {
     if (mode == 0 && *sync_flag == 0)
         return;
     const uint32_t tid = threadIdx.x;
-
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    for (int v = blockIdx.x; v < vtotal; v += gridDim.x) {
-        const int c = chunk_of_workgroup(v, xcd_per);
-        if (c >= nchunks)
-            continue;
-        const AggChunkRec ch = chunks[c];
+    {
+        const AggChunkRec ch = chunks[blockIdx.x];
         const uint32_t n = ch.n_flags & kChunkCountMask;
         float *const *wtab = tabs.w + (size_t)ch.t * K;
         uint16_t *const *ctab = MIXED ? tabs.lowp + (size_t)ch.t * K : nullptr;
@@ -927,10 +905,9 @@ __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, dou
 // update of such a step is the streaming kernel's job).  K compile-time (KC > 0) keeps all
 // 3K loads of a vector in flight.
 template <int BLOCK, int KC, bool MIXED, bool NT>
-__global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, int nchunks,
-                                                     AggTables tabs, int K, double invK, int pow2,
-                                                     const int32_t *__restrict__ sync_flag, int always, SgdArgs a,
-                                                     int xcd_per)
+__global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, AggTables tabs, int K,
+                                                     double invK, int pow2,
+                                                     const int32_t *__restrict__ sync_flag, int always, SgdArgs a)
 {
     constexpr int KM = KC > 0 ? KC : 1;
     if (!always && *sync_flag == 0)
@@ -939,12 +916,8 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
     a1.gs = 1.f;
     const uint32_t tid = threadIdx.x;
     double unused = 0.0;
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    for (int v = blockIdx.x; v < vtotal; v += gridDim.x) {
-        const int c = chunk_of_workgroup(v, xcd_per);
-        if (c >= nchunks)
-            continue;
-        const AggChunkRec ch = chunks[c];
+    {
+        const AggChunkRec ch = chunks[blockIdx.x];
         const uint32_t n = ch.n_flags & kChunkCountMask;
         const size_t row = (size_t)ch.t * K;
         uint32_t done = 0;   // elements covered by the 128-bit body [head, head + done)
@@ -1030,131 +1003,127 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
 
 // ---------------------------------------------------------------- dispatch helpers
 
-constexpr int kBlock = 256;
+// Chunks per wavefront of the streaming kernel (measured on the 133M-parameter fp32 workload):
+// updates do best with the least work per wavefront, one chunk; the read-only norm pass wants
+// more bytes in flight per wavefront, four chunks.
+constexpr int kUpdateChunksPerWave = 1;
+constexpr int kNormChunksPerWave = 4;
+static_assert(kStripeGranule % kNormChunksPerWave == 0 && kStripeGranule % kUpdateChunksPerWave == 0,
+              "a wavefront's slots must not cross a stripe");
 
-// Launch k_stream with the (U, C) shape named by `variant` = 10*C + U.
-template <class OPT, bool MIXED, int MODE, bool NT>
-hipError_t launch_stream_t(const StreamTable &tab, const typename OPT::Args &args, int grid_cap, int variant,
-                           const int32_t *pred, int pred_want, hipStream_t s)
+template <class OPT, int C, bool MIXED, int MODE, bool NT>
+hipError_t launch_stream_c(const StreamTable &tab, const typename OPT::Args &args, const int32_t *pred, int pred_want,
+                           hipStream_t s)
 {
-#define SELSYNC_SHAPE(UU, CC)                                                                                       \
-    do {                                                                                                            \
-        const int nwg = tab.per > 0 ? 8 * (tab.per / (CC)) : (tab.nslots + (CC)-1) / (CC);                          \
-        const int grid = grid_cap < nwg ? grid_cap : nwg;                                                           \
-        hipLaunchKernelGGL((k_stream<OPT, UU, CC, MIXED, MODE, NT>), dim3(grid), dim3(64), 0, s, tab.recs, tab.slots, \
-                           tab.nslots, nwg, tab.per, tab.chunk_elems, tab.partials, args, pred, pred_want);         \
-        return hipGetLastError();                                                                                   \
-    } while (0)
-    switch (variant) {
-    case 11: SELSYNC_SHAPE(1, 1);
-    case 12: SELSYNC_SHAPE(2, 1);
-    case 14: SELSYNC_SHAPE(4, 1);
-    case 21: SELSYNC_SHAPE(1, 2);
-    case 22: SELSYNC_SHAPE(2, 2);
-    case 41: SELSYNC_SHAPE(1, 4);
-    case 42: SELSYNC_SHAPE(2, 4);
-    case 81: SELSYNC_SHAPE(1, 8);
-    default:
-        break;
-    }
-    // defaults (measured on the 133M-parameter fp32 workload): updates do best with the least
-    // work per wavefront; the read-only norm pass wants more bytes in flight per wavefront
-    if (MODE == kNormOnly)
-        SELSYNC_SHAPE(1, 4);
-    SELSYNC_SHAPE(1, 1);
-#undef SELSYNC_SHAPE
+    const int nwg = 8 * (tab.per / C);
+    hipLaunchKernelGGL((k_stream<OPT, C, MIXED, MODE, NT>), dim3(nwg), dim3(64), 0, s, tab.recs, tab.slots, tab.nslots,
+                       tab.per, tab.chunk_elems, tab.partials, args, pred, pred_want);
+    return hipGetLastError();
 }
 
 template <class OPT, bool MIXED, bool NT>
-hipError_t launch_stream_m(StreamMode mode, const StreamTable &tab, const typename OPT::Args &args, int grid_cap,
-                           int variant, const int32_t *pred, int pred_want, hipStream_t s)
+hipError_t launch_stream_m(StreamMode mode, const StreamTable &tab, const typename OPT::Args &args,
+                           const int32_t *pred, int pred_want, hipStream_t s)
 {
     switch (mode) {
     case kNormOnly:
-        return launch_stream_t<OPT, MIXED, kNormOnly, NT>(tab, args, grid_cap, variant, pred, pred_want, s);
+        return launch_stream_c<OPT, kNormChunksPerWave, MIXED, kNormOnly, NT>(tab, args, pred, pred_want, s);
     case kUpdateOnly:
-        return launch_stream_t<OPT, MIXED, kUpdateOnly, NT>(tab, args, grid_cap, variant, pred, pred_want, s);
+        return launch_stream_c<OPT, kUpdateChunksPerWave, MIXED, kUpdateOnly, NT>(tab, args, pred, pred_want, s);
     default:
-        return launch_stream_t<OPT, MIXED, kUpdateAndNorm, NT>(tab, args, grid_cap, variant, pred, pred_want, s);
+        return launch_stream_c<OPT, kUpdateChunksPerWave, MIXED, kUpdateAndNorm, NT>(tab, args, pred, pred_want, s);
     }
 }
 
 template <class OPT>
 hipError_t launch_stream_o(StreamMode mode, bool mixed, const StreamTable &tab, const typename OPT::Args &args,
-                           const LaunchCfg &cfg, const int32_t *pred, int pred_want, hipStream_t s)
+                           bool nontemporal, const int32_t *pred, int pred_want, hipStream_t s)
 {
     if (tab.nchunks <= 0)
         return hipSuccess;
-    const int g = cfg.grid, v = cfg.variant;
     if (mixed)
-        return cfg.nontemporal ? launch_stream_m<OPT, true, true>(mode, tab, args, g, v, pred, pred_want, s)
-                               : launch_stream_m<OPT, true, false>(mode, tab, args, g, v, pred, pred_want, s);
-    return cfg.nontemporal ? launch_stream_m<OPT, false, true>(mode, tab, args, g, v, pred, pred_want, s)
-                           : launch_stream_m<OPT, false, false>(mode, tab, args, g, v, pred, pred_want, s);
+        return nontemporal ? launch_stream_m<OPT, true, true>(mode, tab, args, pred, pred_want, s)
+                           : launch_stream_m<OPT, true, false>(mode, tab, args, pred, pred_want, s);
+    return nontemporal ? launch_stream_m<OPT, false, true>(mode, tab, args, pred, pred_want, s)
+                       : launch_stream_m<OPT, false, false>(mode, tab, args, pred, pred_want, s);
+}
+
+// The two shapes of the K-way kernels: kAggCoarse for launches that follow the device-side decision
+// (few, large workgroups: cheap to dispatch when they only read the decision and exit), kAggFine for
+// launches over 256-element pieces (one wavefront, one 128-bit access per lane and stream).
+template <int KC, bool MIXED, bool NT>
+hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
+                        const int32_t *flag, int mode, hipStream_t s)
+{
+    const int pow2 = (K & (K - 1)) == 0;
+    if (shape == kAggFine)
+        hipLaunchKernelGGL((k_aggregate<64, 1, KC, MIXED, NT>), dim3(nchunks), dim3(64), 0, s, chunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode);
+    else
+        hipLaunchKernelGGL((k_aggregate<256, 4, KC, MIXED, NT>), dim3(nchunks), dim3(256), 0, s, chunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode);
+    return hipGetLastError();
 }
 
 template <int KC, bool MIXED, bool NT>
-hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                        int mode, int grid, int xcd_per, int shape, hipStream_t s)
+hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
+                       const int32_t *flag, int mode, const SgdArgs &sgd, hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
-    // shape = 10 * workgroup size + 128-bit accesses per lane, stream and pass
-#define SELSYNC_AGG(BB, UU)                                                                                       \
-    do {                                                                                                          \
-        hipLaunchKernelGGL((k_aggregate<BB, UU, KC, MIXED, NT>), dim3(grid), dim3(BB), 0, s, chunks, nchunks, tabs, \
-                           K, 1.0 / (double)K, pow2, flag, mode, xcd_per);                                        \
-        return hipGetLastError();                                                                                 \
-    } while (0)
-    switch (shape) {
-    case 641: SELSYNC_AGG(64, 1);
-    case 642: SELSYNC_AGG(64, 2);
-    case 2561: SELSYNC_AGG(256, 1);
-    case 2562: SELSYNC_AGG(256, 2);
-    case 2564: SELSYNC_AGG(256, 4);
-    case 5121: SELSYNC_AGG(512, 1);
-    case 5122: SELSYNC_AGG(512, 2);
-    case 10241: SELSYNC_AGG(1024, 1);
-    default:
-        break;
+    if (shape == kAggFine)
+        hipLaunchKernelGGL((k_update_ga<64, KC, MIXED, NT>), dim3(nchunks), dim3(64), 0, s, chunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode, sgd);
+    else
+        hipLaunchKernelGGL((k_update_ga<256, KC, MIXED, NT>), dim3(nchunks), dim3(256), 0, s, chunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode, sgd);
+    return hipGetLastError();
+}
+
+// Compile-time worker counts of the K-way kernels (replica pointers in registers); any other K
+// takes the run-time-K path (KC = 0).
+#define SELSYNC_SWITCH_K(K, CALL)      \
+    switch (K) {                       \
+    case 1: return CALL(1);            \
+    case 2: return CALL(2);            \
+    case 4: return CALL(4);            \
+    case 8: return CALL(8);            \
+    default: return CALL(0);           \
     }
-    SELSYNC_AGG(256, 4);
-#undef SELSYNC_AGG
+
+template <bool MIXED, bool NT>
+hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
+                        const int32_t *flag, int mode, hipStream_t s)
+{
+#define SELSYNC_AGG_CALL(KC) launch_agg_t<KC, MIXED, NT>(chunks, nchunks, shape, tabs, K, flag, mode, s)
+    SELSYNC_SWITCH_K(K, SELSYNC_AGG_CALL)
+#undef SELSYNC_AGG_CALL
 }
 
 template <bool MIXED, bool NT>
-hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K, const int32_t *flag,
-                        int mode, int grid, int xcd_per, int shape, hipStream_t s)
+hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
+                       const int32_t *flag, int mode, const SgdArgs &sgd, hipStream_t s)
 {
-    switch (K) {
-    case 1:
-        return launch_agg_t<1, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
-    case 2:
-        return launch_agg_t<2, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
-    case 4:
-        return launch_agg_t<4, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
-    case 8:
-        return launch_agg_t<8, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
-    default:
-        return launch_agg_t<0, MIXED, NT>(chunks, nchunks, tabs, K, flag, mode, grid, xcd_per, shape, s);
-    }
+#define SELSYNC_GA_CALL(KC) launch_ga_t<KC, MIXED, NT>(chunks, nchunks, shape, tabs, K, flag, mode, sgd, s)
+    SELSYNC_SWITCH_K(K, SELSYNC_GA_CALL)
+#undef SELSYNC_GA_CALL
 }
 
 }  // namespace
 
 // ---------------------------------------------------------------- launchers
 
-hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, const LaunchCfg &cfg,
+hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, const SgdArgs &sgd, bool nontemporal,
                          hipStream_t s, const int32_t *pred, int pred_want)
 {
     if (!tab.has_momentum)
-        return launch_stream_o<PlainSgdOpt>(mode, mixed, tab, sgd, cfg, pred, pred_want, s);
-    return launch_stream_o<SgdOpt>(mode, mixed, tab, sgd, cfg, pred, pred_want, s);
+        return launch_stream_o<PlainSgdOpt>(mode, mixed, tab, sgd, nontemporal, pred, pred_want, s);
+    return launch_stream_o<SgdOpt>(mode, mixed, tab, sgd, nontemporal, pred, pred_want, s);
 }
 
-hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a,
-                              const LaunchCfg &cfg, hipStream_t s)
+hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a, bool nontemporal,
+                              hipStream_t s)
 {
-    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, cfg, nullptr, 0, s);
+    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, nontemporal, nullptr, 0, s);
 }
 
 hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs, int nsegs, double *seg_sums,
@@ -1181,69 +1150,29 @@ hipError_t launch_track(const TrackerDev &td, const double *values, int slot_per
     return hipGetLastError();
 }
 
-hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, const AggTables &tabs, int K,
-                            const int32_t *sync_flag, int mode, const LaunchCfg &cfg, hipStream_t s)
+hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
+                            int K, const int32_t *sync_flag, int mode, bool nontemporal, hipStream_t s)
 {
     if (nchunks <= 0)
         return hipSuccess;
-    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
     if (mixed)
-        return cfg.nontemporal ? launch_agg_k<true, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s)
-                               : launch_agg_k<true, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s);
-    return cfg.nontemporal ? launch_agg_k<false, true>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s)
-                           : launch_agg_k<false, false>(chunks, nchunks, tabs, K, sync_flag, mode, grid, xcd_per, cfg.agg_shape, s);
+        return nontemporal ? launch_agg_k<true, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s)
+                           : launch_agg_k<true, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s);
+    return nontemporal ? launch_agg_k<false, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s)
+                       : launch_agg_k<false, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s);
 }
 
-namespace {
-template <int KC, bool MIXED, bool NT>
-hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
-{
-    const int pow2 = (K & (K - 1)) == 0;
-    if (block == 64)
-        hipLaunchKernelGGL((k_update_ga<64, KC, MIXED, NT>), dim3(grid), dim3(64), 0, s, chunks, nchunks, tabs, K,
-                           1.0 / (double)K, pow2, flag, mode, sgd, xcd_per);
-    else
-        hipLaunchKernelGGL((k_update_ga<kBlock, KC, MIXED, NT>), dim3(grid), dim3(kBlock), 0, s, chunks, nchunks, tabs,
-                           K, 1.0 / (double)K, pow2, flag, mode, sgd, xcd_per);
-    return hipGetLastError();
-}
-
-template <bool MIXED, bool NT>
-hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const SgdArgs &sgd, int grid, int xcd_per, hipStream_t s)
-{
-    switch (K) {
-    case 1:
-        return launch_ga_t<1, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
-    case 2:
-        return launch_ga_t<2, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
-    case 4:
-        return launch_ga_t<4, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
-    case 8:
-        return launch_ga_t<8, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
-    default:
-        return launch_ga_t<0, MIXED, NT>(chunks, nchunks, block, tabs, K, flag, mode, sgd, grid, xcd_per, s);
-    }
-}
-}  // namespace
-
-hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, int block, const AggTables &tabs, int K,
-                            const int32_t *sync_flag, int mode, const SgdArgs &sgd, const LaunchCfg &cfg,
+hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
+                            int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal,
                             hipStream_t s)
 {
     if (nchunks <= 0)
         return hipSuccess;
-    const int xcd_per = cfg.xcd_swizzle ? (nchunks + 7) / 8 : 0;
-    const int vtotal = xcd_per > 0 ? 8 * xcd_per : nchunks;
-    const int grid = cfg.grid < vtotal ? cfg.grid : vtotal;
     if (mixed)
-        return cfg.nontemporal ? launch_ga_k<true, true>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
-                               : launch_ga_k<true, false>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
-    return cfg.nontemporal ? launch_ga_k<false, true>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s)
-                           : launch_ga_k<false, false>(chunks, nchunks, block, tabs, K, sync_flag, mode, sgd, grid, xcd_per, s);
+        return nontemporal ? launch_ga_k<true, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s)
+                           : launch_ga_k<true, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s);
+    return nontemporal ? launch_ga_k<false, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s)
+                       : launch_ga_k<false, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s);
 }
 
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

@@ -4,6 +4,7 @@ HIP library and compares them after every step."""
 from __future__ import annotations
 
 import math
+from concurrent.futures import ThreadPoolExecutor
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -81,8 +82,13 @@ class LockStep:
     def __init__(self, B, shapes_numel: Sequence[int], K: int, delta: float, window: int = 25, alpha: float = -1.0,
                  mixed: bool = False, init_params: Optional[List[np.ndarray]] = None, misalign: int = 0,
                  tuning: Optional[dict] = None, seed: int = 0, misalign_g: Optional[int] = None,
-                 momentum_free: bool = False, misalign_m: Optional[int] = None, misalign_glob: Optional[int] = None):
+                 momentum_free: bool = False, misalign_m: Optional[int] = None, misalign_glob: Optional[int] = None,
+                 oracle_threads: int = 1):
         self.B, self.K, self.mixed = B, K, mixed
+        # > 1: the oracle's per-replica calls (norm, update) of one step run on that many host threads.
+        # Replicas are independent and every call is the unchanged single-threaded oracle routine, so
+        # no sum changes its order; it only shortens full-size multi-hundred-step runs.
+        self.pool = ThreadPoolExecutor(oracle_threads) if oracle_threads > 1 else None
         self.momentum_free = momentum_free       # no momentum buffers on either side (plain SGD)
         self.numel = list(shapes_numel)
         if init_params is None:
@@ -174,10 +180,20 @@ class LockStep:
             self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first), nesterov=nesterov)
             self.ctx.aggregate_params(plan, always=False)
         g = self.h_grads[slot]
-        rec = self.oracle.track(g, gs)
-        for k in range(self.K):
+
+        def update(k):
             O.sgd_update(self.h_w[k], None if self.momentum_free else self.h_m[k], g[k], lr, mu, wd, gs, first,
                          None if not self.mixed else self.h_c[k], nesterov=nesterov)
+
+        if self.pool is None:
+            rec = self.oracle.track(g, gs)
+            for k in range(self.K):
+                update(k)
+        else:
+            # norms first (they read the gradients only), handed to the trackers in worker order
+            xs = list(self.pool.map(lambda k: O.norm_sq(g[k], gs), range(self.K)))
+            rec = self.oracle.track_norms(xs)
+            list(self.pool.map(update, range(self.K)))
         sync = self._check_decision(dec, rec)
         if sync:
             pre = [np.max(np.abs(np.stack([self.h_w[k][t] for k in range(self.K)])), axis=0).astype(np.float64)
@@ -291,22 +307,32 @@ class LockStep:
 
     def close(self):
         self.ctx.close()
+        if self.pool is not None:
+            self.pool.shutdown()
 
 
 def run_workload(B, wl: W.Workload, steps: Optional[int] = None, compare_every: int = 1, fused: bool = True,
-                 tuning: Optional[dict] = None, pool: Optional[int] = None) -> LockStep:
-    """Run a whole seeded workload in lock step and return the runner (with counters)."""
+                 tuning: Optional[dict] = None, pool: Optional[int] = None, oracle_threads: int = 1,
+                 progress_every: int = 0) -> LockStep:
+    """Run a whole seeded workload in lock step and return the runner (with counters).  Decisions,
+    norms and Delta are compared every step; tensors every `compare_every` steps (0: never on request),
+    at every synchronising step and after the last step."""
+    import time
+    t0 = time.time()
     steps = wl.steps if steps is None else steps
     pool = min(wl.pool if pool is None else pool, steps)
     ls = LockStep(B, wl.numels, wl.num_workers, wl.delta, wl.window, -1.0, wl.mixed_bf16,
-                  init_params=W.initial_params(wl), tuning=tuning)
+                  init_params=W.initial_params(wl), tuning=tuning, oracle_threads=oracle_threads)
     for b in range(pool):
         ls.bind_grads(b, [W.unit_grads(wl, k, b) for k in range(wl.num_workers)])
     sig = wl.sigmas(steps)
     for t in range(steps):
-        cmp_now = (t % compare_every == 0) or t == steps - 1
+        cmp_now = (compare_every > 0 and t % compare_every == 0) or t == steps - 1
         dec, rec = ls.step(t % pool, wl.lr, wl.momentum, wl.weight_decay, sig[t], fused=fused,
                            compare_tensors=cmp_now)
+        if progress_every and (t + 1) % progress_every == 0:
+            print("  %s step %d/%d: %d sync so far, min |Delta - delta| %.3g (%.0f s)" % (
+                wl.name, t + 1, steps, ls.oracle.steps_sync, ls.min_margin, time.time() - t0), flush=True)
     st = ls.ctx.stats()
     assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
     assert st["lssr"] == ls.oracle.lssr

@@ -47,7 +47,7 @@ def test_struct_layouts_are_plain_c(B):
     assert ctypes.sizeof(B.selsync_config) == 24
     assert ctypes.sizeof(B.selsync_sgd) == 24
     assert ctypes.sizeof(B.selsync_stats) == 40
-    assert ctypes.sizeof(B.selsync_tuning) == 36
+    assert ctypes.sizeof(B.selsync_tuning) == 16
 
 
 def test_status_strings(B):

@@ -41,6 +41,25 @@ def test_vgg11_like_full_size_three_steps_with_sync():
     ls.close()
 
 
+def test_vgg11_like_full_size_all_200_steps():
+    """The 133M-parameter configuration exactly as stated -- full size, K = 4, all 200 steps, library
+    defaults (the launch configuration bench.py times): decisions, norms and Delta compared with the
+    oracle after every step, every tensor of every replica at each synchronising step and at the end."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2307_07950_amd import binding as B
+    wl = W.get("c4")
+    assert (wl.num_params, wl.num_workers, wl.steps) == (132_863_336, 4, 200)
+    ls = PU.run_workload(B, wl, compare_every=0, oracle_threads=wl.num_workers, progress_every=20)
+    print("%s: steps=%d sync=%d lssr=%.3f min|Delta-delta|=%.3g worst norm rel=%.2g worst ulp=%d forced=%d" % (
+        wl.name, ls.steps_done, ls.oracle.steps_sync, ls.oracle.lssr, ls.min_margin, ls.worst_norm_rel,
+        ls.worst_ulp, ls.forced), flush=True)
+    assert ls.steps_done == 200 and ls.oracle.steps_sync >= 7
+    assert ls.forced == 0 and ls.min_margin > 1e-3
+    assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-10
+    ls.close()
+
+
 @pytest.mark.parametrize("name,params,tensors,workers", [("c2", 44_541_480, 314, 8), ("c3", 61_100_840, 16, 8),
                                                          ("c5", 61_212_158, 186, 8)])
 def test_other_workloads_full_size_local_step_then_sync(name, params, tensors, workers):

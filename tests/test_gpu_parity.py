@@ -29,7 +29,7 @@ def rng(seed):
     return np.random.default_rng(seed)
 
 
-SMALL_CHUNK = dict(chunk_elems=8192, blocks_per_cu=2, stream_variant=14, nontemporal=1)   # persistent grid, multi-pass chunks
+SMALL_CHUNK = dict(chunk_elems=8192, nontemporal=1)   # pieces of 32 tiles: the multi-tile loop of the streaming kernel
 
 # tensor-size sets: tiny / ragged tails / several tiles / empty tensors / exactly one chunk
 SIZE_SETS = {
@@ -180,12 +180,11 @@ def test_local_step_automatic_first_step(B):
 
 
 @pytest.mark.parametrize("mixed", [False, True])
-@pytest.mark.parametrize("layout", [0, 1, 2])
-def test_many_chunks_take_the_segment_reduction_level(B, mixed, layout):
+def test_many_chunks_take_the_segment_reduction_level(B, mixed):
     # more than 16384 chunks: per-chunk partials -> per-segment sums -> tracker
     numel = [4_200_000 + 13, 77]
     K = 2
-    ls = PU.LockStep(B, numel, K, delta=float("inf"), mixed=mixed, seed=3, tuning=dict(table_layout=layout))
+    ls = PU.LockStep(B, numel, K, delta=float("inf"), mixed=mixed, seed=3)
     r = rng(23)
     grads = []
     for k in range(K):
@@ -199,17 +198,12 @@ def test_many_chunks_take_the_segment_reduction_level(B, mixed, layout):
     ls.close()
 
 
-@pytest.mark.parametrize("variant,chunk", [(0, 0), (0, 1024), (11, 256), (11, 768), (12, 512), (12, 2048), (14, 1024),
-                                           (14, 65536), (21, 256), (22, 512), (22, 1536), (41, 256), (42, 512),
-                                           (81, 256), (81, 512)])
-@pytest.mark.parametrize("layout", [0, 1, 2])
-@pytest.mark.parametrize("persistent", [0, 2])
+@pytest.mark.parametrize("chunk", [0, 256, 768, 1024, 2048, 65536])
 @pytest.mark.parametrize("nt", [0, 1])
-def test_every_kernel_shape_and_table_layout_gives_the_same_results(B, variant, chunk, layout, persistent, nt):
+def test_every_piece_size_and_access_kind_gives_the_same_results(B, chunk, nt):
     numel = [100003, 513, 4096, 255]
     K = 2
-    tuning = dict(chunk_elems=chunk, blocks_per_cu=persistent, stream_variant=variant, table_layout=layout,
-                  nontemporal=nt)
+    tuning = dict(chunk_elems=chunk, nontemporal=nt)
     for mixed in (False, True):
         ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, tuning=tuning, seed=4)
         r = rng(24)
@@ -255,22 +249,29 @@ def test_aggregate_matches_oracle(B, K, mixed):
     ls.close()
 
 
-@pytest.mark.parametrize("shape,chunk", [(641, 256), (642, 512), (2561, 1024), (2562, 2048), (2564, 4096), (5121, 2048),
-                                         (5122, 4096), (10241, 4096), (2564, 1024), (641, 8192)])
+@pytest.mark.parametrize("chunk", [256, 512, 768, 1024, 4096, 8192])
 @pytest.mark.parametrize("K", [3, 4])
-def test_aggregate_kernel_shapes_give_identical_results(B, shape, chunk, K):
+def test_aggregate_piece_sizes_give_identical_results(B, chunk, K):
+    # the table of the decision-following launch, cut into pieces of the given size (one-wavefront
+    # workgroups below 1024 elements, 256-thread workgroups from there on)
     numel = [70001, 5, 8192, 0, 33333]
     for mixed in (False, True):
-        ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, seed=7,
-                         tuning=dict(agg_shape=shape, agg_chunk_elems=chunk, xcd_swizzle=K % 2, nontemporal=K % 2))
+        ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, seed=7,
+                         tuning=dict(agg_chunk_elems=chunk, nontemporal=K % 2))
         r = rng(300 + K)
         for k in range(K):
             for t, n in enumerate(numel):
                 ls.h_w[k][t] += (r.standard_normal(n) * 1e-3).astype(np.float32)
                 ls.d_w[k][t].copy_(torch.from_numpy(ls.h_w[k][t]))
-        ls.bind_grads(0, [[W.round_to_bf16_bits(np.zeros(n, np.float32)) if mixed else np.zeros(n, np.float32)
-                           for n in numel] for _ in range(K)])
-        ls.ctx.aggregate_params(ls.plans[0], always=True)
+        grads = []
+        for k in range(K):
+            gk = [r.standard_normal(n).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(0, grads)
+        # a 3x jump of the gradient scale makes the device-side decision "sync" under delta = 0.3
+        assert ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True).sync == 0
+        assert ls.ctx.track_grad_change(ls.plans[0], 3.0, blocking=True).sync == 1
+        ls.ctx.aggregate_params(ls.plans[0], always=False)
         O.average_params(ls.h_w, ls.h_glob, ls.h_c, ls.h_gc)
         for t in range(len(numel)):
             assert PU.to_host(ls.d_glob[t]).tobytes() == ls.h_glob[t].tobytes()
@@ -426,12 +427,11 @@ def test_reset_clears_tracker_and_counters(B):
     ls.close()
 
 
-@pytest.mark.parametrize("layout", [0, 1, 2])
-def test_per_tensor_norms_match_oracle(B, layout):
+def test_per_tensor_norms_match_oracle(B):
     numel = [70001, 0, 5, 4096, 513]
     K = 3
     for mixed in (False, True):
-        ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, seed=17, tuning=dict(table_layout=layout))
+        ls = PU.LockStep(B, numel, K, delta=0.3, mixed=mixed, seed=17)
         r = rng(97)
         grads = []
         for k in range(K):
@@ -480,6 +480,137 @@ def test_tracker_state_checkpoint_and_resume(B):
     assert e.value.status == B.SELSYNC_ERR_INVALID_ARG
     ctx3.close()
     ctx2.close()
+    ls.close()
+
+
+def test_checkpoint_restores_the_threshold_on_host_and_device(B):
+    """A blob saved under delta = 0.3 restored into a context that was created with delta = 0 and has
+    already taken a decision: from then on the context must behave as under 0.3 (local steps are NOT
+    averaged), checked against the oracle on decisions and every tensor."""
+    numel = [70001, 513, 4096]
+    K = 3
+    ls = PU.LockStep(B, numel, K, delta=0.3, window=5, alpha=0.5, seed=71)
+    r = rng(710)
+    for slot in range(2):
+        ls.bind_grads(slot, [[(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+                             for _ in range(K)])
+    sched = [0, 0, 1, 1, 0, 0, 1, 0, 1, 1, 0, 0]
+    for t in range(5):
+        ls.step(sched[t], 0.05, 0.9, 1e-4, 1.0)
+    blob = ls.ctx.get_state()
+    ctx2 = B.SelSync(K, 0.0, 5, 0.5)
+    plans2 = {slot: ctx2.plan(ls.d_grads[slot], ls.d_w, ls.d_m, ls.d_glob) for slot in (0, 1)}
+    assert ctx2.track_grad_change(plans2[0], 1.0, blocking=True).sync == 1     # delta 0: "every step syncs"
+    ctx2.set_state(blob)
+    assert ctx2.stats() == ls.ctx.stats()
+    old = ls.ctx
+    ls.ctx, ls.plans = ctx2, plans2
+    syncs = 0
+    for t in range(5, 12):
+        dec, rec = ls.step(sched[t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0))
+        syncs += rec.sync
+    assert 0 < syncs < 7 and ls.worst_ulp == 0 and ls.forced == 0
+    # the gradient-aggregation update takes the same host-side shortcut: it must follow the decision too
+    for t in range(3):
+        ls.step_ga(sched[t], 0.05, 0.9, 1e-4, 1.0, fused=(t != 1))
+    # and the other direction: a delta = 0 blob restored into a delta = 0.3 context synchronises every step
+    ctx3 = B.SelSync(K, 0.0, 5, 0.5)
+    ctx3.track_grad_change(ctx3.plan(ls.d_grads[0], ls.d_w, ls.d_m, ls.d_glob), 1.0, blocking=True)
+    blob0 = ctx3.get_state()
+    ctx3.close()
+    ls.ctx.set_state(blob0)
+    ls.oracle = O.OracleSelSync(K, 0.0, 5, 0.5)
+    ls.oracle.track(ls.h_grads[0], 1.0)
+    for t in range(3):
+        dec, rec = ls.step(sched[t], 0.05, 0.9, 1e-4, 1.0, fused=(t != 1))
+        assert dec.sync == 1
+    assert ls.worst_ulp == 0
+    old.close()
+    ls.close()
+
+
+def test_mode0_follows_the_device_decision_after_the_threshold_changes(B):
+    """The decision of the last tracking call stands until the next one: lowering delta to 0 after a
+    "local" decision must not make a mode-0 aggregation (or gradient-aggregation update) synchronise."""
+    numel = [50000, 7]
+    K = 2
+    ls = PU.LockStep(B, numel, K, delta=0.3, seed=72)
+    ls.d_w[1][0].add_(1.0)
+    ls.h_w[1][0] += np.float32(1.0)
+    before = [[PU.to_host(x) for x in ls.d_w[k]] for k in range(K)]
+    ls.bind_grads(0, [[rng(720 + k).standard_normal(n).astype(np.float32) for n in numel] for k in range(K)])
+    assert ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True).sync == 0
+    ls.oracle.track(ls.h_grads[0], 1.0)
+    ls.ctx.set_delta(0.0)
+    ls.ctx.aggregate_params(ls.plans[0], always=False)
+    for k in range(K):
+        for t in range(len(numel)):
+            assert PU.to_host(ls.d_w[k][t]).tobytes() == before[k][t].tobytes()
+    assert not PU.to_host(ls.d_glob[0]).any()
+    # same for the gradient-aggregation update: the decision is "local", each worker applies its own gradient
+    ls.ctx.ga_update(ls.plans[0], 0.1, 0.9, 1e-4, 1.0, first_step=1, always=False)
+    O.ga_update(ls.h_grads[0], ls.h_w, ls.h_m, 0.1, 0.9, 1e-4, 1.0, True, False)
+    ls.compare()
+    # the next tracking call decides under the new threshold
+    assert ls.ctx.track_grad_change(ls.plans[0], 1.0, blocking=True).sync == 1
+    ls.ctx.aggregate_params(ls.plans[0], always=False)
+    O.average_params(ls.h_w, ls.h_glob)
+    for t in range(len(numel)):
+        assert PU.to_host(ls.d_glob[t]).tobytes() == ls.h_glob[t].tobytes()
+    ls.close()
+
+
+@pytest.mark.parametrize("variant", ["pa", "ga"])
+def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant):
+    """A step recorded into a HIP graph under delta = 0 (when the library expects every step to
+    synchronise) and replayed after selsync_set_delta(0.3) must take the decisions of delta = 0.3:
+    every replay is compared with the oracle, decisions and tensors."""
+    numel = [150001, 777, 4096]
+    K = 4
+    r = rng(730)
+    ls = PU.LockStep(B, numel, K, delta=0.0, window=4, alpha=0.5, seed=73)
+    ls.bind_grads(0, [[(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel] for _ in range(K)])
+    scales = [1.0, 1.0, 3.0, 1.0, 1.0, 0.2, 1.0]
+    step = ls.step if variant == "pa" else ls.step_ga
+    step(0, 0.05, 0.9, 1e-4, scales[0])                     # eager, delta = 0: synchronises
+    assert ls.oracle.steps_sync == 1
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        if variant == "pa":
+            ls.ctx.step(ls.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=0)
+        else:
+            ls.ctx.step_ga(ls.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=0)
+    ls.ctx.set_delta(0.3)
+    ls.oracle.delta = 0.3
+    syncs = 0
+    for t in range(1, 7):
+        for k in range(K):                                  # eager work between replays: rescale the gradients
+            for i, x in enumerate(ls.d_grads[0][k]):
+                f = np.float32(scales[t]) / np.float32(scales[t - 1])
+                x.mul_(float(f))
+                ls.h_grads[0][k][i] *= f
+        g.replay()
+        torch.cuda.synchronize()
+        dec = ls.ctx.read_decision()
+        rec = ls.oracle.track(ls.h_grads[0], 1.0)
+        sync = ls._check_decision(dec, rec)
+        assert ls.forced == 0
+        if variant == "pa":
+            for k in range(K):
+                O.sgd_update(ls.h_w[k], ls.h_m[k], ls.h_grads[0][k], 0.05, 0.9, 1e-4, 1.0, False)
+            if sync:
+                O.average_params(ls.h_w, ls.h_glob)
+        else:
+            O.ga_update(ls.h_grads[0], ls.h_w, ls.h_m, 0.05, 0.9, 1e-4, 1.0, False, bool(sync))
+        ls.steps_done += 1
+        ls.compare()
+        if variant == "pa" and sync:
+            for t2 in range(len(numel)):
+                assert PU.to_host(ls.d_glob[t2]).tobytes() == ls.h_glob[t2].tobytes()
+        syncs += sync
+    assert 0 < syncs < 6 and ls.worst_ulp == 0
+    del g
     ls.close()
 
 
@@ -691,7 +822,7 @@ def test_tensors_at_arbitrary_offsets_inside_larger_buffers(B, off_w, off_g, mix
     # parameters/momenta and gradients may sit at different offsets (equal or different vector phase)
     numel = [70001, 5, 4096, 0, 1023, 255, 257]
     K = 2
-    for tuning in (None, dict(chunk_elems=1024, stream_variant=22, agg_chunk_elems=512, agg_shape=642, ga_chunk_elems=256)):
+    for tuning in (None, dict(chunk_elems=1024, agg_chunk_elems=512, ga_chunk_elems=256)):
         ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=off_w, misalign_g=off_g,
                          seed=41, tuning=tuning)
         r = rng(170)
@@ -731,12 +862,8 @@ def test_random_configuration_matches_oracle(B, seed):
         numel[0] = 777
     mixed = bool(r.integers(0, 2))
     chunk = int(r.choice([256, 512, 1024, 4096]))
-    shapes = [s for s in (11, 12, 14, 21, 22, 41, 42, 81)]
-    tuning = dict(chunk_elems=chunk, stream_variant=int(r.choice([0] + shapes)), table_layout=int(r.integers(0, 3)),
-                  blocks_per_cu=int(r.choice([0, 0, 1])), nontemporal=int(r.integers(0, 2)),
-                  agg_chunk_elems=int(r.choice([0, 256, 1024, 4096])),
-                  agg_shape=int(r.choice([0, 641, 642, 2561, 2562, 2564, 5121, 5122, 10241])),
-                  ga_chunk_elems=int(r.choice([0, 256, 1024])), xcd_swizzle=int(r.integers(0, 2)))
+    tuning = dict(chunk_elems=chunk, nontemporal=int(r.integers(0, 2)),
+                  agg_chunk_elems=int(r.choice([0, 256, 1024, 4096])), ga_chunk_elems=int(r.choice([0, 256, 1024])))
     off = lambda: int(r.choice([0, 0, 1, 2, 3, 4, 17, 64, 100, 255, 256, 300]))
     momentum_free = bool(r.integers(0, 4) == 0)
     ls = PU.LockStep(B, numel, K, delta=float(r.choice([0.0, 0.1, 0.3])), window=int(r.choice([1, 3, 25])),
@@ -772,7 +899,7 @@ def test_random_configuration_matches_oracle(B, seed):
 
 @pytest.mark.parametrize("mixed", [False, True])
 @pytest.mark.parametrize("misalign", [0, 3])
-@pytest.mark.parametrize("tuning", [None, dict(chunk_elems=1024, stream_variant=22, table_layout=1)])
+@pytest.mark.parametrize("tuning", [None, dict(chunk_elems=1024)])
 def test_momentum_free_sgd_matches_oracle(B, mixed, misalign, tuning):
     # plain SGD of the Transformer recipe (Sec. IV-A): plans without momentum buffers
     numel = [70001, 5, 4096, 0, 1023]
@@ -867,23 +994,27 @@ def test_nesterov_under_gradient_aggregation_matches_oracle(B, mixed):
 
 # ================================================================= the five workloads, lock step
 
-@pytest.mark.parametrize("name,shrink,steps,compare_every", [
-    ("c1", 1, None, 1),
-    ("c2", 8, 60, 10),
-    ("c3", 8, 30, 10),
-    ("c4", 8, 60, 10),
-    ("c5", 8, 40, 10),
+@pytest.mark.parametrize("name,shrink,steps,compare_every,min_syncs", [
+    ("c1", 1, 50, 1, 2),         # full size, every tensor after every step
+    ("c2", 4, 200, 20, 1),       # stated step counts; channel widths divided by 4 so that the oracle
+    ("c3", 4, 200, 40, 0),       # finishes in seconds (the full-size runs are in test_gpu_fullsize.py)
+    ("c4", 4, 200, 25, 7),
+    ("c5", 4, 500, 50, 0),       # constant gradient scale: the stated schedule never crosses delta = 0.1
 ])
-def test_workload_lockstep(B, name, shrink, steps, compare_every):
+def test_workload_lockstep(B, name, shrink, steps, compare_every, min_syncs):
+    """The five configurations over ALL their steps: decisions, norms and Delta compared every step,
+    tensors every `compare_every` steps, at every synchronising step and at the end."""
     wl = W.get(name, shrink=shrink)
-    ls = PU.run_workload(B, wl, steps=steps, compare_every=compare_every)
+    assert wl.steps == steps
+    ls = PU.run_workload(B, wl, steps=steps, compare_every=compare_every, oracle_threads=wl.num_workers,
+                         progress_every=100)
     print("%s: steps=%d sync=%d lssr=%.3f min|Delta-delta|=%.3g worst norm rel=%.2g worst ulp=%d forced=%d" % (
         wl.name, ls.steps_done, ls.oracle.steps_sync, ls.oracle.lssr, ls.min_margin, ls.worst_norm_rel,
         ls.worst_ulp, ls.forced))
+    assert ls.steps_done == steps
     assert ls.min_margin > 1e-3, "seed puts a decision too close to the threshold for a meaningful run"
-    assert ls.forced == 0
-    if name in ("c1", "c2", "c4"):
-        assert ls.oracle.steps_sync > 0          # the schedule contains real synchronisations
+    assert ls.forced == 0 and ls.worst_ulp == 0
+    assert ls.oracle.steps_sync >= min_syncs          # the schedule contains real synchronisations
     ls.close()
 
 
