@@ -9,8 +9,12 @@ K = 4, 200 steps, 4x gradient spike every 25 steps) that the 70 %-of-HBM target 
 stated for.  Inputs are seeded synthetic tensors generated directly in HBM.
 
 Prints ONE JSON line: steps/s (value), effective GB/s over the run, the roofline
-object of the dominant kernel (HIP events around every launch, recorded by the
-library on the launch stream), and the CPU oracle's rate on a bounded sample.
+object of the dominant kernel (HIP events around sampled launches, recorded by the
+library on the launch stream), a per-kernel survey taken right after the timed
+region (the same schedule continued until a synchronising step has happened, every
+kernel bracketed by events: working and early-exit times of the aggregation kernel,
+the tracker kernels, whole local and synchronising steps), and the CPU oracle's rate
+on a bounded sample of the same tensors, on one core and on all host cores.
 """
 from __future__ import annotations
 
@@ -26,10 +30,48 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
-# plain copy kernel of known size (profiles/pmc_hbm_traffic_vgg11like_k4.txt); not measurable from inside this
-# process, so it is quoted for the workload it was measured on and null otherwise.
-MEASURED_TRAFFIC_BYTES = {("vgg11_like", 1): 1.0679e10}
+# HBM bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
+# plain copy kernel of known size.  They cannot be measured from inside this process, so they are read from the
+# committed counter summaries (lines "bench-readable: workload=<name> shrink=<n> kernel=k_stream
+# traffic_bytes_per_launch=<bytes>") and are null for a workload nobody has profiled.
+TRAFFIC_PROFILES = ["profiles/pmc_hbm_traffic_vgg11like_k4.txt"]
+
+
+def measured_traffic(workload_name, shrink):
+    """(bytes per k_stream launch, file it was read from) or (None, None)."""
+    import re
+    for rel in TRAFFIC_PROFILES:
+        try:
+            text = open(os.path.join(ROOT, rel)).read()
+        except OSError:
+            continue
+        for m in re.finditer(r"bench-readable:\s+workload=(\S+)\s+shrink=(\d+)\s+kernel=k_stream\s+"
+                             r"traffic_bytes_per_launch=(\S+)", text):
+            if m.group(1) == workload_name and int(m.group(2)) == shrink:
+                return float(m.group(3)), rel
+    return None, None
+
+
+def host_info():
+    """What the CPU baseline ran on: usable cores, CPU model, the oracle's compiler flags."""
+    ncpu = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    # a GPU box hands each job a share of its cores and says so in OMP_NUM_THREADS: never use more
+    share = ncpu
+    try:
+        share = max(1, min(ncpu, int(os.environ.get("OMP_NUM_THREADS", ncpu))))
+    except ValueError:
+        pass
+    from oracle import selsync_oracle as O
+    return {"nproc": ncpu, "os_cpu_count": os.cpu_count(), "core_share": share, "cpu_model": model,
+            "oracle_cflags": "gcc " + " ".join(O.CFLAGS)}
 
 
 def parse_args():
@@ -40,13 +82,9 @@ def parse_args():
     ap.add_argument("--workload", default="c4", help="c1..c5 (default c4, the 133M-parameter configuration)")
     ap.add_argument("--shrink", type=int, default=1, help="divide channel widths (debugging only)")
     ap.add_argument("--chunk-elems", type=int, default=0)
-    ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--agg-chunk-elems", type=int, default=0)
     ap.add_argument("--ga-chunk-elems", type=int, default=0)
-    ap.add_argument("--stream-shape", type=int, default=0,
-                    help="update/norm kernel shape 10*C + U (C chunks per wavefront, U 128-bit accesses per lane)")
-    ap.add_argument("--table-layout", type=int, default=0, help="0 striped by XCD (default), 1 linear, 2 XCD-contiguous")
     ap.add_argument("--variant", default="pa", choices=["pa", "unfused", "ga", "adam", "plain", "nesterov"],
                     help="pa: fused selsync_step (default, the headline); unfused: the three primitives in Alg. 1 "
                          "order; ga: gradient-aggregation variant (selsync_step_ga); adam: Adam as the local update "
@@ -68,7 +106,11 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel (1 GiB read + 1 GiB written, 3 times) so "
                          "that FETCH_SIZE / WRITE_SIZE counters can be scaled by a kernel of known traffic")
-    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for the CPU baseline")
+    ap.add_argument("--cpu-steps", type=int, default=8, help="oracle local steps timed for the CPU baseline")
+    ap.add_argument("--no-survey", action="store_true",
+                    help="skip the per-kernel survey after the timed region (other_kernels becomes null)")
+    ap.add_argument("--survey-max-steps", type=int, default=30,
+                    help="continue the schedule for at most this many steps while waiting for a synchronising one")
     return ap.parse_args()
 
 
@@ -118,68 +160,94 @@ def make_device_state(torch, wl, seed):
     return out
 
 
-def cpu_baseline(wl, lssr, steps_timed):
-    """Time the plain C oracle (single thread) on the host: `steps_timed` local steps
-    (norm + tracker + update for all K replicas) and one aggregation, at full size."""
+def cpu_baseline(torch, wl, st, sigma, lssr, steps_timed):
+    """Time the plain C oracle on the host, on the GPU run's own tensors (copied back after the run:
+    every replica's parameters, momenta and gradient set 0, scaled by `sigma` as in the run):
+    `steps_timed` full-size local steps (norm + tracker + update for all K replicas) and full-size
+    aggregations, once on a single thread (the definitional baseline) and once spread over every
+    host core in ways that leave the order of every sum unchanged."""
     import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import selsync_oracle as O
     K = wl.num_workers
-    r = np.random.default_rng(wl.seed)
+
+    def host(t):
+        c = t.detach().cpu().contiguous()
+        if c.dtype == torch.bfloat16:
+            return c.view(torch.int16).numpy().view(np.uint16)
+        return c.numpy()
+
     numel = wl.numels
-    base = [(r.standard_normal(n, dtype=np.float32) * np.float32(wl.param_std)) for n in numel]
-    w = [[b.copy() for b in base] for _ in range(K)]
-    m = [[np.zeros_like(b) for b in base] for _ in range(K)]
-    glob = [np.zeros_like(b) for b in base]
-    if wl.mixed_bf16:
-        from paper_2307_07950_amd import workloads as W
-        g = [[W.round_to_bf16_bits(r.standard_normal(n, dtype=np.float32) * np.float32(1e-3)) for n in numel]
-             for _ in range(K)]
-        c = [[W.round_to_bf16_bits(b) for b in base] for _ in range(K)]
-        gc = [np.zeros(n, np.uint16) for n in numel]
-    else:
-        g = [[r.standard_normal(n, dtype=np.float32) * np.float32(1e-3) for n in numel] for _ in range(K)]
-        c, gc = None, None
+    w = [[host(x) for x in st["w"][k]] for k in range(K)]
+    m = [[host(x) for x in st["m"][k]] for k in range(K)]
+    g = [[host(x) for x in st["grads"][0][k]] for k in range(K)]
+    glob = [host(x) for x in st["glob"]]
+    c = [[host(x) for x in st["copy"][k]] for k in range(K)] if wl.mixed_bf16 else None
+    gc = [host(x) for x in st["gcopy"]] if wl.mixed_bf16 else None
+    n_agg = max(1, steps_timed // 4)
+
+    # (i) one thread
     o = O.OracleSelSync(K, float("inf"), wl.window)
     t0 = time.perf_counter()
     for i in range(steps_timed):
-        o.step(g, w, m, glob, wl.lr, wl.momentum, wl.weight_decay, 1.0, copies=c, global_copy=gc)
+        o.step(g, w, m, glob, wl.lr, wl.momentum, wl.weight_decay, sigma, copies=c, global_copy=gc, first=False)
     t_local = (time.perf_counter() - t0) / steps_timed
     t0 = time.perf_counter()
-    O.average_params(w, glob, c, gc)
-    t_sync = time.perf_counter() - t0
+    for i in range(n_agg):
+        O.average_params(w, glob, c, gc)
+    t_sync = (time.perf_counter() - t0) / n_agg
     per_step = t_local + (1.0 - lssr) * t_sync
+    info = host_info()
     out = {
         "value": 1.0 / per_step, "unit": "steps/s", "cores": 1, "kind": "oracle",
-        "sample": "%d full-size local steps (all K=%d replicas, %d params each) + 1 full-size aggregation, "
-                  "combined with the run's LSSR %.3f; single thread, gcc -O2" % (steps_timed, K, sum(numel), lssr),
-        "local_step_s": t_local, "aggregation_s": t_sync,
+        "sample": "%d full-size local steps (all K=%d replicas, %d params each) + %d full-size aggregations on the "
+                  "GPU run's own tensors, combined with the run's LSSR %.3f; single thread" % (
+                      steps_timed, K, sum(numel), n_agg, lssr),
+        "local_step_s": t_local, "aggregation_s": t_sync, "host": info,
     }
-    # The same oracle calls spread over host threads where that changes no order of arithmetic: one thread
-    # per replica for norm + update (replicas are independent), one task per tensor for the aggregation.
-    from concurrent.futures import ThreadPoolExecutor
-    ncpu = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
-    nthreads = max(1, min(ncpu, 16))
 
-    def replica_step(k):
-        x = O.norm_sq(g[k], 1.0)
-        O.sgd_update(w[k], m[k], g[k], wl.lr, wl.momentum, wl.weight_decay, 1.0, False, None if c is None else c[k])
-        return x
+    # (ii) every host core.  The norm is one in-order sum per replica: one task per replica.  Update and
+    # averaging are element-wise: tasks over (replica, tensor, element range) / (tensor, element range),
+    # each the unchanged oracle routine on a contiguous slice.
+    ncpu = info["core_share"]
+    span = 1 << 21
 
-    def tensor_average(t):
-        O.average_params([[w[k][t]] for k in range(K)], [glob[t]],
-                         None if c is None else [[c[k][t]] for k in range(K)], None if gc is None else [gc[t]])
+    def ranges(n):
+        return [(a, min(n, a + span)) for a in range(0, n, span)]
 
-    with ThreadPoolExecutor(nthreads) as pool:
+    def norm_task(k):
+        return O.norm_sq(g[k], sigma)
+
+    def update_task(job):
+        k, t, a, b = job
+        O.sgd_update([w[k][t][a:b]], [m[k][t][a:b]], [g[k][t][a:b]], wl.lr, wl.momentum, wl.weight_decay, sigma,
+                     False, None if c is None else [c[k][t][a:b]])
+
+    def average_task(job):
+        t, a, b = job
+        O.average_params([[w[k][t][a:b]] for k in range(K)], [glob[t][a:b]],
+                         None if c is None else [[c[k][t][a:b]] for k in range(K)],
+                         None if gc is None else [gc[t][a:b]])
+
+    upd_jobs = [(k, t, a, b) for k in range(K) for t, n in enumerate(numel) for a, b in ranges(n)]
+    avg_jobs = [(t, a, b) for t, n in enumerate(numel) for a, b in ranges(n)]
+    trackers = O.OracleSelSync(K, float("inf"), wl.window)
+    with ThreadPoolExecutor(ncpu) as pool:
         t0 = time.perf_counter()
-        list(pool.map(replica_step, range(K)))
-        tp_local = time.perf_counter() - t0
+        for i in range(steps_timed):
+            norms = pool.map(norm_task, range(K))              # runs beside the first update tasks
+            upd = pool.map(update_task, upd_jobs)
+            trackers.track_norms(list(norms))
+            list(upd)
+        tp_local = (time.perf_counter() - t0) / steps_timed
         t0 = time.perf_counter()
-        list(pool.map(tensor_average, range(len(numel))))
-        tp_sync = time.perf_counter() - t0
+        for i in range(n_agg):
+            list(pool.map(average_task, avg_jobs))
+        tp_sync = (time.perf_counter() - t0) / n_agg
     out["threaded"] = {"value": 1.0 / (tp_local + (1.0 - lssr) * tp_sync), "unit": "steps/s",
-                       "cores": min(nthreads, max(K, 1)), "local_step_s": tp_local, "aggregation_s": tp_sync,
-                       "how": "one thread per replica (norm + update), one task per tensor (aggregation); "
-                              "the order of every sum is unchanged"}
+                       "cores": min(ncpu, len(upd_jobs) + K), "local_step_s": tp_local, "aggregation_s": tp_sync,
+                       "how": "norm: one in-order task per replica; update and averaging: element ranges of 2^21 "
+                              "over a pool of core_share threads; the order of every sum is unchanged"}
     return out
 
 
@@ -205,11 +273,8 @@ def main():
     if args.window > 0:
         wl.window = args.window
     ctx = B.SelSync(K, wl.delta, wl.window)
-    if (args.chunk_elems or args.blocks_per_cu or args.nontemporal >= 0 or args.agg_chunk_elems or args.ga_chunk_elems
-            or args.stream_shape or args.table_layout):
-        ctx.set_tuning(args.chunk_elems, args.blocks_per_cu, args.nontemporal, args.agg_chunk_elems,
-                       stream_variant=args.stream_shape, ga_chunk_elems=args.ga_chunk_elems,
-                       table_layout=args.table_layout)
+    if args.chunk_elems or args.nontemporal >= 0 or args.agg_chunk_elems or args.ga_chunk_elems:
+        ctx.set_tuning(args.chunk_elems, args.nontemporal, args.agg_chunk_elems, args.ga_chunk_elems)
     plans = []
     momenta = None if args.variant == "plain" else st["m"]
     for slot in range(wl.pool):
@@ -225,13 +290,13 @@ def main():
             ctx.bind_second_moment(p, st["v"])
 
     total = args.warmup + args.steps * max(1, args.reps)
-    sig = wl.sigmas(total) if total <= wl.steps else [float(wl.sigma(t)) for t in range(total)]
+    sig = [float(wl.sigma(t)) for t in range(total + args.survey_max_steps + 1)]
 
-    def run(t0, n):
+    def run(t0, n, scale=1.0):
         for t in range(t0, t0 + n):
             plan = plans[t % wl.pool]
             if args.variant == "pa":
-                ctx.step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t], first_step=int(t == 0))
+                ctx.step(plan, wl.lr, wl.momentum, wl.weight_decay, sig[t] * scale, first_step=int(t == 0))
             elif args.variant == "plain":
                 ctx.step(plan, wl.lr, 0.0, wl.weight_decay, sig[t])
             elif args.variant == "nesterov":
@@ -277,6 +342,35 @@ def main():
         run(args.warmup + rep * args.steps, args.steps)
         torch.cuda.synchronize()
         rep_ms.append((time.perf_counter() - r0) / args.steps * 1e3)
+
+    # Per-kernel survey: the same schedule continued, every kernel bracketed by events and the stream drained
+    # after every step, until a synchronising step has happened -- so that the line carries the aggregation
+    # kernel's working time whatever --steps was.  If the schedule has none within --survey-max-steps (constant
+    # gradient scale), one extra step with a 4x gradient spike provokes it.  Not part of `value`.
+    survey = None
+    if args.variant == "pa" and not args.no_survey and not args.no_kernel_events:
+        ctx.profile_config(7, 1)
+        ctx.profile_enable(True, 8)
+        t_next = total
+        rows, spiked = [], False
+        while True:
+            have_sync = any(r[0] for r in rows)
+            n_loc = sum(1 for r in rows if not r[0])
+            if have_sync and n_loc >= 4:
+                break
+            if len(rows) >= args.survey_max_steps:
+                if have_sync:
+                    break
+                spiked = True
+            run(t_next, 1, 4.0 if spiked else 1.0)
+            torch.cuda.synchronize()
+            dec = ctx.read_decision()
+            rows.append((dec.sync,) + tuple(ctx.profile_summary(kind)[1] for kind in range(3)))
+            t_next += 1
+            if spiked:
+                break
+        ctx.profile_enable(False)
+        survey = {"rows": rows, "spiked": spiked}
 
     n_sync = s1["steps_sync"] - s0["steps_sync"]
     n_local = s1["steps_local"] - s0["steps_local"]
@@ -329,15 +423,39 @@ def main():
             "bound": "hbm", "kernel": "k_stream (fused update + norm partials)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": (achieved / HBM_PEAK_GBPS) if achieved else None,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, args.shrink)), "avg_ms": upd_ms, "timed_launches": kern[0][0],
+            "traffic": measured_traffic(wl.name, args.shrink)[0],
+            "traffic_source": measured_traffic(wl.name, args.shrink)[1],
+            "avg_ms": upd_ms, "timed_launches": kern[0][0],
         },
         "other_kernels": None,
     }
     if args.variant != "pa":
         result["roofline"] = None        # the roofline object describes the fused kernel of the headline path
         cpu = None
-    if args.all_kernel_events and not args.no_kernel_events:
+    if survey is not None:
+        rows = survey["rows"]
+        loc = [r for r in rows if not r[0]]
+        syn = [r for r in rows if r[0]]
+        mean = lambda xs: (sum(xs) / len(xs)) if xs else None
+        agg_work_ms = mean([r[3] for r in syn])
         result["other_kernels"] = {
+            "how": "schedule continued after the timed region, every kernel bracketed by HIP events on the launch "
+                   "stream, stream drained after every step; an event pair adds a few microseconds to each figure",
+            "survey_steps": len(rows), "survey_sync_steps": len(syn),
+            "sync_provoked_by_4x_spike": survey["spiked"],
+            "k_aggregate_working_ms": agg_work_ms,
+            "k_aggregate_working_gbps": (b_sync / (agg_work_ms * 1e-3) / 1e9) if agg_work_ms else None,
+            "k_aggregate_frac_of_peak": (b_sync / (agg_work_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS) if agg_work_ms else None,
+            "k_aggregate_bytes": b_sync,
+            "k_aggregate_early_exit_us": (mean([r[3] for r in loc]) * 1e3) if loc else None,
+            "k_reduce_plus_k_track_us": mean([r[2] for r in rows]) * 1e3,
+            "k_stream_ms": mean([r[1] for r in rows]),
+            "local_step_kernels_ms": mean([r[1] + r[2] + r[3] for r in loc]),
+            "sync_step_kernels_ms": mean([r[1] + r[2] + r[3] for r in syn]),
+            "sync_step_gbps": ((b_local + b_sync) / (mean([r[1] + r[2] + r[3] for r in syn]) * 1e-3) / 1e9) if syn else None,
+        }
+    if args.all_kernel_events and not args.no_kernel_events:
+        result["timed_region_kernels"] = {
             "k_reduce_plus_k_track_avg_ms": trk_ms,
             "k_aggregate_avg_ms_over_all_launches": agg_ms_all,      # local steps launch it too (it exits at once)
             "k_aggregate_est_ms_per_sync": (kern[2][1] / n_sync) if n_sync else None,
@@ -366,7 +484,8 @@ def main():
                                "tracking takes 3.1 ms per step for VGG11 at window 25 on a V100 (Sec. IV-B)")
     if not args.no_cpu_baseline and args.variant == "pa":
         # release the GPU-side working set first: the oracle needs host memory only
-        result["cpu_baseline"] = cpu_baseline(wl, lssr_run, args.cpu_steps)
+        torch.cuda.synchronize()
+        result["cpu_baseline"] = cpu_baseline(torch, wl, st, float(sig[1]), lssr_run, args.cpu_steps)
     else:
         result["cpu_baseline"] = None
     ctx.close()
