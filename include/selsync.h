@@ -59,6 +59,7 @@ extern "C" {
 #define SELSYNC_ERR_HIP             5   /* a HIP runtime call failed (see selsync_last_error) */
 #define SELSYNC_ERR_NOT_DEVICE_MEM  6   /* a tensor pointer is not device memory of the context's GPU */
 #define SELSYNC_ERR_STATE           7   /* call not valid for this plan/context (e.g. no gradients bound) */
+#define SELSYNC_ERR_TOO_LARGE       8   /* input beyond the fixed capacity of an allocation-free entry point */
 #define SELSYNC_WARN_NONFINITE    100   /* blocking read saw a non-finite ||g||^2; results are still written */
 
 /* ---- element types --------------------------------------------------------- */
@@ -324,6 +325,35 @@ int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sg
 int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
                         int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                         int32_t *sync_out);
+
+/* ---- for callers that cannot allocate ------------------------------------------------------ */
+
+/*
+ * For callers that cannot call hipMalloc -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation: the squared gradient norms of selsync_track_grad_change,
+ *     x_k = || fl32(grad_scale * g_k) ||^2   over every tensor of worker k, fp64 accumulation,
+ * with NO context, NO plan and NO allocation of any kind (no hipMalloc/hipFree, no memset, no
+ * copy: kernel launches on `stream` only).  The per-piece partial sums live in a fixed 8 MiB
+ * array in the library's device image, one copy per GPU, kept until the process ends.
+ *
+ *   grads        HOST array of num_workers lists (HOST descriptors, read during the call only) of
+ *                DEVICE tensors on the current GPU; every list the same count and per-tensor numel,
+ *                all tensors F32 or all BF16; element alignment suffices (16-byte aligned fp32 /
+ *                8-byte aligned bf16 tensors take 128-/64-bit loads).  Each tensor must lie inside
+ *                one device allocation (checked).
+ *   norm_sq_out  DEVICE array of num_workers doubles, written by the last kernel on `stream`.
+ *
+ * Limits: num_workers <= 64 and, over all workers, sum of ceil(numel / 4096) <= 1,048,576 pieces
+ * (4.29e9 elements when tensors are large); beyond either SELSYNC_ERR_TOO_LARGE is returned and
+ * nothing is enqueued.  Other errors: INVALID_ARG, SHAPE_MISMATCH, DTYPE, NOT_DEVICE_MEM, HIP.
+ * The result is deterministic (fixed slot per piece, fixed order of every sum) and differs from
+ * selsync_track_grad_change's norm only by the grouping of the fp64 sum (about 1e-15 relative).
+ * All calls on one GPU share the array: calls that may overlap in time on one GPU (different
+ * streams, different threads) race and must be serialised by the caller.  Nothing in the array
+ * needs clearing between calls (a call writes every slot it reads).
+ */
+int32_t selsync_grad_norm_sq_noalloc(const selsync_tensor_list *grads, int32_t num_workers, float grad_scale,
+                                     double *norm_sq_out, void *stream);
 
 /* ---- data partitioning (Sec. III-D; the step before the hot path, Alg. 1 line 6) ------------ */
 

@@ -36,6 +36,7 @@ SELSYNC_ERR_OOM = 4
 SELSYNC_ERR_HIP = 5
 SELSYNC_ERR_NOT_DEVICE_MEM = 6
 SELSYNC_ERR_STATE = 7
+SELSYNC_ERR_TOO_LARGE = 8
 SELSYNC_WARN_NONFINITE = 100
 SELSYNC_F32 = 0
 SELSYNC_BF16 = 1
@@ -106,6 +107,7 @@ PROTOTYPES = {
     "selsync_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_ga_update": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _i32, _vp]),
     "selsync_step_ga": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_grad_norm_sq_noalloc": (_i32, [_tl, _i32, ctypes.c_float, _vp, _vp]),
     "selsync_partition_order": (_i32, [ctypes.c_int64, _i32, _i32, _i32, ctypes.c_int64,
                                        ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
     "selsync_partition_order_device": (_i32, [ctypes.c_int64, _i32, _i32, _i32, ctypes.c_int64, _vp,
@@ -180,6 +182,18 @@ def _marshal_lists(lists: Optional[Sequence[Sequence[torch.Tensor]]]):
         keep.append(list(tl))
     keep.append(arr)
     return arr, keep
+
+
+def grad_norm_sq_noalloc(grads: Sequence[Sequence[torch.Tensor]], out: torch.Tensor, grad_scale: float = 1.0,
+                         stream=None) -> None:
+    """||grad_scale * g_k||^2 for every worker k into the float64 CUDA tensor `out` (one element per
+    worker), through the entry point that allocates nothing (no context, no plan).  Asynchronous."""
+    if out.dtype != torch.float64 or not out.is_cuda or not out.is_contiguous() or out.numel() != len(grads):
+        raise ValueError("out must be a contiguous float64 CUDA tensor with one element per worker")
+    arr, keep = _marshal_lists(grads)
+    rc = selsync_grad_norm_sq_noalloc(arr, len(grads), grad_scale, _vp(out.data_ptr()), _vp(_stream_handle(stream)))
+    if rc != SELSYNC_OK:
+        raise SelSyncError(rc, "selsync_grad_norm_sq_noalloc")
 
 
 def partition_order(num_samples: int, num_workers: int, worker: int, seldp: bool = True) -> List[int]:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libselsync.so")
-SOURCES = ["selsync_host.hip", "selsync_kernels.hip"]
+SOURCES = ["selsync_host.hip", "selsync_kernels.hip", "selsync_noalloc.hip"]
 HEADERS = ["selsync_internal.h", os.path.join("..", "..", "include", "selsync.h")]
 
 HIPCC_FLAGS = [

@@ -419,6 +419,7 @@ extern "C" const char *selsync_status_string(int32_t status)
     case SELSYNC_ERR_HIP: return "SELSYNC_ERR_HIP";
     case SELSYNC_ERR_NOT_DEVICE_MEM: return "SELSYNC_ERR_NOT_DEVICE_MEM";
     case SELSYNC_ERR_STATE: return "SELSYNC_ERR_STATE";
+    case SELSYNC_ERR_TOO_LARGE: return "SELSYNC_ERR_TOO_LARGE";
     case SELSYNC_WARN_NONFINITE: return "SELSYNC_WARN_NONFINITE";
     default: return "SELSYNC_UNKNOWN_STATUS";
     }
