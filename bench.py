@@ -290,7 +290,7 @@ def main():
             ctx.bind_second_moment(p, st["v"])
 
     total = args.warmup + args.steps * max(1, args.reps)
-    sig = [float(wl.sigma(t)) for t in range(total + args.survey_max_steps + 1)]
+    sig = [float(wl.sigma(t)) for t in range(total + args.survey_max_steps + 4)]
 
     def run(t0, n, scale=1.0):
         for t in range(t0, t0 + n):
@@ -348,7 +348,7 @@ def main():
     # kernel's working time whatever --steps was.  If the schedule has none within --survey-max-steps (constant
     # gradient scale), one extra step with a 4x gradient spike provokes it.  Not part of `value`.
     survey = None
-    if args.variant == "pa" and not args.no_survey and not args.no_kernel_events:
+    if args.variant == "pa" and not args.no_survey and not args.no_kernel_events and wl.delta > 0.0:
         ctx.profile_config(7, 1)
         ctx.profile_enable(True, 8)
         t_next = total
@@ -386,15 +386,22 @@ def main():
             torch.cuda.synchronize()
             return (time.perf_counter() - r0) / n * 1e3
 
-        # the survey ends on a local step unless the spike was needed: take the early-exit figure first
+        # the decision of the survey's last step stands on the device: measure under it, then take one more
+        # step that flips it (a 4x spike after a local step, an ordinary step after a synchronising one)
         agg_exit_ms = agg_work_ms = None
-        if not rows[-1][0]:
-            agg_exit_ms = repeat_aggregation(plans[0], 200)
-        # then one more synchronising step (the schedule's next spike may be far: provoke it) for the working figure
-        run(t_next, 1, 4.0)
-        torch.cuda.synchronize()
-        if ctx.read_decision().sync:
-            agg_work_ms = repeat_aggregation(plans[0], 20)
+        for attempt in range(2):
+            if ctx.read_decision().sync:
+                if agg_work_ms is None:
+                    agg_work_ms = repeat_aggregation(plans[0], 20)
+                flip = 1.0
+            else:
+                if agg_exit_ms is None:
+                    agg_exit_ms = repeat_aggregation(plans[0], 200)
+                flip = 4.0
+            if attempt == 0:
+                run(t_next, 1, flip)
+                t_next += 1
+                torch.cuda.synchronize()
         survey = {"rows": rows, "spiked": spiked, "agg_exit_ms": agg_exit_ms, "agg_work_ms": agg_work_ms}
 
     n_sync = s1["steps_sync"] - s0["steps_sync"]
@@ -402,6 +409,11 @@ def main():
     assert n_sync + n_local == args.steps
     lssr_run = n_local / args.steps
     b_local, b_sync = algorithmic_bytes(wl, P)
+    # Under a threshold of 0 every step is known to synchronise before it starts, so the minimum is one pass:
+    # each worker's g, w, m read, m written, and the mean written to every replica and the global model.
+    one_pass = args.variant == "pa" and wl.delta == 0.0
+    if one_pass:
+        b_sync = (6 if wl.mixed_bf16 else 4) * P
     if args.variant == "ga":
         # the decision must precede the update, so the gradients are read twice; no parameter exchange
         b_local, b_sync = b_local + K * (2 if wl.mixed_bf16 else 4) * P, 0
@@ -416,7 +428,8 @@ def main():
     upd_ms = kern[0][1] / max(1, kern[0][0])
     trk_ms = kern[1][1] / max(1, kern[1][0])
     agg_ms_all = kern[2][1] / max(1, kern[2][0])          # includes the early-exit launches of local steps
-    achieved = b_local / (upd_ms * 1e-3) / 1e9 if kern[0][0] else None
+    b_kernel = b_local + (b_sync if one_pass else 0)
+    achieved = b_kernel / (upd_ms * 1e-3) / 1e9 if kern[0][0] else None
     result = {
         "metric": "SelSync steps/s (one GPU, K replicas in HBM)" + ("" if args.variant == "pa" else
                                                                        " [variant: %s]" % args.variant),
@@ -445,11 +458,13 @@ def main():
         "bytes_per_local_step": b_local,
         "extra_bytes_per_sync_step": b_sync,
         "roofline": {
-            "bound": "hbm", "kernel": "k_stream (fused update + norm partials)",
+            "bound": "hbm", "kernel": ("k_sync_step (norm partials + update + mean of the replicas in one pass)" if one_pass
+                                       else "k_stream (fused update + norm partials)"),
+            "algorithmic_bytes_per_launch": b_kernel,
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": (achieved / HBM_PEAK_GBPS) if achieved else None,
-            "traffic": measured_traffic(wl.name, args.shrink)[0],
-            "traffic_source": measured_traffic(wl.name, args.shrink)[1],
+            "traffic": None if one_pass else measured_traffic(wl.name, args.shrink)[0],
+            "traffic_source": None if one_pass else measured_traffic(wl.name, args.shrink)[1],
             "avg_ms": upd_ms, "timed_launches": kern[0][0],
         },
         "other_kernels": None,

@@ -281,10 +281,30 @@ int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan, int32_t m
  * into ONE pass over the gradients (g is read once), then the predicated aggregation.
  * Results are identical to selsync_track_grad_change + selsync_local_step +
  * selsync_aggregate_params(mode 0) in that order.  Outputs as for tracking.
+ * When the context's threshold is 0 (every step synchronises) and `stream` is not being captured
+ * into a HIP graph, the call runs selsync_step_bsp's single pass instead: same results, fewer bytes.
  */
 int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
                      int32_t blocking, double *norm_sq_out, double *delta_out,
                      int32_t *flags_out, int32_t *sync_out);
+
+/*
+ * One fully synchronous iteration in a single pass over the data (Sec. III-B: a threshold of 0
+ * turns SelSync into BSP, every step synchronises): every worker's ||grad_scale*g_k||^2, every
+ * worker's local update (Alg. 1 line 9) and the mean of the UPDATED parameters written to the
+ * global model and to all K replicas (Alg. 1 lines 14-15) -- 20*K + 4 bytes per parameter instead of
+ * the 28*K + 4 of selsync_step's update pass plus aggregation pass.  The aggregation is
+ * UNCONDITIONAL: it does not wait for, or depend on, the tracker's decision.  The tracker still runs
+ * afterwards on this pass's norms (window, Delta, flags, counters under the context's threshold), so
+ * with a threshold of 0 the call is selsync_step exactly: the same bits in every tensor, and the same
+ * bits in the norms when the buffers of each tensor share their address modulo 1 KiB (another
+ * placement regroups the fp64 sum, about 1e-16 relative).  selsync_step itself takes this path when
+ * the context's threshold is 0 and `stream` is not being captured.  SGD forms only (momentum,
+ * Nesterov, momentum-free plans); outputs as for selsync_track_grad_change.
+ */
+int32_t selsync_step_bsp(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
+                         int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                         int32_t *sync_out);
 
 /* ---- variant: Adam local update (Sec. IV-A, AlexNet recipe) ---------------------------------- */
 

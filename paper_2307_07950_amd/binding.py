@@ -102,6 +102,7 @@ PROTOTYPES = {
     "selsync_local_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp]),
     "selsync_aggregate_params": (_i32, [_vp, _vp, _i32, _vp]),
     "selsync_step": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_step_bsp": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_plan_bind_second_moment": (_i32, [_vp, _tl]),
     "selsync_local_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp]),
     "selsync_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
@@ -339,6 +340,16 @@ class SelSync:
         n, d, f, s = self._outs()
         rc = self._check(selsync_step(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
                                       int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
+        return self._decision(rc, n, d, f, s) if blocking else None
+
+    def step_bsp(self, plan: Plan, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                 grad_scale: float = 1.0, first_step: int = -1, blocking: bool = False, stream=None,
+                 nesterov: bool = False):
+        """One fully synchronous iteration in a single pass: update, tracking and unconditional aggregation."""
+        sgd = selsync_sgd(lr, momentum, weight_decay, grad_scale, first_step, int(nesterov))
+        n, d, f, s = self._outs()
+        rc = self._check(selsync_step_bsp(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
+                                          int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
         return self._decision(rc, n, d, f, s) if blocking else None
 
     # -- variant: Adam local update

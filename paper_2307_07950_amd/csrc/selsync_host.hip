@@ -86,6 +86,15 @@ struct selsync_plan {
     int32_t *d_tensor_chunk_begin = nullptr;
     double *d_tensor_norms = nullptr;
     bool partials_valid = false;     // a tracking pass has been enqueued on this plan
+    bool partials_from_sync = false; // ... and the last one was the one-pass synchronous step (its own partial array)
+    // one-pass synchronous step: partial sums indexed k * n_agg_fine + piece, and their reduction tables
+    double *d_sync_partials = nullptr;
+    int32_t *d_sync_begin = nullptr;         // [K+1] worker k's partials
+    int n_sync_segs = 0;
+    int2 *d_sync_segs = nullptr;
+    double *d_sync_seg_sums = nullptr;
+    int32_t *d_sync_seg_begin = nullptr;     // [K+1]
+    int32_t *d_sync_tensor_begin = nullptr;  // [K*T+1] partial range of every (worker, tensor) pair
     std::vector<TensorRec> h_recs;   // host copy (re-uploaded when second-moment buffers are bound)
     std::vector<int64_t> numel;      // per-tensor element counts
     std::vector<Interval> ivals;     // every bound buffer (checked again when more buffers are bound)
@@ -369,12 +378,24 @@ int32_t resolve_sgd(selsync_ctx *ctx, const selsync_plan *plan, const selsync_sg
 }
 
 // a1 final passes + a2: (optional) segment reduction, then the single-workgroup tracker.
-int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s)
+int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s, bool from_sync = false)
 {
     plan->partials_valid = true;
+    plan->partials_from_sync = from_sync;
     ctx->tracked = true;
     ctx->tracked_delta = ctx->cfg.delta;
     ProfScope p(ctx, 1, s);
+    if (from_sync) {
+        // partials of the one-pass synchronous step: a plain array, worker k's at [k * pieces, (k+1) * pieces)
+        if (plan->n_sync_segs > 0) {
+            HIP_TRY(ctx, launch_reduce(plan->d_sync_partials, 0, plan->d_sync_segs, plan->n_sync_segs,
+                                       plan->d_sync_seg_sums, s));
+            HIP_TRY(ctx, launch_track(ctx->td, plan->d_sync_seg_sums, 0, plan->d_sync_seg_begin, s));
+        } else {
+            HIP_TRY(ctx, launch_track(ctx->td, plan->d_sync_partials, 0, plan->d_sync_begin, s));
+        }
+        return SELSYNC_OK;
+    }
     if (plan->n_segs > 0) {
         HIP_TRY(ctx, launch_reduce(plan->tab.partials, plan->tab.per, plan->d_segs, plan->n_segs, plan->d_seg_sums, s));
         HIP_TRY(ctx, launch_track(ctx->td, plan->d_seg_sums, 0, plan->d_seg_begin, s));
@@ -752,13 +773,15 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             }
             al = al && stream_phase(agg_w[(size_t)t * K + k], 4) == ph;
         }
-        bool al_grads = momenta != nullptr;
-        if (momenta) {
+        bool al_grads = grads != nullptr;
+        if (grads) {
             for (int k = 0; k < K; ++k) {
                 agg_grad[(size_t)t * K + k] = grads[k].tensors[t].data;
-                agg_m[(size_t)t * K + k] = static_cast<float *>(momenta[k].tensors[t].data);
-                al_grads = al_grads && stream_phase(agg_grad[(size_t)t * K + k], mixed ? 2 : 4) == ph &&
-                           stream_phase(agg_m[(size_t)t * K + k], 4) == ph;
+                al_grads = al_grads && stream_phase(agg_grad[(size_t)t * K + k], mixed ? 2 : 4) == ph;
+                if (momenta) {
+                    agg_m[(size_t)t * K + k] = static_cast<float *>(momenta[k].tensors[t].data);
+                    al_grads = al_grads && stream_phase(agg_m[(size_t)t * K + k], 4) == ph;
+                }
             }
         }
         if (mixed) {
@@ -787,11 +810,11 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             c.off = (uint64_t)off;
             agg_fine.push_back(c);
         });
-        if (momenta) {
+        if (grads) {
             refs.clear();
             for (int k = 0; k < K; ++k) {
                 refs.push_back({agg_w[(size_t)t * K + k], 4, 8});
-                refs.push_back({agg_m[(size_t)t * K + k], 4, 8});
+                refs.push_back({momenta ? agg_m[(size_t)t * K + k] : nullptr, 4, 8});
                 refs.push_back({agg_grad[(size_t)t * K + k], mixed ? 2 : 4, mixed ? 2 : 4});
             }
             split_tensor(numel[t], ga_chunk, vote_lead(refs, ga_chunk), [&](int64_t off, int64_t n, int64_t j) {
@@ -805,8 +828,40 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
         }
     }
     if (agg_chunks.size() > (size_t)INT32_MAX || agg_fine.size() > (size_t)INT32_MAX ||
-        ga_chunks.size() > (size_t)INT32_MAX)
+        ga_chunks.size() > (size_t)INT32_MAX || (grads && agg_fine.size() * (size_t)K > (size_t)INT32_MAX))
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan");
+
+    // Partial sums of the one-pass synchronous step: worker k's sit at [k * np, (k+1) * np), piece order.
+    // Same two-level scheme as for the streaming kernel: fixed segments of kSegChunks partials that never
+    // cross a worker boundary once there are many.
+    const int np = (int)agg_fine.size();
+    std::vector<int32_t> sync_begin(K + 1, 0), sync_seg_begin(K + 1, 0), sync_tensor_begin((size_t)K * T + 1, 0);
+    std::vector<int2> sync_segs;
+    if (grads) {
+        std::vector<int32_t> fine_begin(T + 1, 0);        // first piece of every tensor
+        {
+            int t_prev = 0;
+            for (int i = 0; i < np; ++i)
+                for (; t_prev <= (int)agg_fine[i].t; ++t_prev)
+                    fine_begin[t_prev] = i;
+            for (; t_prev <= T; ++t_prev)
+                fine_begin[t_prev] = np;
+        }
+        for (int k = 0; k <= K; ++k)
+            sync_begin[k] = k * np;
+        for (int k = 0; k < K; ++k)
+            for (int t = 0; t < T; ++t)
+                sync_tensor_begin[(size_t)k * T + t] = k * np + fine_begin[t];
+        sync_tensor_begin[(size_t)K * T] = K * np;
+        if ((size_t)K * np > (size_t)kDirectChunkLimit) {
+            for (int k = 0; k < K; ++k) {
+                sync_seg_begin[k] = (int32_t)sync_segs.size();
+                for (int32_t b0 = k * np; b0 < (k + 1) * np; b0 += kSegChunks)
+                    sync_segs.push_back(make_int2(b0, std::min<int32_t>(b0 + kSegChunks, (k + 1) * np)));
+            }
+            sync_seg_begin[K] = (int32_t)sync_segs.size();
+        }
+    }
 
     std::unique_ptr<selsync_plan> plan(new selsync_plan());     // frees its device tables on any early exit
     plan->ctx = ctx;
@@ -847,6 +902,12 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
     const size_t o_aggf = take(agg_fine.size() * sizeof(AggChunkRec));
     const size_t o_gac = take(ga_chunks.size() * sizeof(AggChunkRec));
+    const size_t o_spart = take(grads ? (size_t)K * np * sizeof(double) : 0);
+    const size_t o_sbegin = take(sync_begin.size() * sizeof(int32_t));
+    const size_t o_ssegs = take(sync_segs.size() * sizeof(int2));
+    const size_t o_ssegsum = take(sync_segs.size() * sizeof(double));
+    const size_t o_ssegbegin = take(sync_seg_begin.size() * sizeof(int32_t));
+    const size_t o_stb = take(sync_tensor_begin.size() * sizeof(int32_t));
     const size_t o_aw = take(agg_w.size() * sizeof(float *));
     const size_t o_ac = take(agg_c.size() * sizeof(uint16_t *));
     const size_t o_ag = take(agg_g.size() * sizeof(float *));
@@ -868,6 +929,10 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
     put(o_aggf, agg_fine.data(), agg_fine.size() * sizeof(AggChunkRec));
     put(o_gac, ga_chunks.data(), ga_chunks.size() * sizeof(AggChunkRec));
+    put(o_sbegin, sync_begin.data(), sync_begin.size() * sizeof(int32_t));
+    put(o_ssegs, sync_segs.data(), sync_segs.size() * sizeof(int2));
+    put(o_ssegbegin, sync_seg_begin.data(), sync_seg_begin.size() * sizeof(int32_t));
+    put(o_stb, sync_tensor_begin.data(), sync_tensor_begin.size() * sizeof(int32_t));
     put(o_aw, agg_w.data(), agg_w.size() * sizeof(float *));
     put(o_ac, agg_c.data(), agg_c.size() * sizeof(uint16_t *));
     put(o_ag, agg_g.data(), agg_g.size() * sizeof(float *));
@@ -902,6 +967,13 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
     plan->d_agg_fine = reinterpret_cast<AggChunkRec *>(b + o_aggf);
     plan->d_ga_chunks = reinterpret_cast<AggChunkRec *>(b + o_gac);
+    plan->d_sync_partials = reinterpret_cast<double *>(b + o_spart);
+    plan->d_sync_begin = reinterpret_cast<int32_t *>(b + o_sbegin);
+    plan->n_sync_segs = (int)sync_segs.size();
+    plan->d_sync_segs = reinterpret_cast<int2 *>(b + o_ssegs);
+    plan->d_sync_seg_sums = reinterpret_cast<double *>(b + o_ssegsum);
+    plan->d_sync_seg_begin = reinterpret_cast<int32_t *>(b + o_ssegbegin);
+    plan->d_sync_tensor_begin = reinterpret_cast<int32_t *>(b + o_stb);
     plan->agg.w = reinterpret_cast<float *const *>(b + o_aw);
     plan->agg.lowp = reinterpret_cast<uint16_t *const *>(b + o_ac);
     plan->agg.global = reinterpret_cast<float *const *>(b + o_ag);
@@ -1050,6 +1122,49 @@ extern "C" int32_t selsync_aggregate_params(selsync_ctx *ctx, selsync_plan *plan
     return SELSYNC_OK;
 }
 
+namespace {
+// One pass: per-worker norm partials + local update + unconditional mean into every replica and the
+// global model, then the tracker over that pass's partials.
+int32_t enqueue_sync_step(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a, hipStream_t s)
+{
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_sync_step(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, plan->agg,
+                                      plan->K, a, plan->d_sync_partials, plan->nontemporal, s));
+    }
+    ctx->local_steps += 1;
+    return enqueue_track(ctx, plan, s, true);
+}
+
+bool stream_is_capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return true;        // unknown: take the path that is right under any later threshold
+    }
+    return st != hipStreamCaptureStatusNone;
+}
+}  // namespace
+
+extern "C" int32_t selsync_step_bsp(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
+                                    int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                                    int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true);
+    if (rc)
+        return rc;
+    SgdArgs a;
+    if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((rc = enqueue_sync_step(ctx, plan, a, s)))
+        return rc;
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
 extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
                                 int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                                 int32_t *sync_out)
@@ -1061,6 +1176,16 @@ extern "C" int32_t selsync_step(selsync_ctx *ctx, selsync_plan *plan, const sels
     if ((rc = resolve_sgd(ctx, plan, sgd, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // Under a threshold of 0 every step synchronises (Delta >= 0 always holds): the one-pass kernel gives
+    // the same tensors and decisions with 20K+4 instead of 28K+4 bytes per parameter.  Not while the
+    // stream is being captured: a recorded launch must stay right if the threshold changes before a replay.
+    if (ctx->cfg.delta == 0.0 && !stream_is_capturing(s)) {
+        if ((rc = enqueue_sync_step(ctx, plan, a, s)))
+            return rc;
+        if (blocking)
+            return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+        return SELSYNC_OK;
+    }
     {
         ProfScope p(ctx, 0, s);
         HIP_TRY(ctx, launch_stream(kUpdateAndNorm, plan->mixed, plan->tab, a, plan->nontemporal, s));
@@ -1349,8 +1474,11 @@ extern "C" int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *pla
     if (n == 0)
         return SELSYNC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(ctx, launch_tensor_norms(plan->tab.partials, plan->tab.per, plan->d_tensor_chunk_begin, n,
-                                     plan->d_tensor_norms, s));
+    if (plan->partials_from_sync)
+        HIP_TRY(ctx, launch_tensor_norms(plan->d_sync_partials, 0, plan->d_sync_tensor_begin, n, plan->d_tensor_norms, s));
+    else
+        HIP_TRY(ctx, launch_tensor_norms(plan->tab.partials, plan->tab.per, plan->d_tensor_chunk_begin, n,
+                                         plan->d_tensor_norms, s));
     HIP_TRY(ctx, hipMemcpyAsync(out, plan->d_tensor_norms, sizeof(double) * n, hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
     return SELSYNC_OK;

@@ -57,7 +57,7 @@ struct AggChunkRec {
 // (element index mod 4 of its address relative to 16-byte alignment; bf16 streams relative to
 // 8-byte alignment), so after peeling head = (4 - p) % 4 elements all streams are vector-aligned.
 constexpr uint32_t kChunkAligned = 0x80000000u;
-constexpr uint32_t kChunkAlignedGrads = 0x40000000u;   // aggregation chunks: gradients and momenta share the phase too
+constexpr uint32_t kChunkAlignedGrads = 0x40000000u;   // aggregation chunks: gradients (and momenta, if bound) share the phase too
 constexpr uint32_t kChunkHeadShift = 28;               // bits 28..29: head element count
 constexpr uint32_t kChunkCountMask = 0x0fffffffu;
 
@@ -68,7 +68,7 @@ struct AggTables {
     float *const *global;      // [T]
     uint16_t *const *glowp;    // [T]    (mixed only)
     const void *const *g;      // [T*K]  gradients (only when the plan has gradients)
-    float *const *m;           // [T*K]  momentum buffers (only when the plan has gradients)
+    float *const *m;           // [T*K]  momentum buffers (only when the plan has them)
 };
 
 // Results of the last step plus the cumulative counters; one contiguous block so a
@@ -195,6 +195,12 @@ hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32
 hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
                             int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal,
                             hipStream_t s);
+
+// One whole synchronous iteration in one pass over 256-element pieces of all K workers: per-worker
+// squared-gradient partials (partials[k * npieces + piece]), local update, mean of the updated
+// parameters into every replica and the global model.
+hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggChunkRec *pieces, int npieces, const AggTables &tabs,
+                            int K, const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s);
 
 // out[p] = partition_index(D, N, n, scheme, p) for p < count (device array).
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

@@ -1001,6 +1001,234 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
     }
 }
 
+// ---------------------------------------------------------------- k_sync_step
+
+// A whole fully synchronous iteration in ONE pass (a threshold of 0 turns SelSync into BSP,
+// Sec. III-B): for one 256-element piece of one tensor across all K workers, a single
+// wavefront reads every worker's g, w, m once, accumulates each worker's squared scaled
+// gradient (Alg. 1 line 8), applies each worker's local update (line 9), forms the mean of
+// the updated parameters in fp64 in worker order (lines 14-15) and writes it to every
+// replica and the global model, and each worker's new momentum to its buffer:
+// 20*K + 4 bytes per parameter instead of the 28*K + 4 of update pass + aggregation pass.
+// Arithmetic, rounding sequence and sum orders are those of k_stream and k_aggregate, so
+// the tensors are bit-identical to the two-pass sequence.  Per (worker, piece) it leaves one
+// fp64 partial at partials[k * npieces + piece], formed in the order k_stream uses for a
+// chunk (vector body, peeled head, ragged tail; DPP wavefront sum).
+template <class OPT, int KC, bool MIXED, bool NT>
+__global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict__ chunks, int npieces, AggTables tabs,
+                                                  int K, double invK, int pow2, typename OPT::Args a,
+                                                  double *__restrict__ partials)
+{
+    constexpr int KM = KC > 0 ? KC : 1;
+    const uint32_t tid = threadIdx.x;
+    const int piece = blockIdx.x;
+    const AggChunkRec ch = chunks[piece];
+    const uint32_t n = ch.n_flags & kChunkCountMask;
+    const size_t row = (size_t)ch.t * K;
+    SELSYNC_GLOBAL float *gl = as_global<float>(tabs.global[ch.t]);
+    SELSYNC_GLOBAL uint16_t *glc = MIXED ? as_global<uint16_t>(tabs.glowp[ch.t]) : nullptr;
+    const bool vec = (ch.n_flags & kChunkAligned) && (ch.n_flags & kChunkAlignedGrads);
+    const uint32_t head = vec ? chunk_head(ch.n_flags, n) : 0u;
+    const uint32_t nvec = vec ? (n - head) / 4 : 0u;          // <= 64: a piece holds at most 256 elements
+    const uint64_t e0 = ch.off + head;
+    const bool lane_vec = tid < nvec;
+
+    if constexpr (KC > 0) {
+        double acc[KM];
+        f32x4 gv[KM], wv[KM], mv[KM], unused = 0.f;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            acc[k] = 0.0;
+            gv[k] = 0.f;
+            wv[k] = 0.f;
+            mv[k] = 0.f;
+            if (lane_vec) {
+                if (MIXED)
+                    gv[k] = widen4(ld<NT>(as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + e0) + tid));
+                else
+                    gv[k] = ld<NT>(as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + e0) + tid);
+                wv[k] = ld<NT>(as_global<const f32x4>(tabs.w[row + k] + e0) + tid);
+                if (OPT::kMomentum && !a.first)
+                    mv[k] = ld<NT>(as_global<const f32x4>(tabs.m[row + k] + e0) + tid);
+            }
+        }
+        if (lane_vec) {
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                elem4<OPT, true, true>(gv[k], wv[k], mv[k], unused, a, acc[k]);
+                s0 += (double)wv[k].x;
+                s1 += (double)wv[k].y;
+                s2 += (double)wv[k].z;
+                s3 += (double)wv[k].w;
+                if (OPT::kMomentum)
+                    st<NT>(as_global<f32x4>(tabs.m[row + k] + e0) + tid, mv[k]);
+            }
+            f32x4 r;
+            r.x = finish_mean(s0, KC, invK, pow2);
+            r.y = finish_mean(s1, KC, invK, pow2);
+            r.z = finish_mean(s2, KC, invK, pow2);
+            r.w = finish_mean(s3, KC, invK, pow2);
+            u32x2 h;
+            if (MIXED) {
+                h.x = bf16_pack(r.x, r.y);
+                h.y = bf16_pack(r.z, r.w);
+            }
+            st<NT>((SELSYNC_GLOBAL f32x4 *)(gl + e0) + tid, r);
+            if (MIXED)
+                st<NT>((SELSYNC_GLOBAL u32x2 *)(glc + e0) + tid, h);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                st<NT>(as_global<f32x4>(tabs.w[row + k] + e0) + tid, r);
+                if (MIXED)
+                    st<NT>(as_global<u32x2>(tabs.lowp[row + k] + e0) + tid, h);
+            }
+        }
+        // peeled head, then ragged tail (all of the piece when its streams are not vector-aligned together);
+        // lane i takes element begin + i of either range, as in k_stream, so the partial sums group alike
+        auto scalar_elem = [&](uint64_t e) {
+            double s = 0.0;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float g;
+                if (MIXED)
+                    g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
+                else
+                    g = as_global<const float>(tabs.g[row + k])[e];
+                float w = as_global<const float>(tabs.w[row + k])[e];
+                float m = 0.f, v = 0.f;
+                if (OPT::kMomentum && !a.first)
+                    m = as_global<const float>(tabs.m[row + k])[e];
+                OPT::template elem<true, true>(g, w, m, v, a, acc[k]);
+                s += (double)w;
+                if (OPT::kMomentum)
+                    as_global<float>(tabs.m[row + k])[e] = m;
+            }
+            const float r = finish_mean(s, KC, invK, pow2);
+            const uint16_t h = MIXED ? (uint16_t)bf16_bits(r) : (uint16_t)0;
+            gl[e] = r;
+            if (MIXED)
+                glc[e] = h;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                as_global<float>(tabs.w[row + k])[e] = r;
+                if (MIXED)
+                    as_global<uint16_t>(tabs.lowp[row + k])[e] = h;
+            }
+        };
+        const uint32_t done = nvec * 4;
+        for (uint32_t i = tid; i < head; i += 64)
+            scalar_elem(ch.off + i);
+        for (uint32_t i = head + done + tid; i < n; i += 64)
+            scalar_elem(ch.off + i);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            const double x = wave_sum_to_last_lane(acc[k]);
+            if (tid == 63 && n > 0)
+                partials[(size_t)k * npieces + piece] = x;
+        }
+    } else {
+        // Any other K: the same arithmetic with one worker in registers at a time.  Lane `tid` owns vector
+        // `tid` of the body and elements tid, tid + 64, ... of head and tail; every worker's contribution to
+        // a lane's fp64 sums arrives in worker order.
+        const uint32_t done = nvec * 4;
+        uint32_t nsc = 0;                       // scalar elements of this lane (at most 4: a piece has <= 256)
+        uint64_t se[4];
+        if (tid < head)
+            se[nsc++] = ch.off + tid;
+        for (uint32_t i = head + done + tid; i < n && nsc < 4; i += 64)
+            se[nsc++] = ch.off + i;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        double ss[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int k = 0; k < K; ++k) {
+            double acc = 0.0;
+            if (lane_vec) {
+                f32x4 gv, wv, mv = 0.f, unused = 0.f;
+                if (MIXED)
+                    gv = widen4(ld<NT>(as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + e0) + tid));
+                else
+                    gv = ld<NT>(as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + e0) + tid);
+                wv = ld<NT>(as_global<const f32x4>(tabs.w[row + k] + e0) + tid);
+                if (OPT::kMomentum && !a.first)
+                    mv = ld<NT>(as_global<const f32x4>(tabs.m[row + k] + e0) + tid);
+                elem4<OPT, true, true>(gv, wv, mv, unused, a, acc);
+                s0 += (double)wv.x;
+                s1 += (double)wv.y;
+                s2 += (double)wv.z;
+                s3 += (double)wv.w;
+                if (OPT::kMomentum)
+                    st<NT>(as_global<f32x4>(tabs.m[row + k] + e0) + tid, mv);
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                if (q < nsc) {
+                    const uint64_t e = se[q];
+                    float g;
+                    if (MIXED)
+                        g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
+                    else
+                        g = as_global<const float>(tabs.g[row + k])[e];
+                    float w = as_global<const float>(tabs.w[row + k])[e];
+                    float m = 0.f, v = 0.f;
+                    if (OPT::kMomentum && !a.first)
+                        m = as_global<const float>(tabs.m[row + k])[e];
+                    OPT::template elem<true, true>(g, w, m, v, a, acc);
+                    ss[q] += (double)w;
+                    if (OPT::kMomentum)
+                        as_global<float>(tabs.m[row + k])[e] = m;
+                }
+            }
+            const double x = wave_sum_to_last_lane(acc);
+            if (tid == 63 && n > 0)
+                partials[(size_t)k * npieces + piece] = x;
+        }
+        f32x4 r = 0.f;
+        u32x2 h = 0u;
+        if (lane_vec) {
+            r.x = finish_mean(s0, K, invK, pow2);
+            r.y = finish_mean(s1, K, invK, pow2);
+            r.z = finish_mean(s2, K, invK, pow2);
+            r.w = finish_mean(s3, K, invK, pow2);
+            if (MIXED) {
+                h.x = bf16_pack(r.x, r.y);
+                h.y = bf16_pack(r.z, r.w);
+            }
+            st<NT>((SELSYNC_GLOBAL f32x4 *)(gl + e0) + tid, r);
+            if (MIXED)
+                st<NT>((SELSYNC_GLOBAL u32x2 *)(glc + e0) + tid, h);
+        }
+        float rs[4];
+        uint16_t hs[4];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            rs[q] = 0.f;
+            hs[q] = 0;
+            if (q < nsc) {
+                rs[q] = finish_mean(ss[q], K, invK, pow2);
+                hs[q] = MIXED ? (uint16_t)bf16_bits(rs[q]) : (uint16_t)0;
+                gl[se[q]] = rs[q];
+                if (MIXED)
+                    glc[se[q]] = hs[q];
+            }
+        }
+        for (int k = 0; k < K; ++k) {
+            if (lane_vec) {
+                st<NT>(as_global<f32x4>(tabs.w[row + k] + e0) + tid, r);
+                if (MIXED)
+                    st<NT>(as_global<u32x2>(tabs.lowp[row + k] + e0) + tid, h);
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                if (q < nsc) {
+                    as_global<float>(tabs.w[row + k])[se[q]] = rs[q];
+                    if (MIXED)
+                        as_global<uint16_t>(tabs.lowp[row + k])[se[q]] = hs[q];
+                }
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- dispatch helpers
 
 // Chunks per wavefront of the streaming kernel (measured on the 133M-parameter fp32 workload):
@@ -1108,6 +1336,36 @@ hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, AggShape shape, c
 #undef SELSYNC_GA_CALL
 }
 
+template <class OPT, int KC, bool MIXED, bool NT>
+hipError_t launch_sync_t(const AggChunkRec *pieces, int npieces, const AggTables &tabs, int K, const SgdArgs &sgd,
+                         double *partials, hipStream_t s)
+{
+    const int pow2 = (K & (K - 1)) == 0;
+    hipLaunchKernelGGL((k_sync_step<OPT, KC, MIXED, NT>), dim3(npieces), dim3(64), 0, s, pieces, npieces, tabs, K,
+                       1.0 / (double)K, pow2, sgd, partials);
+    return hipGetLastError();
+}
+
+template <class OPT, bool MIXED, bool NT>
+hipError_t launch_sync_k(const AggChunkRec *pieces, int npieces, const AggTables &tabs, int K, const SgdArgs &sgd,
+                         double *partials, hipStream_t s)
+{
+#define SELSYNC_SYNC_CALL(KC) launch_sync_t<OPT, KC, MIXED, NT>(pieces, npieces, tabs, K, sgd, partials, s)
+    SELSYNC_SWITCH_K(K, SELSYNC_SYNC_CALL)
+#undef SELSYNC_SYNC_CALL
+}
+
+template <class OPT>
+hipError_t launch_sync_o(bool mixed, const AggChunkRec *pieces, int npieces, const AggTables &tabs, int K,
+                         const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s)
+{
+    if (mixed)
+        return nontemporal ? launch_sync_k<OPT, true, true>(pieces, npieces, tabs, K, sgd, partials, s)
+                           : launch_sync_k<OPT, true, false>(pieces, npieces, tabs, K, sgd, partials, s);
+    return nontemporal ? launch_sync_k<OPT, false, true>(pieces, npieces, tabs, K, sgd, partials, s)
+                       : launch_sync_k<OPT, false, false>(pieces, npieces, tabs, K, sgd, partials, s);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launchers
@@ -1173,6 +1431,16 @@ hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, 
                            : launch_ga_k<true, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s);
     return nontemporal ? launch_ga_k<false, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s)
                        : launch_ga_k<false, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s);
+}
+
+hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggChunkRec *pieces, int npieces, const AggTables &tabs,
+                            int K, const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s)
+{
+    if (npieces <= 0)
+        return hipSuccess;
+    if (!has_momentum)
+        return launch_sync_o<PlainSgdOpt>(mixed, pieces, npieces, tabs, K, sgd, partials, nontemporal, s);
+    return launch_sync_o<SgdOpt>(mixed, pieces, npieces, tabs, K, sgd, partials, nontemporal, s);
 }
 
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

@@ -179,6 +179,17 @@ class LockStep:
             dec = self.ctx.track_grad_change(plan, gs, blocking=True)
             self.ctx.local_step(plan, lr, mu, wd, gs, first_step=int(first), nesterov=nesterov)
             self.ctx.aggregate_params(plan, always=False)
+        rec = self._oracle_track_and_update(slot, lr, mu, wd, gs, first, nesterov)
+        sync = self._check_decision(dec, rec)
+        if sync:
+            self._oracle_average()
+        self.steps_done += 1
+        if compare_tensors or sync:          # every aggregation is checked, local steps on request
+            self.compare(after_sync=bool(sync))
+        return dec, rec
+
+    def _oracle_track_and_update(self, slot, lr, mu, wd, gs, first, nesterov):
+        """Oracle side of Alg. 1 lines 8-13 for all K workers: norms, trackers, local updates."""
         g = self.h_grads[slot]
 
         def update(k):
@@ -194,15 +205,27 @@ class LockStep:
             xs = list(self.pool.map(lambda k: O.norm_sq(g[k], gs), range(self.K)))
             rec = self.oracle.track_norms(xs)
             list(self.pool.map(update, range(self.K)))
-        sync = self._check_decision(dec, rec)
-        if sync:
-            pre = [np.max(np.abs(np.stack([self.h_w[k][t] for k in range(self.K)])), axis=0).astype(np.float64)
-                   for t in range(len(self.numel))]
-            O.average_params(self.h_w, self.h_glob, self.h_c, self.h_gc)
-            self._pre_scale = pre
+        return rec
+
+    def _oracle_average(self):
+        """Oracle side of Alg. 1 lines 14-15 (keeps the pre-averaging magnitudes for the relative bar)."""
+        self._pre_scale = [np.max(np.abs(np.stack([self.h_w[k][t] for k in range(self.K)])), axis=0).astype(np.float64)
+                           for t in range(len(self.numel))]
+        O.average_params(self.h_w, self.h_glob, self.h_c, self.h_gc)
+
+    def step_bsp(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, nesterov: bool = False,
+                 compare_tensors: bool = True):
+        """One fully synchronous iteration (update, tracking, UNCONDITIONAL aggregation) on both sides.  The
+        tracker's own decision is still compared: it follows the threshold, the aggregation does not."""
+        first = self.steps_done == 0
+        dec = self.ctx.step_bsp(self.plans[slot], lr, mu, wd, gs, first_step=int(first), blocking=True,
+                                nesterov=nesterov)
+        rec = self._oracle_track_and_update(slot, lr, mu, wd, gs, first, nesterov)
+        self._check_decision(dec, rec)
+        self._oracle_average()
         self.steps_done += 1
-        if compare_tensors or sync:          # every aggregation is checked, local steps on request
-            self.compare(after_sync=bool(sync))
+        if compare_tensors:
+            self.compare(after_sync=True)
         return dec, rec
 
     def enable_adam(self):

@@ -60,6 +60,22 @@ def test_vgg11_like_full_size_all_200_steps():
     ls.close()
 
 
+def test_vgg11_like_full_size_fully_synchronous_steps():
+    """The 133M-parameter configuration at full size under a threshold of 0 (BSP): selsync_step takes the
+    one-pass kernel; three steps, every tensor of every replica compared with the oracle after the last."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2307_07950_amd import binding as B
+    wl = W.get("c4")
+    wl.delta = 0.0
+    ls = PU.run_workload(B, wl, steps=3, compare_every=0, oracle_threads=wl.num_workers, pool=1)
+    assert ls.oracle.steps_sync == 3 and ls.forced == 0
+    assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-10
+    for t in range(len(wl.numels)):
+        assert PU.to_host(ls.d_glob[t]).tobytes() == ls.h_glob[t].tobytes()
+    ls.close()
+
+
 @pytest.mark.parametrize("name,params,tensors,workers", [("c2", 44_541_480, 314, 8), ("c3", 61_100_840, 16, 8),
                                                          ("c5", 61_212_158, 186, 8)])
 def test_other_workloads_full_size_local_step_then_sync(name, params, tensors, workers):

@@ -668,6 +668,96 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed(B):
     graphed.close()
 
 
+# ================================================================= fully synchronous step in one pass
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 8, 17])
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign,misalign_g", [(0, 0), (1, 1), (2, 3)])
+def test_one_pass_synchronous_step_matches_oracle(B, K, mixed, misalign, misalign_g):
+    # update + tracking + unconditional aggregation in one kernel; compile-time K, run-time K (3, 17),
+    # vector path (equal address phases), peeled heads (1, 1) and the element-wise path (2, 3)
+    numel = [70001, 5, 4096, 0, 1023, 255, 257]
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign,
+                     misalign_g=misalign_g, seed=81, tuning=dict(nontemporal=K % 2))
+    r = rng(810 + K)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot) * (1 + 0.1 * k)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    flagged = 0
+    for t in range(7):
+        dec, rec = ls.step_bsp([0, 1, 2, 2, 0, 1, 1][t], 0.05, 0.9, [0.0, 1e-4][t % 2], [1.0, 0.7][t % 2],
+                               nesterov=(t >= 5))
+        flagged += rec.sync
+        for tt in range(len(numel)):         # the averaged model is bit-identical to the oracle's
+            assert PU.to_host(ls.d_glob[tt]).tobytes() == ls.h_glob[tt].tobytes()
+    assert 0 < flagged < 7                   # the tracker still follows its threshold; the aggregation ignores it
+    assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12 and ls.forced == 0
+    got = ls.ctx.read_tensor_norms(ls.plans[1])          # per-tensor norms come from this pass's partials
+    for k in range(K):
+        for t in range(len(numel)):
+            assert got[k][t] == pytest.approx(O.norm_sq([ls.h_grads[1][k][t]], 1.0), rel=1e-12, abs=0.0)
+    st = ls.ctx.stats()
+    assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
+    ls.close()
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+def test_one_pass_synchronous_step_on_momentum_free_plans(B, mixed):
+    numel = [70001, 5, 4096, 0, 1023]
+    K = 4
+    ls = PU.LockStep(B, numel, K, delta=0.0, mixed=mixed, seed=82, momentum_free=True)
+    r = rng(820)
+    for slot in range(2):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    for t in range(5):
+        dec, rec = ls.step_bsp(t % 2, 2.0 * 0.8 ** t, 0.0, [0.0, 1e-4][t % 2], 1.0)
+        assert dec.sync == 1
+    assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+    ls.close()
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+def test_step_at_threshold_zero_takes_the_one_pass_kernel_with_identical_results(B, mixed):
+    """selsync_step under delta = 0 runs the one-pass kernel; the three-call sequence runs the update pass
+    and the aggregation pass.  Same tensors bit for bit, and (buffers of a tensor at equal addresses modulo
+    1 KiB, as here) the same bits in norms and Delta."""
+    numel = [100003, 257, 65536, 4096]
+    K = 4
+    runs = []
+    for fused in (True, False):
+        ls = PU.LockStep(B, numel, K, delta=0.0, alpha=0.5, window=5, mixed=mixed, seed=83)
+        rr = rng(830)
+        for slot in range(3):
+            grads = []
+            for k in range(K):
+                gk = [(rr.standard_normal(n) * (1 + slot) * 1e-2).astype(np.float32) for n in numel]
+                grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+            ls.bind_grads(slot, grads)
+        ls.ctx.profile_enable(True, 64)
+        decs = [ls.step(t % 3, 0.05, 0.9, 1e-4, 1.0, fused=fused)[0] for t in range(6)]
+        launches = [ls.ctx.profile_summary(kind)[0] for kind in range(3)]
+        # one-pass: 6 launches of the streaming kind, none of the aggregation kind; three calls: 12 and 6
+        assert launches == ([6, 6, 0] if fused else [12, 6, 6])
+        state = [[PU.to_host(x).tobytes() for x in ls.d_w[k]] + [PU.to_host(x).tobytes() for x in ls.d_m[k]]
+                 for k in range(K)]
+        runs.append((decs, state, [PU.to_host(x).tobytes() for x in ls.d_glob]))
+        assert ls.oracle.steps_sync == 6 and ls.worst_ulp == 0
+        ls.close()
+    (d1, s1, g1), (d2, s2, g2) = runs
+    assert s1 == s2 and g1 == g2
+    for a, b in zip(d1, d2):
+        assert a.flags == b.flags and a.sync == b.sync == 1
+        assert [x.hex() for x in a.norm_sq] == [x.hex() for x in b.norm_sq]
+        assert [x.hex() for x in a.delta] == [x.hex() for x in b.delta]
+
+
 # ================================================================= data partitioning (Sec. III-D)
 
 @pytest.mark.parametrize("D,N", [(100, 4), (103, 4), (5, 8), (0, 3), (1_000_003, 16)])
@@ -1110,7 +1200,7 @@ def test_empty_model_and_single_worker(B):
 
 
 def test_profile_counters_report_launches(B):
-    ls = PU.LockStep(B, [300000], 2, delta=0.0, seed=16)
+    ls = PU.LockStep(B, [300000], 2, delta=0.3, seed=16)      # (under delta = 0 a step is one kernel, not three)
     ls.bind_grads(0, [[rng(95 + k).standard_normal(300000).astype(np.float32)] for k in range(2)])
     ls.ctx.profile_enable(True, 16)
     for _ in range(4):
