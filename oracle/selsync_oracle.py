@@ -243,22 +243,41 @@ def average_grads(grads: Sequence[Sequence[np.ndarray]], grad_scale: float = 1.0
 
 def ga_update(grads, params, momenta, lr, momentum, weight_decay, grad_scale=1.0, first=False, sync=True,
               copies=None, nesterov=False) -> None:
-    """Update of all K workers under gradient aggregation: on a synchronising step every
-    worker applies the averaged gradient to its own state, otherwise its own gradient."""
-    L = lib()
+    """Update of all K workers under gradient aggregation (Sec. III-C): on a synchronising step every
+    worker applies the averaged gradient to its own state, otherwise its own gradient.  ``momenta=None``
+    is momentum-free SGD.  In mixed precision (``copies`` given) the averaged fp32 gradient acts on the
+    fp32 masters and every bf16 copy is then refreshed by rounding its master."""
     K = len(params)
+    mom = lambda k: None if momenta is None else momenta[k]
     if not sync:
         for k in range(K):
-            sgd_update(params[k], momenta[k], grads[k], lr, momentum, weight_decay, grad_scale, first,
+            sgd_update(params[k], mom(k), grads[k], lr, momentum, weight_decay, grad_scale, first,
                        None if copies is None else copies[k], nesterov=nesterov)
         return
     gbar = average_grads(grads, grad_scale)
     for k in range(K):
-        if copies is None:
-            sgd_update(params[k], momenta[k], gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)
-        else:
-            # fp32 averaged gradient applied to the fp32 masters, then the bf16 copies are refreshed
-            sgd_update(params[k], momenta[k], gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)
+        sgd_update(params[k], mom(k), gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)
+        if copies is not None:
+            for t in range(len(gbar)):
+                copies[k][t][...] = f32_to_bf16(params[k][t])
+
+
+def ga_update_adam(grads, params, m, v, lr, beta1, beta2, eps, weight_decay, step: int, grad_scale=1.0, sync=True,
+                   copies=None) -> None:
+    """Gradient aggregation with Adam as the update (Sec. III-C with the Adam recipe of Sec. IV-A): on a
+    synchronising step every worker feeds the averaged gradient to its OWN Adam state (both moment
+    buffers stay per worker), otherwise its own gradient.  `step` is the 1-based step of the bias
+    corrections, the same for every worker."""
+    K = len(params)
+    if not sync:
+        for k in range(K):
+            adam_update(params[k], m[k], v[k], grads[k], lr, beta1, beta2, eps, weight_decay, step, grad_scale,
+                        None if copies is None else copies[k])
+        return
+    gbar = average_grads(grads, grad_scale)
+    for k in range(K):
+        adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)
+        if copies is not None:
             for t in range(len(gbar)):
                 copies[k][t][...] = f32_to_bf16(params[k][t])
 

@@ -10,7 +10,10 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
-# (name, text in oracle/selsync_oracle.c, replacement)
+C = os.path.join("oracle", "selsync_oracle.c")
+PY = os.path.join("oracle", "selsync_oracle.py")
+
+# (name, text in the oracle source, replacement[, file: the C source unless said otherwise])
 MUT = [
  ("norm float product", "acc += (double)gh * (double)gh;\n    }\n    return acc;\n}\n\ndouble selsync_oracle_norm_sq_accum_bf16", "acc += (double)(gh * gh);\n    }\n    return acc;\n}\n\ndouble selsync_oracle_norm_sq_accum_bf16"),
  ("norm ignores scale", "float gh = grad_scale * g[j];\n        acc +=", "float gh = g[j];\n        acc +="),
@@ -34,6 +37,15 @@ MUT = [
  ("nesterov looks at old buffer", "float look = mu * mom;\n        float dir = d + look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]", "float look = mu * m[j];\n        float dir = d + look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]"),
  ("nesterov drops gradient term", "float dir = d + look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]", "float dir = look;\n        float stepv = lr * dir;\n        m[j] = mom;\n        w[j]"),
  ("nesterov stores direction", "float stepv = lr * dir;\n        m[j] = mom;\n        w[j]", "float stepv = lr * dir;\n        m[j] = dir;\n        w[j]"),
+ ("grad mean drops last worker", "for (int k = 0; k < K; ++k) {\n            float gh = grad_scale * grads[k][j];", "for (int k = 0; k < K - 1; ++k) {\n            float gh = grad_scale * grads[k][j];"),
+ ("grad mean scaled after the sum", "float gh = grad_scale * grads[k][j];\n            s += (double)gh;\n        }\n        gbar[j] = (float)(s / (double)K);", "float gh = grads[k][j];\n            s += (double)gh;\n        }\n        gbar[j] = grad_scale * (float)(s / (double)K);"),
+ # mistakes in the composition of the gradient-aggregation variants (oracle/selsync_oracle.py)
+ ("ga sync applies own gradient", "sgd_update(params[k], mom(k), gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)", "sgd_update(params[k], mom(k), grads[k], lr, momentum, weight_decay, grad_scale, first, nesterov=nesterov)", PY),
+ ("ga scales the mean again", "sgd_update(params[k], mom(k), gbar, lr, momentum, weight_decay, 1.0, first, nesterov=nesterov)", "sgd_update(params[k], mom(k), gbar, lr, momentum, weight_decay, grad_scale, first, nesterov=nesterov)", PY),
+ ("ga leaves stale bf16 copies", "copies[k][t][...] = f32_to_bf16(params[k][t])\n\n\ndef ga_update_adam", "pass\n\n\ndef ga_update_adam", PY),
+ ("ga adam applies own gradient", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)", "adam_update(params[k], m[k], v[k], grads[k], lr, beta1, beta2, eps, weight_decay, step, grad_scale)", PY),
+ ("ga adam scales the mean again", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, grad_scale)", PY),
+ ("ga local step averages anyway", "    if not sync:\n        for k in range(K):\n            sgd_update(", "    if False:\n        for k in range(K):\n            sgd_update(", PY),
 ]
 
 
@@ -57,10 +69,12 @@ def test_unmutated_copy_passes(tree):
     assert rc == 0, out
 
 
-@pytest.mark.parametrize("name,old,new", MUT, ids=[m[0].replace(" ", "_") for m in MUT])
-def test_pins_catch_planted_mistake(tree, name, old, new):
-    path = os.path.join(tree, "oracle", "selsync_oracle.c")
-    good = open(os.path.join(ROOT, "oracle", "selsync_oracle.c")).read()
+@pytest.mark.parametrize("mut", MUT, ids=[m[0].replace(" ", "_") for m in MUT])
+def test_pins_catch_planted_mistake(tree, mut):
+    name, old, new = mut[:3]
+    rel = mut[3] if len(mut) > 3 else C
+    path = os.path.join(tree, rel)
+    good = open(os.path.join(ROOT, rel)).read()
     assert good.count(old) >= 1, "mutation site not found: %s" % name
     try:
         open(path, "w").write(good.replace(old, new, 1))

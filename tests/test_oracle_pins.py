@@ -728,6 +728,14 @@ def test_ga_sync_keeps_replica_offsets_while_pa_removes_them():
     O.ga_update([grads[0]], p2, m2, 0.1, 0.9, 1e-3, sync=False)
     O.sgd_update(p3[0], m3[0], grads[0], 0.1, 0.9, 1e-3)
     assert p2[0][0].tobytes() == p3[0][0].tobytes() and m2[0][0].tobytes() == m3[0][0].tobytes()
+    # ... for every worker, each with its OWN gradient (no averaging on a local step)
+    p4, m4 = [[base.copy()] for _ in range(K)], [[m0.copy()] for _ in range(K)]
+    O.ga_update(grads, p4, m4, 0.1, 0.9, 1e-3, grad_scale=0.5, sync=False)
+    for k in range(K):
+        pk, mk = [base.copy()], [m0.copy()]
+        O.sgd_update(pk, mk, grads[k], 0.1, 0.9, 1e-3, 0.5)
+        assert p4[k][0].tobytes() == pk[0].tobytes() and m4[k][0].tobytes() == mk[0].tobytes()
+    assert p4[0][0].tobytes() != p4[1][0].tobytes()
 
 
 def test_ga_equals_pa_when_every_step_synchronises_from_identical_start():
@@ -752,6 +760,128 @@ def test_ga_equals_pa_when_every_step_synchronises_from_identical_start():
         np.testing.assert_allclose(ga_w[0][0], pa_w[0][0], rtol=0, atol=2e-7)
         np.testing.assert_allclose(ga_m[0][0], np.mean([m[0].astype(np.float64) for m in pa_m], axis=0),
                                    rtol=0, atol=2e-8)
+
+
+def test_ga_momentum_free_closed_form_identity_and_agreement_with_pa():
+    # momentum-free SGD under gradient aggregation: w <- w - lr * (gbar + wd * w), no buffer anywhere
+    K, n = 4, 256
+    r = rng(54)
+    # exactly representable numbers: the closed form holds bit for bit
+    w0 = (r.integers(-64, 64, n) / 8.0).astype(np.float32)
+    grads = [[(r.integers(-32, 32, n) / 4.0).astype(np.float32)] for _ in range(K)]
+    params = [[w0.copy()] for _ in range(K)]
+    O.ga_update(grads, params, None, 0.5, 0.0, 0.25, grad_scale=2.0, sync=True)
+    gbar = 2.0 * np.mean([g[0].astype(np.float64) for g in grads], axis=0)
+    want = (w0 - 0.5 * (gbar + 0.25 * w0)).astype(np.float32)
+    for k in range(K):
+        assert params[k][0].tobytes() == want.tobytes()
+    # identical gradients: aggregation changes nothing, the step is the plain local update
+    same = [[grads[0][0].copy()] for _ in range(K)]
+    p_ga, p_loc = [[w0.copy()] for _ in range(K)], [w0.copy()]
+    O.ga_update(same, p_ga, None, 0.1, 0.0, 1e-3, grad_scale=0.37, sync=True)
+    O.sgd_update(p_loc, None, same[0], 0.1, 0.0, 1e-3, 0.37)
+    assert p_ga[2][0].tobytes() == p_loc[0].tobytes()
+    # sync=False is the per-worker update; replicas that differ stay apart under GA, unlike under PA
+    pa = [[w0.copy()], [w0 + np.float32(0.5)]]
+    ga = [[w0.copy()], [w0 + np.float32(0.5)]]
+    g2 = [[r.standard_normal(n).astype(np.float32)] for _ in range(2)]
+    O.ga_update(g2, ga, None, 0.1, 0.0, 0.0, sync=True)
+    np.testing.assert_allclose(ga[1][0] - ga[0][0], 0.5, rtol=0, atol=1e-6)
+    for k in range(2):
+        O.sgd_update(pa[k], None, g2[k], 0.1, 0.0, 0.0)
+    O.average_params(pa, [np.zeros(n, np.float32)])
+    assert pa[0][0].tobytes() == pa[1][0].tobytes()
+    # from identical replicas, synchronising every step, GA and PA coincide up to rounding (Sec. III-C)
+    ga = [[w0.copy()] for _ in range(K)]
+    pa = [[w0.copy()] for _ in range(K)]
+    for t in range(8):
+        gt = [[(r.standard_normal(n) * 1e-2).astype(np.float32)] for _ in range(K)]
+        O.ga_update(gt, ga, None, 2.0 * 0.8 ** t, 0.0, 1e-4, sync=True)
+        for k in range(K):
+            O.sgd_update(pa[k], None, gt[k], 2.0 * 0.8 ** t, 0.0, 1e-4)
+        O.average_params(pa, [np.zeros(n, np.float32)])
+        np.testing.assert_allclose(ga[0][0], pa[0][0], rtol=0, atol=2e-6)
+
+
+def test_ga_mixed_precision_masters_follow_the_fp32_path_and_copies_are_their_roundings():
+    # bf16 gradients: the mean is that of the exactly widened values; the masters take the fp32 update;
+    # every bf16 copy is the nearest-even rounding of its master (checked with torch's own conversion)
+    torch = pytest.importorskip("torch")
+    K, n = 3, 400
+    r = rng(55)
+    g32 = [[(r.standard_normal(n) * 1e-2).astype(np.float32)] for _ in range(K)]
+    gb = [[O.f32_to_bf16(g[0])] for g in g32]
+    wide = [[(b[0].astype(np.uint32) << 16).view(np.float32).copy()] for b in gb]
+    w0 = [(r.standard_normal(n) * 0.05).astype(np.float32) + np.float32(0.01 * k) for k in range(K)]
+    m0 = (r.standard_normal(n) * 1e-3).astype(np.float32)
+    for mom_free in (False, True):
+        for sync in (True, False):
+            mx = [[w.copy()] for w in w0]
+            mm = None if mom_free else [[m0.copy()] for _ in range(K)]
+            cp = [[np.zeros(n, np.uint16)] for _ in range(K)]
+            fx = [[w.copy()] for w in w0]
+            fm = None if mom_free else [[m0.copy()] for _ in range(K)]
+            mu = 0.0 if mom_free else 0.9
+            O.ga_update(gb, mx, mm, 0.05, mu, 1e-4, grad_scale=0.7, sync=sync, copies=cp)
+            O.ga_update(wide, fx, fm, 0.05, mu, 1e-4, grad_scale=0.7, sync=sync)
+            for k in range(K):
+                assert mx[k][0].tobytes() == fx[k][0].tobytes()
+                if not mom_free:
+                    assert mm[k][0].tobytes() == fm[k][0].tobytes()
+                want = torch.from_numpy(mx[k][0]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+                assert np.array_equal(cp[k][0], want)
+            if sync:                        # replicas that started apart stay apart under gradient aggregation
+                assert mx[0][0].tobytes() != mx[K - 1][0].tobytes()
+
+
+def test_ga_with_adam_against_torch_adam_fed_the_mean_gradient():
+    torch = pytest.importorskip("torch")
+    K, n, steps = 3, 300, 6
+    r = rng(56)
+    w0 = [(r.standard_normal(n) * 0.05).astype(np.float32) + np.float32(0.1 * k) for k in range(K)]
+    params = [[w.copy()] for w in w0]
+    m = [[np.zeros(n, np.float32)] for _ in range(K)]
+    v = [[np.zeros(n, np.float32)] for _ in range(K)]
+    tp = [torch.nn.Parameter(torch.from_numpy(w.copy()).double()) for w in w0]
+    opts = [torch.optim.Adam([p], lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=1e-2) for p in tp]
+    for t in range(1, steps + 1):
+        grads = [[(r.standard_normal(n) * 1e-2).astype(np.float32)] for _ in range(K)]
+        sync = t % 2 == 1
+        O.ga_update_adam(grads, params, m, v, 1e-3, 0.9, 0.999, 1e-8, 1e-2, t, grad_scale=0.5, sync=sync)
+        gbar = 0.5 * np.mean([g[0].astype(np.float64) for g in grads], axis=0)
+        for k in range(K):
+            tp[k].grad = torch.from_numpy(gbar if sync else 0.5 * grads[k][0].astype(np.float64))
+            opts[k].step()
+            np.testing.assert_allclose(params[k][0], tp[k].detach().numpy(), rtol=0, atol=3e-6)
+    # identical gradients on every worker: aggregation changes nothing, the step is each worker's own Adam step
+    same = [[grads[0][0].copy()] for _ in range(K)]
+    pa = [[w.copy()] for w in w0]
+    pb = [[w.copy()] for w in w0]
+    ma, va = [[np.zeros(n, np.float32)] for _ in range(K)], [[np.zeros(n, np.float32)] for _ in range(K)]
+    mb, vb = [[np.zeros(n, np.float32)] for _ in range(K)], [[np.zeros(n, np.float32)] for _ in range(K)]
+    O.ga_update_adam(same, pa, ma, va, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, grad_scale=0.25, sync=True)
+    O.ga_update_adam(same, pb, mb, vb, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, grad_scale=0.25, sync=False)
+    for k in range(K):
+        assert pa[k][0].tobytes() == pb[k][0].tobytes() and va[k][0].tobytes() == vb[k][0].tobytes()
+    # step 1 from zero moments: every worker moves by lr * sign(gbar), whatever its own parameters are
+    pc = [[w.copy()] for w in w0]
+    mc, vc = [[np.zeros(n, np.float32)] for _ in range(K)], [[np.zeros(n, np.float32)] for _ in range(K)]
+    O.ga_update_adam(grads, pc, mc, vc, 1e-3, 0.9, 0.999, 1e-12, 0.0, 1, sync=True)
+    sgn = np.sign(np.mean([g[0].astype(np.float64) for g in grads], axis=0))
+    for k in range(K):
+        np.testing.assert_allclose(w0[k] - pc[k][0], 1e-3 * sgn, rtol=0, atol=1e-6)
+    # mixed precision: masters follow the fp32 path, copies are their roundings
+    gb = [[O.f32_to_bf16(g[0])] for g in grads]
+    wide = [[(b[0].astype(np.uint32) << 16).view(np.float32).copy()] for b in gb]
+    px, mx, vx = [[w.copy()] for w in w0], [[np.zeros(n, np.float32)] for _ in range(K)], [[np.zeros(n, np.float32)] for _ in range(K)]
+    py, my, vy = [[w.copy()] for w in w0], [[np.zeros(n, np.float32)] for _ in range(K)], [[np.zeros(n, np.float32)] for _ in range(K)]
+    cp = [[np.zeros(n, np.uint16)] for _ in range(K)]
+    O.ga_update_adam(gb, px, mx, vx, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, sync=True, copies=cp)
+    O.ga_update_adam(wide, py, my, vy, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, sync=True)
+    for k in range(K):
+        assert px[k][0].tobytes() == py[k][0].tobytes()
+        want = torch.from_numpy(px[k][0]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(cp[k][0], want)
 
 
 # =============================================================== data partitioning (Sec. III-D)
