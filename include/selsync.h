@@ -192,8 +192,8 @@ const char *selsync_status_string(int32_t status);
  *   params  [K] worker replicas w_k.     F32; in mixed mode the BF16 working copies.
  *   momenta [K] momentum buffers m_k.    F32.  NULL when grads is NULL.  NULL with grads given makes a
  *                                         momentum-free plan: 12 instead of 20 bytes move per
- *                                         parameter; SGD entry points then require momentum = 0, and
- *                                         the Adam and gradient-aggregation entry points return STATE.
+ *                                         parameter; SGD entry points (gradient aggregation included)
+ *                                         then require momentum = 0, and the Adam entry points return STATE.
  *   master  [K] fp32 master parameters.  NULL in fp32 mode; required in mixed mode.
  *   global      the global model.        F32 (the fp32 master in mixed mode).
  *   global_lowp BF16 copy of the global model; NULL in fp32 mode, required in mixed mode.
@@ -345,6 +345,19 @@ int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sg
 int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, void *stream,
                         int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                         int32_t *sync_out);
+
+/*
+ * Gradient aggregation with Adam as the update (Sec. III-C with the Adam recipe of Sec. IV-A): on "sync"
+ * every worker feeds the mean gradient to its OWN Adam state (first and second moments stay per worker and
+ * are not averaged), otherwise its own gradient.  Needs bound second-moment buffers.  mode as above.
+ */
+int32_t selsync_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, int32_t mode,
+                               void *stream);
+
+/* One iteration: tracking pass over the gradients, then selsync_ga_update_adam(mode 0). */
+int32_t selsync_step_ga_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
+                             int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                             int32_t *sync_out);
 
 /* ---- for callers that cannot allocate ------------------------------------------------------ */
 

@@ -108,6 +108,8 @@ PROTOTYPES = {
     "selsync_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_ga_update": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _i32, _vp]),
     "selsync_step_ga": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_ga_update_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _i32, _vp]),
+    "selsync_step_ga_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_grad_norm_sq_noalloc": (_i32, [_tl, _i32, ctypes.c_float, _vp, _vp]),
     "selsync_partition_order": (_i32, [ctypes.c_int64, _i32, _i32, _i32, ctypes.c_int64,
                                        ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
@@ -389,6 +391,22 @@ class SelSync:
         n, d, f, s = self._outs()
         rc = self._check(selsync_step_ga(self._h, plan._h, ctypes.byref(sgd), _vp(_stream_handle(stream)),
                                          int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
+        return self._decision(rc, n, d, f, s) if blocking else None
+
+    def ga_update_adam(self, plan: Plan, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                       weight_decay: float = 0.0, grad_scale: float = 1.0, step: int = 0, always: bool = False,
+                       stream=None):
+        ad = selsync_adam(beta1, beta2, lr, eps, weight_decay, grad_scale, step)
+        self._check(selsync_ga_update_adam(self._h, plan._h, ctypes.byref(ad), 1 if always else 0,
+                                           _vp(_stream_handle(stream))))
+
+    def step_ga_adam(self, plan: Plan, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                     weight_decay: float = 0.0, grad_scale: float = 1.0, step: int = 0, blocking: bool = False,
+                     stream=None):
+        ad = selsync_adam(beta1, beta2, lr, eps, weight_decay, grad_scale, step)
+        n, d, f, s = self._outs()
+        rc = self._check(selsync_step_ga_adam(self._h, plan._h, ctypes.byref(ad), _vp(_stream_handle(stream)),
+                                              int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
         return self._decision(rc, n, d, f, s) if blocking else None
 
     # -- observability

@@ -104,6 +104,7 @@ struct selsync_plan {
     int n_agg_fine = 0;
     AggChunkRec *d_ga_chunks = nullptr;   // table of the K-way gradient-aggregation kernel (predicated launches)
     AggTables agg{};
+    float **d_agg_v = nullptr;            // device table behind agg.v (written when second moments are bound)
     AggShape agg_shape = kAggCoarse;      // workgroup shape that goes with d_agg_chunks
     AggShape ga_shape = kAggCoarse;       // workgroup shape that goes with d_ga_chunks
     bool nontemporal = true;              // streaming (non-temporal) loads and stores
@@ -914,6 +915,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     const size_t o_agc = take(agg_gc.size() * sizeof(uint16_t *));
     const size_t o_agrad = take(agg_grad.size() * sizeof(void *));
     const size_t o_am = take(agg_m.size() * sizeof(float *));
+    const size_t o_av = take(agg_m.size() * sizeof(float *));     // second-moment table, filled when they are bound
 
     std::vector<char> blob(off, 0);
     auto put = [&](size_t o, const void *src, size_t bytes) {
@@ -980,6 +982,8 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->agg.glowp = reinterpret_cast<uint16_t *const *>(b + o_agc);
     plan->agg.g = reinterpret_cast<const void *const *>(b + o_agrad);
     plan->agg.m = reinterpret_cast<float *const *>(b + o_am);
+    plan->d_agg_v = reinterpret_cast<float **>(b + o_av);
+    plan->agg.v = plan->d_agg_v;
 
     ctx->live_plans += 1;
     *out = plan.release();
@@ -1319,9 +1323,15 @@ extern "C" int32_t selsync_plan_bind_second_moment(selsync_plan *plan, const sel
             for (int t = 0; t < plan->T; ++t)
                 plan->h_recs[(size_t)k * plan->T + t].v = static_cast<float *>(v[k].tensors[t].data);
         (void)hipDeviceSynchronize();
-        if (!plan->h_recs.empty())
+        if (!plan->h_recs.empty()) {
             HIP_TRY(ctx, hipMemcpy(plan->d_recs, plan->h_recs.data(), plan->h_recs.size() * sizeof(TensorRec),
                                    hipMemcpyHostToDevice));
+            std::vector<float *> vt((size_t)plan->T * plan->K);      // K-way kernels index t * K + k
+            for (int k = 0; k < plan->K; ++k)
+                for (int t = 0; t < plan->T; ++t)
+                    vt[(size_t)t * plan->K + k] = static_cast<float *>(v[k].tensors[t].data);
+            HIP_TRY(ctx, hipMemcpy(plan->d_agg_v, vt.data(), vt.size() * sizeof(float *), hipMemcpyHostToDevice));
+        }
         plan->has_second_moment = true;      // plan->ivals stays the base set, so buffers can be re-bound
         return SELSYNC_OK;
     });
@@ -1382,8 +1392,8 @@ int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a
     if (mode == 1) {
         // always aggregate: one launch, shaped for bandwidth
         ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
-                                      &ctx->td.out->sync, 1, a, plan->nontemporal, s));
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, kAggFine,
+                                      plan->agg, plan->K, &ctx->td.out->sync, 1, a, plan->nontemporal, s));
         return SELSYNC_OK;
     }
     // Both launches follow the device-side decision word, so exactly one of them works whatever the
@@ -1395,11 +1405,34 @@ int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a
     }
     ProfScope p(ctx, 2, s);
     if (expect_sync(ctx))
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
-                                      &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, kAggFine,
+                                      plan->agg, plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
     else
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape, plan->agg,
-                                      plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_ga_chunks, plan->n_ga_chunks,
+                                      plan->ga_shape, plan->agg, plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+    return SELSYNC_OK;
+}
+
+// The same structure with Adam as the update.
+int32_t enqueue_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const AdamArgs &a, int mode, hipStream_t s)
+{
+    if (mode == 1) {
+        ProfScope p(ctx, 2, s);
+        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
+                                           &ctx->td.out->sync, 1, a, plan->nontemporal, s));
+        return SELSYNC_OK;
+    }
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->tab, a, plan->nontemporal, s, &ctx->td.out->sync, 0));
+    }
+    ProfScope p(ctx, 2, s);
+    if (expect_sync(ctx))
+        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
+                                           &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+    else
+        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape, plan->agg,
+                                           plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
     return SELSYNC_OK;
 }
 }  // namespace
@@ -1407,7 +1440,7 @@ int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a
 extern "C" int32_t selsync_ga_update(selsync_ctx *ctx, selsync_plan *plan, const selsync_sgd *sgd, int32_t mode,
                                      void *stream)
 {
-    int32_t rc = check_plan(ctx, plan, true, true);
+    int32_t rc = check_plan(ctx, plan, true);
     if (rc)
         return rc;
     if (mode != 0 && mode != 1)
@@ -1426,7 +1459,7 @@ extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const s
                                    int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                                    int32_t *sync_out)
 {
-    int32_t rc = check_plan(ctx, plan, true, true);
+    int32_t rc = check_plan(ctx, plan, true);
     if (rc)
         return rc;
     SgdArgs a;
@@ -1440,6 +1473,50 @@ extern "C" int32_t selsync_step_ga(selsync_ctx *ctx, selsync_plan *plan, const s
     if ((rc = enqueue_track(ctx, plan, s)))
         return rc;
     if ((rc = enqueue_ga_update(ctx, plan, a, 0, s)))
+        return rc;
+    ctx->local_steps += 1;
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, int32_t mode,
+                                          void *stream)
+{
+    int32_t rc = check_plan(ctx, plan, true, true);
+    if (rc)
+        return rc;
+    if (mode != 0 && mode != 1)
+        return fail(ctx, SELSYNC_ERR_INVALID_ARG, "mode must be 0 (follow the decision) or 1 (always aggregate)");
+    AdamArgs a;
+    if ((rc = resolve_adam(ctx, plan, adam, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((rc = enqueue_ga_update_adam(ctx, plan, a, mode, s)))
+        return rc;
+    ctx->local_steps += 1;
+    return SELSYNC_OK;
+}
+
+extern "C" int32_t selsync_step_ga_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
+                                        int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                                        int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true, true);
+    if (rc)
+        return rc;
+    AdamArgs a;
+    if ((rc = resolve_adam(ctx, plan, adam, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        SgdArgs n{0.f, 0.f, 0.f, a.gs, 0, 0};      // the norm-only pass uses the gradient scale alone
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_stream(kNormOnly, plan->mixed, plan->tab, n, plan->nontemporal, s));
+    }
+    if ((rc = enqueue_track(ctx, plan, s)))
+        return rc;
+    if ((rc = enqueue_ga_update_adam(ctx, plan, a, 0, s)))
         return rc;
     ctx->local_steps += 1;
     if (blocking)

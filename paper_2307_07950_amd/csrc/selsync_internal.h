@@ -69,6 +69,7 @@ struct AggTables {
     uint16_t *const *glowp;    // [T]    (mixed only)
     const void *const *g;      // [T*K]  gradients (only when the plan has gradients)
     float *const *m;           // [T*K]  momentum buffers (only when the plan has them)
+    float *const *v;           // [T*K]  second-moment buffers (filled when they are bound)
 };
 
 // Results of the last step plus the cumulative counters; one contiguous block so a
@@ -171,7 +172,7 @@ hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, co
 
 // Adam variant of the streaming kernel: update (+ norm partials when with_norm).
 hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a, bool nontemporal,
-                              hipStream_t s);
+                              hipStream_t s, const int32_t *pred = nullptr, int pred_want = 0);
 
 // Sums the partials of chunks segs[j].x .. segs[j].y - 1 into seg_sums[j], one workgroup per
 // segment.  slot_per: see chunk_slot().
@@ -192,9 +193,13 @@ hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32
 // Synchronising update of gradient aggregation (Sec. III-C): when the decision is "sync" (or
 // mode 1) every worker applies the mean gradient to its own parameters and momentum; on a
 // "local" decision the launch does nothing (the caller runs the plain local update instead).
-hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
-                            int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal,
-                            hipStream_t s);
+hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggChunkRec *chunks, int nchunks, AggShape shape,
+                            const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd,
+                            bool nontemporal, hipStream_t s);
+// ... with Adam as the update (first and second moment buffers per worker).
+hipError_t launch_update_ga_adam(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape,
+                                 const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const AdamArgs &a,
+                                 bool nontemporal, hipStream_t s);
 
 // One whole synchronous iteration in one pass over 256-element pieces of all K workers: per-worker
 // squared-gradient partials (partials[k * npieces + piece]), local update, mean of the updated

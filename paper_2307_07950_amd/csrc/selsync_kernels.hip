@@ -230,21 +230,6 @@ __device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, f32x4 
     v.x = v0; v.y = v1; v.z = v2; v.w = v3;
 }
 
-// SGD forms without a second-moment operand (used by the gradient-aggregation update).
-template <bool UPD, bool NORM>
-__device__ __forceinline__ void elem(float g, float &w, float &m, const SgdArgs &a, double &acc)
-{
-    float unused = 0.f;
-    SgdOpt::elem<UPD, NORM>(g, w, m, unused, a, acc);
-}
-
-template <bool UPD, bool NORM>
-__device__ __forceinline__ void elem4(const f32x4 &g, f32x4 &w, f32x4 &m, const SgdArgs &a, double &acc)
-{
-    f32x4 unused = 0.f;
-    elem4<SgdOpt, UPD, NORM>(g, w, m, unused, a, acc);
-}
-
 // ---------------------------------------------------------------- k_stream
 
 // What a wavefront knows about one chunk (all of it wave-uniform, i.e. in scalar registers).
@@ -900,19 +885,21 @@ __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, dou
 
 // The synchronising update of gradient aggregation (Sec. III-C): one workgroup walks one
 // piece of one tensor across the K workers and applies the mean gradient to every worker's
-// own (w, m).  Launched on every step of that variant: unless `always`, it does this only
-// when the device-side decision says "sync" and otherwise exits at once (the plain local
-// update of such a step is the streaming kernel's job).  K compile-time (KC > 0) keeps all
-// 3K loads of a vector in flight.
-template <int BLOCK, int KC, bool MIXED, bool NT>
+// own state with the optimiser policy OPT (momentum SGD, momentum-free SGD, Adam: the
+// moment buffers stay per worker).  Launched on every step of that variant: unless `always`,
+// it does this only when the device-side decision says "sync" and otherwise exits at once
+// (the plain local update of such a step is the streaming kernel's job).  K compile-time
+// (KC > 0) keeps all loads of a vector in flight.
+template <class OPT, int BLOCK, int KC, bool MIXED, bool NT>
 __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, AggTables tabs, int K,
                                                      double invK, int pow2,
-                                                     const int32_t *__restrict__ sync_flag, int always, SgdArgs a)
+                                                     const int32_t *__restrict__ sync_flag, int always,
+                                                     typename OPT::Args a)
 {
     constexpr int KM = KC > 0 ? KC : 1;
     if (!always && *sync_flag == 0)
         return;
-    SgdArgs a1 = a;   // applied to the mean gradient, which is already scaled
+    typename OPT::Args a1 = a;   // applied to the mean gradient, which is already scaled
     a1.gs = 1.f;
     const uint32_t tid = threadIdx.x;
     double unused = 0.0;
@@ -928,13 +915,15 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                 const uint64_t off = ch.off + head;
                 SELSYNC_GLOBAL f32x4 *wp[KM];
                 SELSYNC_GLOBAL f32x4 *mp[KM];
+                SELSYNC_GLOBAL f32x4 *vp[KM];
                 const SELSYNC_GLOBAL f32x4 *gp[KM];
                 const SELSYNC_GLOBAL u32x2 *gbp[KM];
                 SELSYNC_GLOBAL u32x2 *cp[KM];
 #pragma unroll
                 for (int k = 0; k < KC; ++k) {
                     wp[k] = as_global<f32x4>(tabs.w[row + k] + off);
-                    mp[k] = as_global<f32x4>(tabs.m[row + k] + off);
+                    mp[k] = OPT::kMomentum ? as_global<f32x4>(tabs.m[row + k] + off) : nullptr;
+                    vp[k] = OPT::kSecondMoment ? as_global<f32x4>(tabs.v[row + k] + off) : nullptr;
                     gp[k] = MIXED ? nullptr : as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + off);
                     gbp[k] = MIXED ? as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + off)
                                    : nullptr;
@@ -942,7 +931,7 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                 }
                 const uint32_t nvec = (n - head) / 4;
                 for (uint32_t i = tid; i < nvec; i += BLOCK) {
-                    f32x4 gv[KM], wv[KM], mv[KM];
+                    f32x4 gv[KM], wv[KM], mv[KM], vv[KM];
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
                         if (MIXED)
@@ -951,15 +940,22 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                             gv[k] = ld<NT>(gp[k] + i);
                         wv[k] = ld<NT>(wp[k] + i);
                         mv[k] = 0.f;
-                        if (!a.first)
+                        vv[k] = 0.f;
+                        if (OPT::kMomentum && !a.first) {
                             mv[k] = ld<NT>(mp[k] + i);
+                            if (OPT::kSecondMoment)
+                                vv[k] = ld<NT>(vp[k] + i);
+                        }
                     }
                     const f32x4 gbar = mean_grad4<KC>(gv, KC, a.gs, invK, pow2);
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
-                        elem4<true, false>(gbar, wv[k], mv[k], a1, unused);
+                        elem4<OPT, true, false>(gbar, wv[k], mv[k], vv[k], a1, unused);
                         st<NT>(wp[k] + i, wv[k]);
-                        st<NT>(mp[k] + i, mv[k]);
+                        if (OPT::kMomentum)
+                            st<NT>(mp[k] + i, mv[k]);
+                        if (OPT::kSecondMoment)
+                            st<NT>(vp[k] + i, vv[k]);
                         if (MIXED) {
                             u32x2 cv;
                             cv.x = bf16_pack(wv[k].x, wv[k].y);
@@ -988,12 +984,19 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
             const float gbar = finish_mean(s, K, invK, pow2);
             for (int k = 0; k < K; ++k) {
                 SELSYNC_GLOBAL float *wq = as_global<float>(tabs.w[row + k]);
-                SELSYNC_GLOBAL float *mq = as_global<float>(tabs.m[row + k]);
                 float w = wq[e];
-                float m = a.first ? 0.f : mq[e];
-                elem<true, false>(gbar, w, m, a1, unused);
+                float m = 0.f, v = 0.f;
+                if (OPT::kMomentum && !a.first) {
+                    m = as_global<const float>(tabs.m[row + k])[e];
+                    if (OPT::kSecondMoment)
+                        v = as_global<const float>(tabs.v[row + k])[e];
+                }
+                OPT::template elem<true, false>(gbar, w, m, v, a1, unused);
                 wq[e] = w;
-                mq[e] = m;
+                if (OPT::kMomentum)
+                    as_global<float>(tabs.m[row + k])[e] = m;
+                if (OPT::kSecondMoment)
+                    as_global<float>(tabs.v[row + k])[e] = v;
                 if (MIXED)
                     as_global<uint16_t>(tabs.lowp[row + k])[e] = (uint16_t)bf16_bits(w);
             }
@@ -1293,17 +1296,17 @@ hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, AggShape shape, 
     return hipGetLastError();
 }
 
-template <int KC, bool MIXED, bool NT>
+template <class OPT, int KC, bool MIXED, bool NT>
 hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const SgdArgs &sgd, hipStream_t s)
+                       const int32_t *flag, int mode, const typename OPT::Args &args, hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
     if (shape == kAggFine)
-        hipLaunchKernelGGL((k_update_ga<64, KC, MIXED, NT>), dim3(nchunks), dim3(64), 0, s, chunks, tabs, K,
-                           1.0 / (double)K, pow2, flag, mode, sgd);
+        hipLaunchKernelGGL((k_update_ga<OPT, 64, KC, MIXED, NT>), dim3(nchunks), dim3(64), 0, s, chunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode, args);
     else
-        hipLaunchKernelGGL((k_update_ga<256, KC, MIXED, NT>), dim3(nchunks), dim3(256), 0, s, chunks, tabs, K,
-                           1.0 / (double)K, pow2, flag, mode, sgd);
+        hipLaunchKernelGGL((k_update_ga<OPT, 256, KC, MIXED, NT>), dim3(nchunks), dim3(256), 0, s, chunks, tabs, K,
+                           1.0 / (double)K, pow2, flag, mode, args);
     return hipGetLastError();
 }
 
@@ -1327,13 +1330,26 @@ hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, AggShape shape, 
 #undef SELSYNC_AGG_CALL
 }
 
-template <bool MIXED, bool NT>
+template <class OPT, bool MIXED, bool NT>
 hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const SgdArgs &sgd, hipStream_t s)
+                       const int32_t *flag, int mode, const typename OPT::Args &args, hipStream_t s)
 {
-#define SELSYNC_GA_CALL(KC) launch_ga_t<KC, MIXED, NT>(chunks, nchunks, shape, tabs, K, flag, mode, sgd, s)
+#define SELSYNC_GA_CALL(KC) launch_ga_t<OPT, KC, MIXED, NT>(chunks, nchunks, shape, tabs, K, flag, mode, args, s)
     SELSYNC_SWITCH_K(K, SELSYNC_GA_CALL)
 #undef SELSYNC_GA_CALL
+}
+
+template <class OPT>
+hipError_t launch_ga_o(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
+                       const int32_t *flag, int mode, const typename OPT::Args &args, bool nontemporal, hipStream_t s)
+{
+    if (nchunks <= 0)
+        return hipSuccess;
+    if (mixed)
+        return nontemporal ? launch_ga_k<OPT, true, true>(chunks, nchunks, shape, tabs, K, flag, mode, args, s)
+                           : launch_ga_k<OPT, true, false>(chunks, nchunks, shape, tabs, K, flag, mode, args, s);
+    return nontemporal ? launch_ga_k<OPT, false, true>(chunks, nchunks, shape, tabs, K, flag, mode, args, s)
+                       : launch_ga_k<OPT, false, false>(chunks, nchunks, shape, tabs, K, flag, mode, args, s);
 }
 
 template <class OPT, int KC, bool MIXED, bool NT>
@@ -1379,9 +1395,10 @@ hipError_t launch_stream(StreamMode mode, bool mixed, const StreamTable &tab, co
 }
 
 hipError_t launch_stream_adam(bool with_norm, bool mixed, const StreamTable &tab, const AdamArgs &a, bool nontemporal,
-                              hipStream_t s)
+                              hipStream_t s, const int32_t *pred, int pred_want)
 {
-    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, nontemporal, nullptr, 0, s);
+    return launch_stream_o<AdamOpt>(with_norm ? kUpdateAndNorm : kUpdateOnly, mixed, tab, a, nontemporal, pred,
+                                    pred_want, s);
 }
 
 hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs, int nsegs, double *seg_sums,
@@ -1420,17 +1437,20 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
                        : launch_agg_k<false, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s);
 }
 
-hipError_t launch_update_ga(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
-                            int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal,
-                            hipStream_t s)
+hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggChunkRec *chunks, int nchunks, AggShape shape,
+                            const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd,
+                            bool nontemporal, hipStream_t s)
 {
-    if (nchunks <= 0)
-        return hipSuccess;
-    if (mixed)
-        return nontemporal ? launch_ga_k<true, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s)
-                           : launch_ga_k<true, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s);
-    return nontemporal ? launch_ga_k<false, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s)
-                       : launch_ga_k<false, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, s);
+    if (!has_momentum)
+        return launch_ga_o<PlainSgdOpt>(mixed, chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, nontemporal, s);
+    return launch_ga_o<SgdOpt>(mixed, chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, nontemporal, s);
+}
+
+hipError_t launch_update_ga_adam(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape,
+                                 const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const AdamArgs &a,
+                                 bool nontemporal, hipStream_t s)
+{
+    return launch_ga_o<AdamOpt>(mixed, chunks, nchunks, shape, tabs, K, sync_flag, mode, a, nontemporal, s);
 }
 
 hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggChunkRec *pieces, int npieces, const AggTables &tabs,

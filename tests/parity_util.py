@@ -285,6 +285,31 @@ class LockStep:
             assert to_host(self.d_glob[t]).tobytes() == glob_before[t].tobytes()
         return dec, rec
 
+    def step_ga_adam(self, slot: int, lr: float, b1: float, b2: float, eps: float, wd: float, gs: float = 1.0,
+                     fused: bool = True):
+        """One iteration under gradient aggregation with Adam as the update, on both sides."""
+        plan = self.plans[slot]
+        t = self.steps_done + 1
+        glob_before = [to_host(x) for x in self.d_glob]
+        if fused:
+            dec = self.ctx.step_ga_adam(plan, lr, b1, b2, eps, wd, gs, step=t, blocking=True)
+        else:
+            dec = self.ctx.track_grad_change(plan, gs, blocking=True)
+            self.ctx.ga_update_adam(plan, lr, b1, b2, eps, wd, gs, step=t, always=False)
+        g = self.h_grads[slot]
+        rec = self.oracle.track(g, gs)
+        sync = self._check_decision(dec, rec)
+        O.ga_update_adam(g, self.h_w, self.h_m, self.h_v, lr, b1, b2, eps, wd, t, gs, bool(sync), self.h_c)
+        self.steps_done += 1
+        self.compare(after_sync=False)
+        for k in range(self.K):
+            for i in range(len(self.numel)):
+                self.worst_ulp = max(self.worst_ulp, assert_update_close(to_host(self.d_v[k][i]), self.h_v[k][i],
+                                                                         "second moment[%d][%d]" % (k, i)))
+        for i in range(len(self.numel)):
+            assert to_host(self.d_glob[i]).tobytes() == glob_before[i].tobytes()
+        return dec, rec
+
     def compare(self, after_sync: bool = False):
         torch.cuda.synchronize()
         for k in range(self.K):

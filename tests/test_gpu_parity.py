@@ -873,6 +873,84 @@ def test_gradient_aggregation_always_mode_and_bsp_equivalence(B):
     ls.close()
 
 
+@pytest.mark.parametrize("K", [2, 3, 4, 8])
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_gradient_aggregation_on_momentum_free_plans(B, K, mixed, misalign):
+    # Sec. III-C with the momentum-free SGD of the Transformer recipe: no buffer is bound, read or written
+    numel = [70001, 5, 4096, 0, 1023]
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=24,
+                     momentum_free=True, tuning=dict(nontemporal=K % 2, ga_chunk_elems=[0, 256][misalign]))
+    r = rng(240 + K)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    for k in range(K):                          # replicas start apart: they must stay apart
+        for t, n in enumerate(numel):
+            ls.h_w[k][t] += np.float32(1e-3 * k)
+            ls.d_w[k][t].copy_(torch.from_numpy(ls.h_w[k][t]))
+            if mixed:
+                ls.h_c[k][t][...] = W.round_to_bf16_bits(ls.h_w[k][t])
+                ls.d_c[k][t].copy_(PU.to_dev(ls.h_c[k][t]))
+    syncs = 0
+    for t in range(9):
+        dec, rec = ls.step_ga([0, 1, 2, 2, 0, 1, 1, 2, 0][t], 2.0 * 0.8 ** t, 0.0, [0.0, 1e-4][t % 2], [1.0, 0.7][t % 2],
+                              fused=(t % 3 != 1))
+        syncs += rec.sync
+    assert 0 < syncs < 9 and ls.worst_ulp == 0
+    assert PU.to_host(ls.d_w[0][0]).tobytes() != PU.to_host(ls.d_w[K - 1][0]).tobytes()
+    # always-mode on the bandwidth-shaped table
+    ls.ctx.ga_update(ls.plans[0], 0.1, 0.0, 1e-4, 0.5, always=True)
+    O.ga_update(ls.h_grads[0], ls.h_w, None, 0.1, 0.0, 1e-4, 0.5, False, True, ls.h_c)
+    ls.compare()
+    ls.close()
+
+
+@pytest.mark.parametrize("K", [1, 3, 4, 8])
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_gradient_aggregation_with_adam_matches_oracle(B, K, mixed, misalign):
+    # every worker feeds the mean gradient to its own Adam state on "sync", its own gradient on "local"
+    numel = [70001, 5, 4096, 0, 1023]
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign, seed=25,
+                     tuning=dict(nontemporal=int(misalign == 0), ga_chunk_elems=[0, 512][K % 2]))
+    r = rng(250 + K)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    for k in range(K):
+        for t, n in enumerate(numel):
+            ls.h_w[k][t] += np.float32(1e-3 * k)
+            ls.d_w[k][t].copy_(torch.from_numpy(ls.h_w[k][t]))
+            if mixed:
+                ls.h_c[k][t][...] = W.round_to_bf16_bits(ls.h_w[k][t])
+                ls.d_c[k][t].copy_(PU.to_dev(ls.h_c[k][t]))
+    with pytest.raises(B.SelSyncError) as e:                 # needs its second-moment buffers
+        ls.ctx.ga_update_adam(ls.plans[0], 1e-3)
+    assert e.value.status == B.SELSYNC_ERR_STATE
+    ls.enable_adam()
+    syncs = 0
+    for t in range(9):
+        dec, rec = ls.step_ga_adam([0, 1, 2, 2, 0, 1, 1, 2, 0][t], 1e-3, 0.9, 0.999, 1e-8, [0.0, 1e-2][t % 2],
+                                   [1.0, 0.7][t % 2], fused=(t % 3 != 1))
+        syncs += rec.sync
+    assert 0 < syncs < 9 and ls.worst_ulp == 0
+    if K > 1:
+        assert PU.to_host(ls.d_w[0][0]).tobytes() != PU.to_host(ls.d_w[K - 1][0]).tobytes()
+    # always-mode on the bandwidth-shaped table
+    t = ls.steps_done + 1
+    ls.ctx.ga_update_adam(ls.plans[1], 1e-3, 0.9, 0.999, 1e-8, 0.0, 0.5, step=t, always=True)
+    O.ga_update_adam(ls.h_grads[1], ls.h_w, ls.h_m, ls.h_v, 1e-3, 0.9, 0.999, 1e-8, 0.0, t, 0.5, True, ls.h_c)
+    ls.compare()
+    ls.close()
+
+
 # ================================================================= many workers
 
 @pytest.mark.parametrize("K", [17, 40, 130])
@@ -970,15 +1048,19 @@ def test_random_configuration_matches_oracle(B, seed):
     for t in range(6):
         ls.step(int(r.integers(0, 2)), 0.05, mu, float(r.choice([0.0, 1e-4])), float(r.choice([1.0, 0.5])),
                 fused=bool(r.integers(0, 2)), nesterov=nesterov)
+    for t in range(3):
+        ls.step_ga(int(r.integers(0, 2)), 0.05, mu, 1e-4, 1.0, fused=bool(r.integers(0, 2)), nesterov=nesterov)
+    ls.step_bsp(int(r.integers(0, 2)), 0.05, mu, 1e-4, 0.5, nesterov=nesterov)
     if not momentum_free:
-        for t in range(3):
-            ls.step_ga(int(r.integers(0, 2)), 0.05, mu, 1e-4, 1.0, fused=bool(r.integers(0, 2)), nesterov=nesterov)
         if r.integers(0, 2):
             ls.enable_adam()
             ls.steps_done = 0                      # Adam's bias correction counts its own steps from 1
             for t in range(3):
                 ls.step_adam(int(r.integers(0, 2)), 1e-3, 0.9, 0.999, 1e-8, float(r.choice([0.0, 1e-4])), 1.0,
                              fused=bool(r.integers(0, 2)))
+            for t in range(2):
+                ls.step_ga_adam(int(r.integers(0, 2)), 1e-3, 0.9, 0.999, 1e-8, float(r.choice([0.0, 1e-4])), 1.0,
+                                fused=bool(r.integers(0, 2)))
     assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
     st = ls.ctx.stats()
     assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
@@ -1012,7 +1094,7 @@ def test_momentum_free_sgd_matches_oracle(B, mixed, misalign, tuning):
     ls.close()
 
 
-def test_momentum_free_plan_rejects_momentum_adam_and_gradient_aggregation(B):
+def test_momentum_free_plan_rejects_momentum_and_adam(B):
     K = 2
     ctx = B.SelSync(K, 0.3)
     mk = lambda n: torch.zeros(n, dtype=torch.float32, device="cuda")
@@ -1027,9 +1109,13 @@ def test_momentum_free_plan_rejects_momentum_adam_and_gradient_aggregation(B):
     ctx.local_step(plan, 0.1, 0.0)
     assert status(lambda: ctx.local_step(plan, 0.1, 0.9)) == B.SELSYNC_ERR_INVALID_ARG
     assert status(lambda: ctx.step(plan, 0.1, 0.0, nesterov=True)) == B.SELSYNC_ERR_INVALID_ARG
-    assert status(lambda: ctx.ga_update(plan, 0.1, 0.0)) == B.SELSYNC_ERR_STATE
-    assert status(lambda: ctx.step_ga(plan, 0.1, 0.0)) == B.SELSYNC_ERR_STATE
+    ctx.ga_update(plan, 0.1, 0.0)                       # gradient aggregation works without momentum buffers ...
+    ctx.step_ga(plan, 0.1, 0.0)
+    assert status(lambda: ctx.ga_update(plan, 0.1, 0.9)) == B.SELSYNC_ERR_INVALID_ARG      # ... with momentum 0
+    assert status(lambda: ctx.step_ga(plan, 0.1, 0.9)) == B.SELSYNC_ERR_INVALID_ARG
     assert status(lambda: ctx.bind_second_moment(plan, [[mk(100)] for _ in range(K)])) == B.SELSYNC_ERR_STATE
+    assert status(lambda: ctx.ga_update_adam(plan, 1e-3)) == B.SELSYNC_ERR_STATE
+    assert status(lambda: ctx.step_ga_adam(plan, 1e-3)) == B.SELSYNC_ERR_STATE
     # momenta without gradients make no sense
     assert status(lambda: ctx.plan(None, p, [[mk(100)] for _ in range(K)], glob)) == B.SELSYNC_ERR_INVALID_ARG
     # Nesterov needs momentum > 0 on an ordinary plan too
