@@ -1389,37 +1389,37 @@ namespace {
 // applies the mean gradient).  Mode 1 always aggregates.
 int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a, int mode, hipStream_t s)
 {
-    if (mode == 1) {
-        // always aggregate: one launch, shaped for bandwidth
+    if (mode == 1 || expect_sync(ctx)) {
+        // One launch shaped for bandwidth.  Always-mode aggregates; otherwise (the last decision was taken
+        // under a threshold of 0, so "sync" is expected) the kernel still reads the decision word and, should
+        // it say "local", applies every worker's own gradient itself: right under any decision, also when a
+        // recorded launch is replayed after the threshold has changed.
         ProfScope p(ctx, 2, s);
         HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, kAggFine,
-                                      plan->agg, plan->K, &ctx->td.out->sync, 1, a, plan->nontemporal, s));
+                                      plan->agg, plan->K, &ctx->td.out->sync, mode == 1 ? kGaAlways : kGaSyncOrLocal, a,
+                                      plan->nontemporal, s));
         return SELSYNC_OK;
     }
-    // Both launches follow the device-side decision word, so exactly one of them works whatever the
-    // host expects; the expectation (a last decision under a threshold of 0 synchronises) only gives
-    // the K-way launch its bandwidth shape.
+    // Two launches that both follow the device-side decision word, of which exactly one works: on "local"
+    // the streaming kernel in its fastest shape, on "sync" the K-way kernel.
     {
         ProfScope p(ctx, 0, s);
         HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->nontemporal, s, &ctx->td.out->sync, 0));
     }
     ProfScope p(ctx, 2, s);
-    if (expect_sync(ctx))
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, kAggFine,
-                                      plan->agg, plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
-    else
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_ga_chunks, plan->n_ga_chunks,
-                                      plan->ga_shape, plan->agg, plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+    HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape,
+                                  plan->agg, plan->K, &ctx->td.out->sync, kGaSyncOnly, a, plan->nontemporal, s));
     return SELSYNC_OK;
 }
 
 // The same structure with Adam as the update.
 int32_t enqueue_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const AdamArgs &a, int mode, hipStream_t s)
 {
-    if (mode == 1) {
+    if (mode == 1 || expect_sync(ctx)) {
         ProfScope p(ctx, 2, s);
         HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
-                                           &ctx->td.out->sync, 1, a, plan->nontemporal, s));
+                                           &ctx->td.out->sync, mode == 1 ? kGaAlways : kGaSyncOrLocal, a,
+                                           plan->nontemporal, s));
         return SELSYNC_OK;
     }
     {
@@ -1427,12 +1427,8 @@ int32_t enqueue_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const AdamA
         HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->tab, a, plan->nontemporal, s, &ctx->td.out->sync, 0));
     }
     ProfScope p(ctx, 2, s);
-    if (expect_sync(ctx))
-        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
-                                           &ctx->td.out->sync, 0, a, plan->nontemporal, s));
-    else
-        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape, plan->agg,
-                                           plan->K, &ctx->td.out->sync, 0, a, plan->nontemporal, s));
+    HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape, plan->agg,
+                                       plan->K, &ctx->td.out->sync, kGaSyncOnly, a, plan->nontemporal, s));
     return SELSYNC_OK;
 }
 }  // namespace

@@ -190,9 +190,13 @@ hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, 
 hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32_t *range_begin, int nranges,
                                double *out, hipStream_t s);
 
-// Synchronising update of gradient aggregation (Sec. III-C): when the decision is "sync" (or
-// mode 1) every worker applies the mean gradient to its own parameters and momentum; on a
-// "local" decision the launch does nothing (the caller runs the plain local update instead).
+// What a launch of the gradient-aggregation update does with the device-side decision.
+enum GaMode { kGaSyncOnly = 0, kGaAlways = 1, kGaSyncOrLocal = 2 };
+
+// Update of gradient aggregation (Sec. III-C): on "sync" (or kGaAlways) every worker applies the
+// mean gradient to its own parameters and optimiser state; on "local" the launch exits
+// (kGaSyncOnly: the caller runs the plain local update in a launch of its own) or applies every
+// worker's own gradient itself (kGaSyncOrLocal).
 hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggChunkRec *chunks, int nchunks, AggShape shape,
                             const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd,
                             bool nontemporal, hipStream_t s);

@@ -862,6 +862,15 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restri
 
 // ---------------------------------------------------------------- k_update_ga
 
+// One gradient element: fp32, or bf16 widened exactly.
+template <bool MIXED>
+__device__ __forceinline__ float load_grad(const void *g, uint64_t e)
+{
+    if (MIXED)
+        return __uint_as_float(((uint32_t)as_global<const uint16_t>(g)[e]) << 16);
+    return as_global<const float>(g)[e];
+}
+
 // Mean of K scaled gradients, fp64 sum in worker order, one rounding to fp32.
 template <int KC>
 __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, double invK, int pow2)
@@ -886,18 +895,23 @@ __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, dou
 // The synchronising update of gradient aggregation (Sec. III-C): one workgroup walks one
 // piece of one tensor across the K workers and applies the mean gradient to every worker's
 // own state with the optimiser policy OPT (momentum SGD, momentum-free SGD, Adam: the
-// moment buffers stay per worker).  Launched on every step of that variant: unless `always`,
-// it does this only when the device-side decision says "sync" and otherwise exits at once
-// (the plain local update of such a step is the streaming kernel's job).  K compile-time
-// (KC > 0) keeps all loads of a vector in flight.
+// moment buffers stay per worker).  Launched on every step of that variant.  `mode` says what
+// the launch does with the device-side decision:
+//   kGaAlways         aggregate whatever the decision is;
+//   kGaSyncOnly       aggregate on "sync", exit at once on "local" (the plain local update of such
+//                     a step is then the streaming kernel's job, in its own predicated launch);
+//   kGaSyncOrLocal    aggregate on "sync"; on "local" every worker applies its OWN gradient, here
+//                     (one launch serves both decisions: for steps that are expected to synchronise).
+// K compile-time (KC > 0) keeps all loads of a vector in flight.
 template <class OPT, int BLOCK, int KC, bool MIXED, bool NT>
 __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, AggTables tabs, int K,
                                                      double invK, int pow2,
-                                                     const int32_t *__restrict__ sync_flag, int always,
+                                                     const int32_t *__restrict__ sync_flag, int mode,
                                                      typename OPT::Args a)
 {
     constexpr int KM = KC > 0 ? KC : 1;
-    if (!always && *sync_flag == 0)
+    const bool sync = mode == kGaAlways || *sync_flag != 0;
+    if (!sync && mode == kGaSyncOnly)
         return;
     typename OPT::Args a1 = a;   // applied to the mean gradient, which is already scaled
     a1.gs = 1.f;
@@ -947,10 +961,15 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                                 vv[k] = ld<NT>(vp[k] + i);
                         }
                     }
-                    const f32x4 gbar = mean_grad4<KC>(gv, KC, a.gs, invK, pow2);
+                    f32x4 gbar = 0.f;
+                    if (sync)
+                        gbar = mean_grad4<KC>(gv, KC, a.gs, invK, pow2);
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
-                        elem4<OPT, true, false>(gbar, wv[k], mv[k], vv[k], a1, unused);
+                        if (sync)
+                            elem4<OPT, true, false>(gbar, wv[k], mv[k], vv[k], a1, unused);
+                        else
+                            elem4<OPT, true, false>(gv[k], wv[k], mv[k], vv[k], a, unused);
                         st<NT>(wp[k] + i, wv[k]);
                         if (OPT::kMomentum)
                             st<NT>(mp[k] + i, mv[k]);
@@ -972,14 +991,11 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
             const uint32_t i = j < head ? j : j + done;
             const uint64_t e = ch.off + i;
             double s = 0.0;
-            for (int k = 0; k < K; ++k) {
-                float g;
-                if (MIXED)
-                    g = __uint_as_float(((uint32_t)as_global<const uint16_t>(tabs.g[row + k])[e]) << 16);
-                else
-                    g = as_global<const float>(tabs.g[row + k])[e];
-                const float gh = a.gs * g;
-                s += (double)gh;
+            if (sync) {
+                for (int k = 0; k < K; ++k) {
+                    const float gh = a.gs * load_grad<MIXED>(tabs.g[row + k], e);
+                    s += (double)gh;
+                }
             }
             const float gbar = finish_mean(s, K, invK, pow2);
             for (int k = 0; k < K; ++k) {
@@ -991,7 +1007,10 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
                     if (OPT::kSecondMoment)
                         v = as_global<const float>(tabs.v[row + k])[e];
                 }
-                OPT::template elem<true, false>(gbar, w, m, v, a1, unused);
+                if (sync)
+                    OPT::template elem<true, false>(gbar, w, m, v, a1, unused);
+                else
+                    OPT::template elem<true, false>(load_grad<MIXED>(tabs.g[row + k], e), w, m, v, a, unused);
                 wq[e] = w;
                 if (OPT::kMomentum)
                     as_global<float>(tabs.m[row + k])[e] = m;

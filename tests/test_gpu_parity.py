@@ -560,17 +560,17 @@ def test_mode0_follows_the_device_decision_after_the_threshold_changes(B):
     ls.close()
 
 
-@pytest.mark.parametrize("variant", ["pa", "ga"])
-def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant):
+@pytest.mark.parametrize("variant,K,mixed", [("pa", 4, False), ("ga", 4, False), ("ga", 3, True), ("pa", 3, True)])
+def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant, K, mixed):
     """A step recorded into a HIP graph under delta = 0 (when the library expects every step to
     synchronise) and replayed after selsync_set_delta(0.3) must take the decisions of delta = 0.3:
     every replay is compared with the oracle, decisions and tensors."""
     numel = [150001, 777, 4096]
-    K = 4
     r = rng(730)
-    ls = PU.LockStep(B, numel, K, delta=0.0, window=4, alpha=0.5, seed=73)
-    ls.bind_grads(0, [[(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel] for _ in range(K)])
-    scales = [1.0, 1.0, 3.0, 1.0, 1.0, 0.2, 1.0]
+    ls = PU.LockStep(B, numel, K, delta=0.0, window=4, alpha=0.5, seed=73, mixed=mixed)
+    g0 = [[(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel] for _ in range(K)]
+    ls.bind_grads(0, [[W.round_to_bf16_bits(a) for a in gk] for gk in g0] if mixed else g0)
+    scales = [1.0, 1.0, 4.0, 1.0, 1.0, 0.25, 1.0]           # powers of two: exact in bf16 as well
     step = ls.step if variant == "pa" else ls.step_ga
     step(0, 0.05, 0.9, 1e-4, scales[0])                     # eager, delta = 0: synchronises
     assert ls.oracle.steps_sync == 1
@@ -589,7 +589,10 @@ def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant):
             for i, x in enumerate(ls.d_grads[0][k]):
                 f = np.float32(scales[t]) / np.float32(scales[t - 1])
                 x.mul_(float(f))
-                ls.h_grads[0][k][i] *= f
+                if mixed:
+                    ls.h_grads[0][k][i][...] = W.round_to_bf16_bits(W.bf16_bits_to_f32(ls.h_grads[0][k][i]) * f)
+                else:
+                    ls.h_grads[0][k][i] *= f
         g.replay()
         torch.cuda.synchronize()
         dec = ls.ctx.read_decision()
@@ -598,11 +601,12 @@ def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant):
         assert ls.forced == 0
         if variant == "pa":
             for k in range(K):
-                O.sgd_update(ls.h_w[k], ls.h_m[k], ls.h_grads[0][k], 0.05, 0.9, 1e-4, 1.0, False)
+                O.sgd_update(ls.h_w[k], ls.h_m[k], ls.h_grads[0][k], 0.05, 0.9, 1e-4, 1.0, False,
+                             None if not mixed else ls.h_c[k])
             if sync:
-                O.average_params(ls.h_w, ls.h_glob)
+                O.average_params(ls.h_w, ls.h_glob, ls.h_c, ls.h_gc)
         else:
-            O.ga_update(ls.h_grads[0], ls.h_w, ls.h_m, 0.05, 0.9, 1e-4, 1.0, False, bool(sync))
+            O.ga_update(ls.h_grads[0], ls.h_w, ls.h_m, 0.05, 0.9, 1e-4, 1.0, False, bool(sync), ls.h_c)
         ls.steps_done += 1
         ls.compare()
         if variant == "pa" and sync:
