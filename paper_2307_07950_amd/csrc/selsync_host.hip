@@ -87,8 +87,10 @@ struct selsync_plan {
     double *d_tensor_norms = nullptr;
     bool partials_valid = false;     // a tracking pass has been enqueued on this plan
     bool partials_from_sync = false; // ... and the last one was the one-pass synchronous step (its own partial array)
-    // one-pass synchronous step: partial sums indexed k * n_agg_fine + piece, and their reduction tables
+    // one-pass synchronous step: worker k's piece p is "chunk" k * t_fine.nslots + p of a partial array
+    // striped with per = K * t_fine.per8 (see chunk_slot), and the reduction tables over those chunk numbers
     double *d_sync_partials = nullptr;
+    int sync_per = 0;
     int32_t *d_sync_begin = nullptr;         // [K+1] worker k's partials
     int n_sync_segs = 0;
     int2 *d_sync_segs = nullptr;
@@ -99,14 +101,11 @@ struct selsync_plan {
     std::vector<int64_t> numel;      // per-tensor element counts
     std::vector<Interval> ivals;     // every bound buffer (checked again when more buffers are bound)
     bool has_second_moment = false;
-    AggChunkRec *d_agg_chunks = nullptr;  // pieces for launches that follow the device-side decision
-    AggChunkRec *d_agg_fine = nullptr;    // 256-element pieces: for launches that are expected to work
-    int n_agg_fine = 0;
-    AggChunkRec *d_ga_chunks = nullptr;   // table of the K-way gradient-aggregation kernel (predicated launches)
+    AggTable t_agg{};                     // pieces for aggregation launches that follow the device-side decision
+    AggTable t_fine{};                    // 256-element pieces, striped by XCD: for launches that are expected to work
+    AggTable t_ga{};                      // pieces of the decision-following gradient-aggregation launch
     AggTables agg{};
     float **d_agg_v = nullptr;            // device table behind agg.v (written when second moments are bound)
-    AggShape agg_shape = kAggCoarse;      // workgroup shape that goes with d_agg_chunks
-    AggShape ga_shape = kAggCoarse;       // workgroup shape that goes with d_ga_chunks
     bool nontemporal = true;              // streaming (non-temporal) loads and stores
 
     selsync_plan() = default;
@@ -387,13 +386,13 @@ int32_t enqueue_track(selsync_ctx *ctx, selsync_plan *plan, hipStream_t s, bool 
     ctx->tracked_delta = ctx->cfg.delta;
     ProfScope p(ctx, 1, s);
     if (from_sync) {
-        // partials of the one-pass synchronous step: a plain array, worker k's at [k * pieces, (k+1) * pieces)
+        // partials of the one-pass synchronous step (their own striped array)
         if (plan->n_sync_segs > 0) {
-            HIP_TRY(ctx, launch_reduce(plan->d_sync_partials, 0, plan->d_sync_segs, plan->n_sync_segs,
+            HIP_TRY(ctx, launch_reduce(plan->d_sync_partials, plan->sync_per, plan->d_sync_segs, plan->n_sync_segs,
                                        plan->d_sync_seg_sums, s));
             HIP_TRY(ctx, launch_track(ctx->td, plan->d_sync_seg_sums, 0, plan->d_sync_seg_begin, s));
         } else {
-            HIP_TRY(ctx, launch_track(ctx->td, plan->d_sync_partials, 0, plan->d_sync_begin, s));
+            HIP_TRY(ctx, launch_track(ctx->td, plan->d_sync_partials, plan->sync_per, plan->d_sync_begin, s));
         }
         return SELSYNC_OK;
     }
@@ -828,14 +827,22 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             });
         }
     }
-    if (agg_chunks.size() > (size_t)INT32_MAX || agg_fine.size() > (size_t)INT32_MAX ||
-        ga_chunks.size() > (size_t)INT32_MAX || (grads && agg_fine.size() * (size_t)K > (size_t)INT32_MAX))
+    if (agg_chunks.size() > (size_t)INT32_MAX || ga_chunks.size() > (size_t)INT32_MAX ||
+        (agg_fine.size() + 8) * (size_t)std::max(K, 1) > (size_t)INT32_MAX)
         return fail(ctx, SELSYNC_ERR_INVALID_ARG, "model too large for one plan");
 
-    // Partial sums of the one-pass synchronous step: worker k's sit at [k * np, (k+1) * np), piece order.
-    // Same two-level scheme as for the streaming kernel: fixed segments of kSegChunks partials that never
-    // cross a worker boundary once there are many.
+    // The 256-element table is stored in 8 stripes (piece p in slot (p % 8) * per8 + p / 8, padded with empty
+    // records): workgroup p of a launch runs on XCD p % 8, so each table line is fetched by one L2.
     const int np = (int)agg_fine.size();
+    const int per8 = (np + 7) / 8;
+    const int np_pad = 8 * per8;
+    std::vector<AggChunkRec> fine_striped((size_t)np_pad, AggChunkRec{0u, 0u, 0u});
+    for (int i = 0; i < np; ++i)
+        fine_striped[(size_t)(i & 7) * per8 + (i >> 3)] = agg_fine[i];
+
+    // Partial sums of the one-pass synchronous step: worker k's piece p is chunk k * np_pad + p of an array
+    // striped like the streaming kernel's (per = K * per8).  Same two-level scheme on top: fixed segments of
+    // kSegChunks consecutive chunks that never cross a worker boundary once there are many.
     std::vector<int32_t> sync_begin(K + 1, 0), sync_seg_begin(K + 1, 0), sync_tensor_begin((size_t)K * T + 1, 0);
     std::vector<int2> sync_segs;
     if (grads) {
@@ -848,17 +855,19 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
             for (; t_prev <= T; ++t_prev)
                 fine_begin[t_prev] = np;
         }
+        // worker k's chunks are [k * np_pad, k * np_pad + np); the few padding chunks behind them are never
+        // written and stay zero (they fall into the last tensor's range below, where they add nothing)
         for (int k = 0; k <= K; ++k)
-            sync_begin[k] = k * np;
+            sync_begin[k] = k * np_pad;
         for (int k = 0; k < K; ++k)
             for (int t = 0; t < T; ++t)
-                sync_tensor_begin[(size_t)k * T + t] = k * np + fine_begin[t];
-        sync_tensor_begin[(size_t)K * T] = K * np;
+                sync_tensor_begin[(size_t)k * T + t] = k * np_pad + fine_begin[t];
+        sync_tensor_begin[(size_t)K * T] = K * np_pad;
         if ((size_t)K * np > (size_t)kDirectChunkLimit) {
             for (int k = 0; k < K; ++k) {
                 sync_seg_begin[k] = (int32_t)sync_segs.size();
-                for (int32_t b0 = k * np; b0 < (k + 1) * np; b0 += kSegChunks)
-                    sync_segs.push_back(make_int2(b0, std::min<int32_t>(b0 + kSegChunks, (k + 1) * np)));
+                for (int32_t b0 = k * np_pad; b0 < k * np_pad + np; b0 += kSegChunks)
+                    sync_segs.push_back(make_int2(b0, std::min<int32_t>(b0 + kSegChunks, k * np_pad + np)));
             }
             sync_seg_begin[K] = (int32_t)sync_segs.size();
         }
@@ -877,11 +886,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->ivals = ivals;
     plan->n_upd_chunks = nchunks;
     plan->n_agg_chunks = (int)agg_chunks.size();
-    plan->n_agg_fine = (int)agg_fine.size();
     plan->n_ga_chunks = (int)ga_chunks.size();
-    // one-wave workgroups go with pieces of less than one coarse tile
-    plan->agg_shape = agg_chunk < kAggTileElems ? kAggFine : kAggCoarse;
-    plan->ga_shape = ga_chunk < kAggTileElems ? kAggFine : kAggCoarse;
     plan->nontemporal = nt != 0;
 
     // ---- one device allocation for every table
@@ -901,9 +906,9 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     const size_t o_tcb = take(tensor_chunk_begin.size() * sizeof(int32_t));
     const size_t o_tnorm = take((size_t)K * T * sizeof(double));
     const size_t o_aggc = take(agg_chunks.size() * sizeof(AggChunkRec));
-    const size_t o_aggf = take(agg_fine.size() * sizeof(AggChunkRec));
+    const size_t o_aggf = take(fine_striped.size() * sizeof(AggChunkRec));
     const size_t o_gac = take(ga_chunks.size() * sizeof(AggChunkRec));
-    const size_t o_spart = take(grads ? (size_t)K * np * sizeof(double) : 0);
+    const size_t o_spart = take(grads ? (size_t)K * np_pad * sizeof(double) : 0);
     const size_t o_sbegin = take(sync_begin.size() * sizeof(int32_t));
     const size_t o_ssegs = take(sync_segs.size() * sizeof(int2));
     const size_t o_ssegsum = take(sync_segs.size() * sizeof(double));
@@ -929,7 +934,7 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     put(o_segbegin, seg_begin.data(), seg_begin.size() * sizeof(int32_t));
     put(o_tcb, tensor_chunk_begin.data(), tensor_chunk_begin.size() * sizeof(int32_t));
     put(o_aggc, agg_chunks.data(), agg_chunks.size() * sizeof(AggChunkRec));
-    put(o_aggf, agg_fine.data(), agg_fine.size() * sizeof(AggChunkRec));
+    put(o_aggf, fine_striped.data(), fine_striped.size() * sizeof(AggChunkRec));
     put(o_gac, ga_chunks.data(), ga_chunks.size() * sizeof(AggChunkRec));
     put(o_sbegin, sync_begin.data(), sync_begin.size() * sizeof(int32_t));
     put(o_ssegs, sync_segs.data(), sync_segs.size() * sizeof(int2));
@@ -966,10 +971,19 @@ int32_t plan_create_impl(selsync_ctx *ctx, const selsync_tensor_list *grads, con
     plan->d_seg_begin = reinterpret_cast<int32_t *>(b + o_segbegin);
     plan->d_tensor_chunk_begin = reinterpret_cast<int32_t *>(b + o_tcb);
     plan->d_tensor_norms = reinterpret_cast<double *>(b + o_tnorm);
-    plan->d_agg_chunks = reinterpret_cast<AggChunkRec *>(b + o_aggc);
-    plan->d_agg_fine = reinterpret_cast<AggChunkRec *>(b + o_aggf);
-    plan->d_ga_chunks = reinterpret_cast<AggChunkRec *>(b + o_gac);
+    // one-wave workgroups go with pieces of less than one coarse tile
+    plan->t_agg.recs = reinterpret_cast<AggChunkRec *>(b + o_aggc);
+    plan->t_agg.nslots = (int)agg_chunks.size();
+    plan->t_agg.shape = agg_chunk < kAggTileElems ? kAggFine : kAggCoarse;
+    plan->t_fine.recs = reinterpret_cast<AggChunkRec *>(b + o_aggf);
+    plan->t_fine.nslots = np_pad;
+    plan->t_fine.per8 = per8;
+    plan->t_fine.shape = kAggFine;
+    plan->t_ga.recs = reinterpret_cast<AggChunkRec *>(b + o_gac);
+    plan->t_ga.nslots = (int)ga_chunks.size();
+    plan->t_ga.shape = ga_chunk < kAggTileElems ? kAggFine : kAggCoarse;
     plan->d_sync_partials = reinterpret_cast<double *>(b + o_spart);
+    plan->sync_per = K * per8;
     plan->d_sync_begin = reinterpret_cast<int32_t *>(b + o_sbegin);
     plan->n_sync_segs = (int)sync_segs.size();
     plan->d_sync_segs = reinterpret_cast<int2 *>(b + o_ssegs);
@@ -1086,12 +1100,12 @@ int32_t enqueue_aggregate(selsync_ctx *ctx, selsync_plan *plan, int mode, hipStr
     // whatever the host expects, so a launch recorded into a graph stays correct when the threshold
     // changes between replays.  The expectation only selects the table and workgroup shape.
     if (mode == 1 || expect_sync(ctx)) {
-        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
-                                      &ctx->td.out->sync, mode, plan->nontemporal, s));
+        HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->t_fine, plan->agg, plan->K, &ctx->td.out->sync, mode,
+                                      plan->nontemporal, s));
         return SELSYNC_OK;
     }
-    HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->d_agg_chunks, plan->n_agg_chunks, plan->agg_shape, plan->agg,
-                                  plan->K, &ctx->td.out->sync, mode, plan->nontemporal, s));
+    HIP_TRY(ctx, launch_aggregate(plan->mixed, plan->t_agg, plan->agg, plan->K, &ctx->td.out->sync, mode,
+                                  plan->nontemporal, s));
     return SELSYNC_OK;
 }
 }  // namespace
@@ -1133,8 +1147,8 @@ int32_t enqueue_sync_step(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a
 {
     {
         ProfScope p(ctx, 0, s);
-        HIP_TRY(ctx, launch_sync_step(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, plan->agg,
-                                      plan->K, a, plan->d_sync_partials, plan->nontemporal, s));
+        HIP_TRY(ctx, launch_sync_step(plan->mixed, plan->has_momenta, plan->t_fine, plan->agg, plan->K, a,
+                                      plan->d_sync_partials, plan->nontemporal, s));
     }
     ctx->local_steps += 1;
     return enqueue_track(ctx, plan, s, true);
@@ -1395,9 +1409,8 @@ int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a
         // it say "local", applies every worker's own gradient itself: right under any decision, also when a
         // recorded launch is replayed after the threshold has changed.
         ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_agg_fine, plan->n_agg_fine, kAggFine,
-                                      plan->agg, plan->K, &ctx->td.out->sync, mode == 1 ? kGaAlways : kGaSyncOrLocal, a,
-                                      plan->nontemporal, s));
+        HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->t_fine, plan->agg, plan->K,
+                                      &ctx->td.out->sync, mode == 1 ? kGaAlways : kGaSyncOrLocal, a, plan->nontemporal, s));
         return SELSYNC_OK;
     }
     // Two launches that both follow the device-side decision word, of which exactly one works: on "local"
@@ -1407,8 +1420,8 @@ int32_t enqueue_ga_update(selsync_ctx *ctx, selsync_plan *plan, const SgdArgs &a
         HIP_TRY(ctx, launch_stream(kUpdateOnly, plan->mixed, plan->tab, a, plan->nontemporal, s, &ctx->td.out->sync, 0));
     }
     ProfScope p(ctx, 2, s);
-    HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape,
-                                  plan->agg, plan->K, &ctx->td.out->sync, kGaSyncOnly, a, plan->nontemporal, s));
+    HIP_TRY(ctx, launch_update_ga(plan->mixed, plan->has_momenta, plan->t_ga, plan->agg, plan->K, &ctx->td.out->sync,
+                                  kGaSyncOnly, a, plan->nontemporal, s));
     return SELSYNC_OK;
 }
 
@@ -1417,9 +1430,8 @@ int32_t enqueue_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const AdamA
 {
     if (mode == 1 || expect_sync(ctx)) {
         ProfScope p(ctx, 2, s);
-        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_agg_fine, plan->n_agg_fine, kAggFine, plan->agg, plan->K,
-                                           &ctx->td.out->sync, mode == 1 ? kGaAlways : kGaSyncOrLocal, a,
-                                           plan->nontemporal, s));
+        HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->t_fine, plan->agg, plan->K, &ctx->td.out->sync,
+                                           mode == 1 ? kGaAlways : kGaSyncOrLocal, a, plan->nontemporal, s));
         return SELSYNC_OK;
     }
     {
@@ -1427,8 +1439,8 @@ int32_t enqueue_ga_update_adam(selsync_ctx *ctx, selsync_plan *plan, const AdamA
         HIP_TRY(ctx, launch_stream_adam(false, plan->mixed, plan->tab, a, plan->nontemporal, s, &ctx->td.out->sync, 0));
     }
     ProfScope p(ctx, 2, s);
-    HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->d_ga_chunks, plan->n_ga_chunks, plan->ga_shape, plan->agg,
-                                       plan->K, &ctx->td.out->sync, kGaSyncOnly, a, plan->nontemporal, s));
+    HIP_TRY(ctx, launch_update_ga_adam(plan->mixed, plan->t_ga, plan->agg, plan->K, &ctx->td.out->sync, kGaSyncOnly, a,
+                                       plan->nontemporal, s));
     return SELSYNC_OK;
 }
 }  // namespace
@@ -1548,7 +1560,8 @@ extern "C" int32_t selsync_read_tensor_norms(selsync_ctx *ctx, selsync_plan *pla
         return SELSYNC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (plan->partials_from_sync)
-        HIP_TRY(ctx, launch_tensor_norms(plan->d_sync_partials, 0, plan->d_sync_tensor_begin, n, plan->d_tensor_norms, s));
+        HIP_TRY(ctx, launch_tensor_norms(plan->d_sync_partials, plan->sync_per, plan->d_sync_tensor_begin, n,
+                                         plan->d_tensor_norms, s));
     else
         HIP_TRY(ctx, launch_tensor_norms(plan->tab.partials, plan->tab.per, plan->d_tensor_chunk_begin, n,
                                          plan->d_tensor_norms, s));

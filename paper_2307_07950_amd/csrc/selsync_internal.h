@@ -120,6 +120,15 @@ struct SgdArgs {
 //               shape with the highest bandwidth when the launch does work.
 enum AggShape { kAggCoarse = 0, kAggFine = 1 };
 
+// One table of the K-way kernels.  per8 > 0: 8 stripes of per8 records, piece p in slot
+// (p % 8) * per8 + p / 8 (padding records hold n = 0) and nslots = 8 * per8; per8 = 0: plain.
+struct AggTable {
+    const AggChunkRec *recs = nullptr;
+    int nslots = 0;            // grid size of a launch over the table
+    int per8 = 0;
+    AggShape shape = kAggCoarse;
+};
+
 // Geometry of a plan's chunk table (see chunk_slot).
 struct StreamTable {
     const TensorRec *recs = nullptr;
@@ -183,8 +192,8 @@ hipError_t launch_reduce(const double *partials, int slot_per, const int2 *segs,
 // chunk_slot(., slot_per)) or per-segment ones (slot_per = 0).
 hipError_t launch_track(const TrackerDev &td, const double *values, int slot_per, const int32_t *begin, hipStream_t s);
 
-hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
-                            int K, const int32_t *sync_flag, int mode, bool nontemporal, hipStream_t s);
+hipError_t launch_aggregate(bool mixed, const AggTable &t, const AggTables &tabs, int K, const int32_t *sync_flag,
+                            int mode, bool nontemporal, hipStream_t s);
 
 // out[i] = sum of the partials of chunks range_begin[i] .. range_begin[i+1] - 1, one workgroup per range.
 hipError_t launch_tensor_norms(const double *partials, int slot_per, const int32_t *range_begin, int nranges,
@@ -197,19 +206,18 @@ enum GaMode { kGaSyncOnly = 0, kGaAlways = 1, kGaSyncOrLocal = 2 };
 // mean gradient to its own parameters and optimiser state; on "local" the launch exits
 // (kGaSyncOnly: the caller runs the plain local update in a launch of its own) or applies every
 // worker's own gradient itself (kGaSyncOrLocal).
-hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggChunkRec *chunks, int nchunks, AggShape shape,
-                            const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd,
-                            bool nontemporal, hipStream_t s);
+hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggTable &t, const AggTables &tabs, int K,
+                            const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal, hipStream_t s);
 // ... with Adam as the update (first and second moment buffers per worker).
-hipError_t launch_update_ga_adam(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape,
-                                 const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const AdamArgs &a,
-                                 bool nontemporal, hipStream_t s);
+hipError_t launch_update_ga_adam(bool mixed, const AggTable &t, const AggTables &tabs, int K, const int32_t *sync_flag,
+                                 int mode, const AdamArgs &a, bool nontemporal, hipStream_t s);
 
-// One whole synchronous iteration in one pass over 256-element pieces of all K workers: per-worker
-// squared-gradient partials (partials[k * npieces + piece]), local update, mean of the updated
-// parameters into every replica and the global model.
-hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggChunkRec *pieces, int npieces, const AggTables &tabs,
-                            int K, const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s);
+// One whole synchronous iteration in one pass over the striped table of 256-element pieces: per-worker
+// squared-gradient partials (worker k's piece p is "chunk" k * nslots + p of a partial array striped with
+// per = K * per8, see chunk_slot), local update, mean of the updated parameters into every replica and the
+// global model.
+hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggTable &t, const AggTables &tabs, int K,
+                            const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s);
 
 // out[p] = partition_index(D, N, n, scheme, p) for p < count (device array).
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

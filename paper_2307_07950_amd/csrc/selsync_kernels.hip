@@ -708,18 +708,27 @@ __device__ __forceinline__ float finish_mean(double s, int K, double invK, int p
     return (float)mean;
 }
 
+// Record of the piece that workgroup b works on.  per8 > 0: the table is stored as 8 stripes of per8
+// records and piece b sits in stripe b % 8 -- the XCD that workgroup b runs on -- so every table line
+// is fetched by one L2 instead of eight while pieces are still dispatched in model order (padding
+// records have n = 0).  per8 = 0: plain table.
+__device__ __forceinline__ int agg_slot(uint32_t b, int per8)
+{
+    return per8 > 0 ? (int)(b & 7u) * per8 + (int)(b >> 3) : (int)b;
+}
+
 // One workgroup per piece of the aggregation table (one-shot grid).  With mode 0 the launch
 // follows the device-side decision: every workgroup reads it and exits at once on "local".
 template <int BLOCK, int U, int KC, bool MIXED, bool NT>
-__global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restrict__ chunks, AggTables tabs, int K,
-                                                     double invK, int pow2, const int32_t *__restrict__ sync_flag,
-                                                     int mode)
+__global__ __launch_bounds__(BLOCK) void k_aggregate(const AggChunkRec *__restrict__ chunks, int per8, AggTables tabs,
+                                                     int K, double invK, int pow2,
+                                                     const int32_t *__restrict__ sync_flag, int mode)
 {
     if (mode == 0 && *sync_flag == 0)
         return;
     const uint32_t tid = threadIdx.x;
     {
-        const AggChunkRec ch = chunks[blockIdx.x];
+        const AggChunkRec ch = chunks[agg_slot(blockIdx.x, per8)];
         const uint32_t n = ch.n_flags & kChunkCountMask;
         float *const *wtab = tabs.w + (size_t)ch.t * K;
         uint16_t *const *ctab = MIXED ? tabs.lowp + (size_t)ch.t * K : nullptr;
@@ -904,8 +913,8 @@ __device__ __forceinline__ f32x4 mean_grad4(const f32x4 *g, int K, float gs, dou
 //                     (one launch serves both decisions: for steps that are expected to synchronise).
 // K compile-time (KC > 0) keeps all loads of a vector in flight.
 template <class OPT, int BLOCK, int KC, bool MIXED, bool NT>
-__global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, AggTables tabs, int K,
-                                                     double invK, int pow2,
+__global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restrict__ chunks, int per8, AggTables tabs,
+                                                     int K, double invK, int pow2,
                                                      const int32_t *__restrict__ sync_flag, int mode,
                                                      typename OPT::Args a)
 {
@@ -918,7 +927,7 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
     const uint32_t tid = threadIdx.x;
     double unused = 0.0;
     {
-        const AggChunkRec ch = chunks[blockIdx.x];
+        const AggChunkRec ch = chunks[agg_slot(blockIdx.x, per8)];
         const uint32_t n = ch.n_flags & kChunkCountMask;
         const size_t row = (size_t)ch.t * K;
         uint32_t done = 0;   // elements covered by the 128-bit body [head, head + done)
@@ -1034,17 +1043,20 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
 // 20*K + 4 bytes per parameter instead of the 28*K + 4 of update pass + aggregation pass.
 // Arithmetic, rounding sequence and sum orders are those of k_stream and k_aggregate, so
 // the tensors are bit-identical to the two-pass sequence.  Per (worker, piece) it leaves one
-// fp64 partial at partials[k * npieces + piece], formed in the order k_stream uses for a
-// chunk (vector body, peeled head, ragged tail; DPP wavefront sum).
+// fp64 partial, formed in the order k_stream uses for a chunk (vector body, peeled head, ragged
+// tail; DPP wavefront sum).  The partials are striped by XCD like the table: with worker k's
+// pieces numbered c = k * 8 * per8 + piece, partial c sits at (c % 8) * (K * per8) + c / 8, so the
+// eight-byte results of one XCD's wavefronts share cache lines with each other only.
 template <class OPT, int KC, bool MIXED, bool NT>
-__global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict__ chunks, int npieces, AggTables tabs,
+__global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict__ chunks, int per8, AggTables tabs,
                                                   int K, double invK, int pow2, typename OPT::Args a,
                                                   double *__restrict__ partials)
 {
     constexpr int KM = KC > 0 ? KC : 1;
     const uint32_t tid = threadIdx.x;
-    const int piece = blockIdx.x;
-    const AggChunkRec ch = chunks[piece];
+    const AggChunkRec ch = chunks[agg_slot(blockIdx.x, per8)];
+    // slot of worker 0's partial for this piece; worker k's lies k * per8 further on
+    const size_t pslot = (size_t)(blockIdx.x & 7u) * ((size_t)K * per8) + (blockIdx.x >> 3);
     const uint32_t n = ch.n_flags & kChunkCountMask;
     const size_t row = (size_t)ch.t * K;
     SELSYNC_GLOBAL float *gl = as_global<float>(tabs.global[ch.t]);
@@ -1147,7 +1159,7 @@ __global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict_
         for (int k = 0; k < KC; ++k) {
             const double x = wave_sum_to_last_lane(acc[k]);
             if (tid == 63 && n > 0)
-                partials[(size_t)k * npieces + piece] = x;
+                partials[pslot + (size_t)k * per8] = x;
         }
     } else {
         // Any other K: the same arithmetic with one worker in registers at a time.  Lane `tid` owns vector
@@ -1202,7 +1214,7 @@ __global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict_
             }
             const double x = wave_sum_to_last_lane(acc);
             if (tid == 63 && n > 0)
-                partials[(size_t)k * npieces + piece] = x;
+                partials[pslot + (size_t)k * per8] = x;
         }
         f32x4 r = 0.f;
         u32x2 h = 0u;
@@ -1302,30 +1314,29 @@ hipError_t launch_stream_o(StreamMode mode, bool mixed, const StreamTable &tab, 
 // (few, large workgroups: cheap to dispatch when they only read the decision and exit), kAggFine for
 // launches over 256-element pieces (one wavefront, one 128-bit access per lane and stream).
 template <int KC, bool MIXED, bool NT>
-hipError_t launch_agg_t(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                        const int32_t *flag, int mode, hipStream_t s)
+hipError_t launch_agg_t(const AggTable &t, const AggTables &tabs, int K, const int32_t *flag, int mode, hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
-    if (shape == kAggFine)
-        hipLaunchKernelGGL((k_aggregate<64, 1, KC, MIXED, NT>), dim3(nchunks), dim3(64), 0, s, chunks, tabs, K,
+    if (t.shape == kAggFine)
+        hipLaunchKernelGGL((k_aggregate<64, 1, KC, MIXED, NT>), dim3(t.nslots), dim3(64), 0, s, t.recs, t.per8, tabs, K,
                            1.0 / (double)K, pow2, flag, mode);
     else
-        hipLaunchKernelGGL((k_aggregate<256, 4, KC, MIXED, NT>), dim3(nchunks), dim3(256), 0, s, chunks, tabs, K,
-                           1.0 / (double)K, pow2, flag, mode);
+        hipLaunchKernelGGL((k_aggregate<256, 4, KC, MIXED, NT>), dim3(t.nslots), dim3(256), 0, s, t.recs, t.per8, tabs,
+                           K, 1.0 / (double)K, pow2, flag, mode);
     return hipGetLastError();
 }
 
 template <class OPT, int KC, bool MIXED, bool NT>
-hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const typename OPT::Args &args, hipStream_t s)
+hipError_t launch_ga_t(const AggTable &t, const AggTables &tabs, int K, const int32_t *flag, int mode,
+                       const typename OPT::Args &args, hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
-    if (shape == kAggFine)
-        hipLaunchKernelGGL((k_update_ga<OPT, 64, KC, MIXED, NT>), dim3(nchunks), dim3(64), 0, s, chunks, tabs, K,
-                           1.0 / (double)K, pow2, flag, mode, args);
+    if (t.shape == kAggFine)
+        hipLaunchKernelGGL((k_update_ga<OPT, 64, KC, MIXED, NT>), dim3(t.nslots), dim3(64), 0, s, t.recs, t.per8, tabs,
+                           K, 1.0 / (double)K, pow2, flag, mode, args);
     else
-        hipLaunchKernelGGL((k_update_ga<OPT, 256, KC, MIXED, NT>), dim3(nchunks), dim3(256), 0, s, chunks, tabs, K,
-                           1.0 / (double)K, pow2, flag, mode, args);
+        hipLaunchKernelGGL((k_update_ga<OPT, 256, KC, MIXED, NT>), dim3(t.nslots), dim3(256), 0, s, t.recs, t.per8, tabs,
+                           K, 1.0 / (double)K, pow2, flag, mode, args);
     return hipGetLastError();
 }
 
@@ -1341,64 +1352,63 @@ hipError_t launch_ga_t(const AggChunkRec *chunks, int nchunks, AggShape shape, c
     }
 
 template <bool MIXED, bool NT>
-hipError_t launch_agg_k(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                        const int32_t *flag, int mode, hipStream_t s)
+hipError_t launch_agg_k(const AggTable &t, const AggTables &tabs, int K, const int32_t *flag, int mode, hipStream_t s)
 {
-#define SELSYNC_AGG_CALL(KC) launch_agg_t<KC, MIXED, NT>(chunks, nchunks, shape, tabs, K, flag, mode, s)
+#define SELSYNC_AGG_CALL(KC) launch_agg_t<KC, MIXED, NT>(t, tabs, K, flag, mode, s)
     SELSYNC_SWITCH_K(K, SELSYNC_AGG_CALL)
 #undef SELSYNC_AGG_CALL
 }
 
 template <class OPT, bool MIXED, bool NT>
-hipError_t launch_ga_k(const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const typename OPT::Args &args, hipStream_t s)
+hipError_t launch_ga_k(const AggTable &t, const AggTables &tabs, int K, const int32_t *flag, int mode,
+                       const typename OPT::Args &args, hipStream_t s)
 {
-#define SELSYNC_GA_CALL(KC) launch_ga_t<OPT, KC, MIXED, NT>(chunks, nchunks, shape, tabs, K, flag, mode, args, s)
+#define SELSYNC_GA_CALL(KC) launch_ga_t<OPT, KC, MIXED, NT>(t, tabs, K, flag, mode, args, s)
     SELSYNC_SWITCH_K(K, SELSYNC_GA_CALL)
 #undef SELSYNC_GA_CALL
 }
 
 template <class OPT>
-hipError_t launch_ga_o(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs, int K,
-                       const int32_t *flag, int mode, const typename OPT::Args &args, bool nontemporal, hipStream_t s)
+hipError_t launch_ga_o(bool mixed, const AggTable &t, const AggTables &tabs, int K, const int32_t *flag, int mode,
+                       const typename OPT::Args &args, bool nontemporal, hipStream_t s)
 {
-    if (nchunks <= 0)
+    if (t.nslots <= 0)
         return hipSuccess;
     if (mixed)
-        return nontemporal ? launch_ga_k<OPT, true, true>(chunks, nchunks, shape, tabs, K, flag, mode, args, s)
-                           : launch_ga_k<OPT, true, false>(chunks, nchunks, shape, tabs, K, flag, mode, args, s);
-    return nontemporal ? launch_ga_k<OPT, false, true>(chunks, nchunks, shape, tabs, K, flag, mode, args, s)
-                       : launch_ga_k<OPT, false, false>(chunks, nchunks, shape, tabs, K, flag, mode, args, s);
+        return nontemporal ? launch_ga_k<OPT, true, true>(t, tabs, K, flag, mode, args, s)
+                           : launch_ga_k<OPT, true, false>(t, tabs, K, flag, mode, args, s);
+    return nontemporal ? launch_ga_k<OPT, false, true>(t, tabs, K, flag, mode, args, s)
+                       : launch_ga_k<OPT, false, false>(t, tabs, K, flag, mode, args, s);
 }
 
 template <class OPT, int KC, bool MIXED, bool NT>
-hipError_t launch_sync_t(const AggChunkRec *pieces, int npieces, const AggTables &tabs, int K, const SgdArgs &sgd,
-                         double *partials, hipStream_t s)
+hipError_t launch_sync_t(const AggTable &t, const AggTables &tabs, int K, const SgdArgs &sgd, double *partials,
+                         hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
-    hipLaunchKernelGGL((k_sync_step<OPT, KC, MIXED, NT>), dim3(npieces), dim3(64), 0, s, pieces, npieces, tabs, K,
+    hipLaunchKernelGGL((k_sync_step<OPT, KC, MIXED, NT>), dim3(t.nslots), dim3(64), 0, s, t.recs, t.per8, tabs, K,
                        1.0 / (double)K, pow2, sgd, partials);
     return hipGetLastError();
 }
 
 template <class OPT, bool MIXED, bool NT>
-hipError_t launch_sync_k(const AggChunkRec *pieces, int npieces, const AggTables &tabs, int K, const SgdArgs &sgd,
-                         double *partials, hipStream_t s)
+hipError_t launch_sync_k(const AggTable &t, const AggTables &tabs, int K, const SgdArgs &sgd, double *partials,
+                         hipStream_t s)
 {
-#define SELSYNC_SYNC_CALL(KC) launch_sync_t<OPT, KC, MIXED, NT>(pieces, npieces, tabs, K, sgd, partials, s)
+#define SELSYNC_SYNC_CALL(KC) launch_sync_t<OPT, KC, MIXED, NT>(t, tabs, K, sgd, partials, s)
     SELSYNC_SWITCH_K(K, SELSYNC_SYNC_CALL)
 #undef SELSYNC_SYNC_CALL
 }
 
 template <class OPT>
-hipError_t launch_sync_o(bool mixed, const AggChunkRec *pieces, int npieces, const AggTables &tabs, int K,
-                         const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s)
+hipError_t launch_sync_o(bool mixed, const AggTable &t, const AggTables &tabs, int K, const SgdArgs &sgd,
+                         double *partials, bool nontemporal, hipStream_t s)
 {
     if (mixed)
-        return nontemporal ? launch_sync_k<OPT, true, true>(pieces, npieces, tabs, K, sgd, partials, s)
-                           : launch_sync_k<OPT, true, false>(pieces, npieces, tabs, K, sgd, partials, s);
-    return nontemporal ? launch_sync_k<OPT, false, true>(pieces, npieces, tabs, K, sgd, partials, s)
-                       : launch_sync_k<OPT, false, false>(pieces, npieces, tabs, K, sgd, partials, s);
+        return nontemporal ? launch_sync_k<OPT, true, true>(t, tabs, K, sgd, partials, s)
+                           : launch_sync_k<OPT, true, false>(t, tabs, K, sgd, partials, s);
+    return nontemporal ? launch_sync_k<OPT, false, true>(t, tabs, K, sgd, partials, s)
+                       : launch_sync_k<OPT, false, false>(t, tabs, K, sgd, partials, s);
 }
 
 }  // namespace
@@ -1444,42 +1454,40 @@ hipError_t launch_track(const TrackerDev &td, const double *values, int slot_per
     return hipGetLastError();
 }
 
-hipError_t launch_aggregate(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape, const AggTables &tabs,
-                            int K, const int32_t *sync_flag, int mode, bool nontemporal, hipStream_t s)
+hipError_t launch_aggregate(bool mixed, const AggTable &t, const AggTables &tabs, int K, const int32_t *sync_flag,
+                            int mode, bool nontemporal, hipStream_t s)
 {
-    if (nchunks <= 0)
+    if (t.nslots <= 0)
         return hipSuccess;
     if (mixed)
-        return nontemporal ? launch_agg_k<true, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s)
-                           : launch_agg_k<true, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s);
-    return nontemporal ? launch_agg_k<false, true>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s)
-                       : launch_agg_k<false, false>(chunks, nchunks, shape, tabs, K, sync_flag, mode, s);
+        return nontemporal ? launch_agg_k<true, true>(t, tabs, K, sync_flag, mode, s)
+                           : launch_agg_k<true, false>(t, tabs, K, sync_flag, mode, s);
+    return nontemporal ? launch_agg_k<false, true>(t, tabs, K, sync_flag, mode, s)
+                       : launch_agg_k<false, false>(t, tabs, K, sync_flag, mode, s);
 }
 
-hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggChunkRec *chunks, int nchunks, AggShape shape,
-                            const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const SgdArgs &sgd,
-                            bool nontemporal, hipStream_t s)
+hipError_t launch_update_ga(bool mixed, bool has_momentum, const AggTable &t, const AggTables &tabs, int K,
+                            const int32_t *sync_flag, int mode, const SgdArgs &sgd, bool nontemporal, hipStream_t s)
 {
     if (!has_momentum)
-        return launch_ga_o<PlainSgdOpt>(mixed, chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, nontemporal, s);
-    return launch_ga_o<SgdOpt>(mixed, chunks, nchunks, shape, tabs, K, sync_flag, mode, sgd, nontemporal, s);
+        return launch_ga_o<PlainSgdOpt>(mixed, t, tabs, K, sync_flag, mode, sgd, nontemporal, s);
+    return launch_ga_o<SgdOpt>(mixed, t, tabs, K, sync_flag, mode, sgd, nontemporal, s);
 }
 
-hipError_t launch_update_ga_adam(bool mixed, const AggChunkRec *chunks, int nchunks, AggShape shape,
-                                 const AggTables &tabs, int K, const int32_t *sync_flag, int mode, const AdamArgs &a,
-                                 bool nontemporal, hipStream_t s)
+hipError_t launch_update_ga_adam(bool mixed, const AggTable &t, const AggTables &tabs, int K, const int32_t *sync_flag,
+                                 int mode, const AdamArgs &a, bool nontemporal, hipStream_t s)
 {
-    return launch_ga_o<AdamOpt>(mixed, chunks, nchunks, shape, tabs, K, sync_flag, mode, a, nontemporal, s);
+    return launch_ga_o<AdamOpt>(mixed, t, tabs, K, sync_flag, mode, a, nontemporal, s);
 }
 
-hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggChunkRec *pieces, int npieces, const AggTables &tabs,
-                            int K, const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s)
+hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggTable &t, const AggTables &tabs, int K,
+                            const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s)
 {
-    if (npieces <= 0)
+    if (t.nslots <= 0)
         return hipSuccess;
     if (!has_momentum)
-        return launch_sync_o<PlainSgdOpt>(mixed, pieces, npieces, tabs, K, sgd, partials, nontemporal, s);
-    return launch_sync_o<SgdOpt>(mixed, pieces, npieces, tabs, K, sgd, partials, nontemporal, s);
+        return launch_sync_o<PlainSgdOpt>(mixed, t, tabs, K, sgd, partials, nontemporal, s);
+    return launch_sync_o<SgdOpt>(mixed, t, tabs, K, sgd, partials, nontemporal, s);
 }
 
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,
