@@ -354,8 +354,8 @@ void selsync_oracle_average_grads_bf16(const uint16_t *const *grads, int K, floa
 
 /*
  * One worker's RelativeGradChange state: the last <= window raw values of ||g||^2
- * (the function "calculates and stores" the value every iteration) and the previous
- * smoothed value.
+ * (one is computed and kept per iteration: Alg. 1 line 8 and its walkthrough in
+ * Sec. III-E) and the previous smoothed value.
  */
 typedef struct selsync_oracle_tracker {
     int window;
