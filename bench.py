@@ -419,6 +419,8 @@ def main():
         b_local, b_sync = b_local + K * (2 if wl.mixed_bf16 else 4) * P, 0
     if args.variant == "adam":
         b_local += K * 8 * P                 # second-moment buffer read and written
+        if wl.delta == 0.0:                  # one pass (see above): the mean is written once more, nothing re-read
+            b_sync = (6 if wl.mixed_bf16 else 4) * P
     if args.variant == "plain":
         b_local -= K * 8 * P                 # no momentum buffer read or written
     total_bytes = args.steps * b_local + n_sync * b_sync

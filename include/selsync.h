@@ -326,6 +326,14 @@ int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_ad
                           int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                           int32_t *sync_out);
 
+/* selsync_step_bsp with Adam as the update: one pass, unconditional aggregation of the updated
+ * parameters, moment buffers stay per worker (28*K + 4 instead of 36*K + 4 bytes per parameter).
+ * selsync_step_adam takes this path when the context's threshold is 0 and `stream` is not being
+ * captured. */
+int32_t selsync_step_bsp_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
+                              int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                              int32_t *sync_out);
+
 /* ---- variant: gradient aggregation (Sec. III-C) ------------------------------------------ */
 
 /*

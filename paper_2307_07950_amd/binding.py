@@ -106,6 +106,7 @@ PROTOTYPES = {
     "selsync_plan_bind_second_moment": (_i32, [_vp, _tl]),
     "selsync_local_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp]),
     "selsync_step_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
+    "selsync_step_bsp_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_ga_update": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _i32, _vp]),
     "selsync_step_ga": (_i32, [_vp, _vp, ctypes.POINTER(selsync_sgd), _vp, _i32, _dp, _dp, _ip, _ip]),
     "selsync_ga_update_adam": (_i32, [_vp, _vp, ctypes.POINTER(selsync_adam), _i32, _vp]),
@@ -374,6 +375,15 @@ class SelSync:
         n, d, f, s = self._outs()
         rc = self._check(selsync_step_adam(self._h, plan._h, ctypes.byref(ad), _vp(_stream_handle(stream)),
                                            int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
+        return self._decision(rc, n, d, f, s) if blocking else None
+
+    def step_bsp_adam(self, plan: Plan, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                      weight_decay: float = 0.0, grad_scale: float = 1.0, step: int = 0, blocking: bool = False,
+                      stream=None):
+        ad = selsync_adam(beta1, beta2, lr, eps, weight_decay, grad_scale, step)
+        n, d, f, s = self._outs()
+        rc = self._check(selsync_step_bsp_adam(self._h, plan._h, ctypes.byref(ad), _vp(_stream_handle(stream)),
+                                               int(blocking), n, d, f, ctypes.byref(s)), allow_warn=True)
         return self._decision(rc, n, d, f, s) if blocking else None
 
     # -- variant: gradient aggregation

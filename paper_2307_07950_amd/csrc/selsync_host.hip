@@ -1369,6 +1369,39 @@ extern "C" int32_t selsync_local_step_adam(selsync_ctx *ctx, selsync_plan *plan,
     return SELSYNC_OK;
 }
 
+namespace {
+// One pass with Adam as the update: norm partials + Adam step of every worker + unconditional mean of the
+// updated parameters (moment buffers stay per worker), then the tracker over that pass's partials.
+int32_t enqueue_sync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const AdamArgs &a, hipStream_t s)
+{
+    {
+        ProfScope p(ctx, 0, s);
+        HIP_TRY(ctx, launch_sync_step_adam(plan->mixed, plan->t_fine, plan->agg, plan->K, a, plan->d_sync_partials,
+                                           plan->nontemporal, s));
+    }
+    ctx->local_steps += 1;
+    return enqueue_track(ctx, plan, s, true);
+}
+}  // namespace
+
+extern "C" int32_t selsync_step_bsp_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
+                                         int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
+                                         int32_t *sync_out)
+{
+    int32_t rc = check_plan(ctx, plan, true, true);
+    if (rc)
+        return rc;
+    AdamArgs a;
+    if ((rc = resolve_adam(ctx, plan, adam, &a)))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((rc = enqueue_sync_step_adam(ctx, plan, a, s)))
+        return rc;
+    if (blocking)
+        return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+    return SELSYNC_OK;
+}
+
 extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync_adam *adam, void *stream,
                                      int32_t blocking, double *norm_sq_out, double *delta_out, int32_t *flags_out,
                                      int32_t *sync_out)
@@ -1380,6 +1413,13 @@ extern "C" int32_t selsync_step_adam(selsync_ctx *ctx, selsync_plan *plan, const
     if ((rc = resolve_adam(ctx, plan, adam, &a)))
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (ctx->cfg.delta == 0.0 && !stream_is_capturing(s)) {      // every step synchronises: one pass (see selsync_step)
+        if ((rc = enqueue_sync_step_adam(ctx, plan, a, s)))
+            return rc;
+        if (blocking)
+            return fetch_decision(ctx, s, norm_sq_out, delta_out, flags_out, sync_out, nullptr);
+        return SELSYNC_OK;
+    }
     {
         ProfScope p(ctx, 0, s);
         HIP_TRY(ctx, launch_stream_adam(true, plan->mixed, plan->tab, a, plan->nontemporal, s));

@@ -218,6 +218,9 @@ hipError_t launch_update_ga_adam(bool mixed, const AggTable &t, const AggTables 
 // global model.
 hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggTable &t, const AggTables &tabs, int K,
                             const SgdArgs &sgd, double *partials, bool nontemporal, hipStream_t s);
+// ... with Adam as the update (second-moment buffers bound).
+hipError_t launch_sync_step_adam(bool mixed, const AggTable &t, const AggTables &tabs, int K, const AdamArgs &a,
+                                 double *partials, bool nontemporal, hipStream_t s);
 
 // out[p] = partition_index(D, N, n, scheme, p) for p < count (device array).
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

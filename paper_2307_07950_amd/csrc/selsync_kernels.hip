@@ -1040,7 +1040,8 @@ __global__ __launch_bounds__(BLOCK) void k_update_ga(const AggChunkRec *__restri
 // gradient (Alg. 1 line 8), applies each worker's local update (line 9), forms the mean of
 // the updated parameters in fp64 in worker order (lines 14-15) and writes it to every
 // replica and the global model, and each worker's new momentum to its buffer:
-// 20*K + 4 bytes per parameter instead of the 28*K + 4 of update pass + aggregation pass.
+// 20*K + 4 bytes per parameter instead of the 28*K + 4 of update pass + aggregation pass
+// (with Adam as the update: 28*K + 4 instead of 36*K + 4; the moment buffers stay per worker).
 // Arithmetic, rounding sequence and sum orders are those of k_stream and k_aggregate, so
 // the tensors are bit-identical to the two-pass sequence.  Per (worker, piece) it leaves one
 // fp64 partial, formed in the order k_stream uses for a chunk (vector body, peeled head, ragged
@@ -1069,34 +1070,40 @@ __global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict_
 
     if constexpr (KC > 0) {
         double acc[KM];
-        f32x4 gv[KM], wv[KM], mv[KM], unused = 0.f;
+        f32x4 gv[KM], wv[KM], mv[KM], vv[KM];
 #pragma unroll
         for (int k = 0; k < KC; ++k) {
             acc[k] = 0.0;
             gv[k] = 0.f;
             wv[k] = 0.f;
             mv[k] = 0.f;
+            vv[k] = 0.f;
             if (lane_vec) {
                 if (MIXED)
                     gv[k] = widen4(ld<NT>(as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + e0) + tid));
                 else
                     gv[k] = ld<NT>(as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + e0) + tid);
                 wv[k] = ld<NT>(as_global<const f32x4>(tabs.w[row + k] + e0) + tid);
-                if (OPT::kMomentum && !a.first)
+                if (OPT::kMomentum && !a.first) {
                     mv[k] = ld<NT>(as_global<const f32x4>(tabs.m[row + k] + e0) + tid);
+                    if (OPT::kSecondMoment)
+                        vv[k] = ld<NT>(as_global<const f32x4>(tabs.v[row + k] + e0) + tid);
+                }
             }
         }
         if (lane_vec) {
             double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
             for (int k = 0; k < KC; ++k) {
-                elem4<OPT, true, true>(gv[k], wv[k], mv[k], unused, a, acc[k]);
+                elem4<OPT, true, true>(gv[k], wv[k], mv[k], vv[k], a, acc[k]);
                 s0 += (double)wv[k].x;
                 s1 += (double)wv[k].y;
                 s2 += (double)wv[k].z;
                 s3 += (double)wv[k].w;
                 if (OPT::kMomentum)
                     st<NT>(as_global<f32x4>(tabs.m[row + k] + e0) + tid, mv[k]);
+                if (OPT::kSecondMoment)
+                    st<NT>(as_global<f32x4>(tabs.v[row + k] + e0) + tid, vv[k]);
             }
             f32x4 r;
             r.x = finish_mean(s0, KC, invK, pow2);
@@ -1131,12 +1138,17 @@ __global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict_
                     g = as_global<const float>(tabs.g[row + k])[e];
                 float w = as_global<const float>(tabs.w[row + k])[e];
                 float m = 0.f, v = 0.f;
-                if (OPT::kMomentum && !a.first)
+                if (OPT::kMomentum && !a.first) {
                     m = as_global<const float>(tabs.m[row + k])[e];
+                    if (OPT::kSecondMoment)
+                        v = as_global<const float>(tabs.v[row + k])[e];
+                }
                 OPT::template elem<true, true>(g, w, m, v, a, acc[k]);
                 s += (double)w;
                 if (OPT::kMomentum)
                     as_global<float>(tabs.m[row + k])[e] = m;
+                if (OPT::kSecondMoment)
+                    as_global<float>(tabs.v[row + k])[e] = v;
             }
             const float r = finish_mean(s, KC, invK, pow2);
             const uint16_t h = MIXED ? (uint16_t)bf16_bits(r) : (uint16_t)0;
@@ -1177,21 +1189,26 @@ __global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict_
         for (int k = 0; k < K; ++k) {
             double acc = 0.0;
             if (lane_vec) {
-                f32x4 gv, wv, mv = 0.f, unused = 0.f;
+                f32x4 gv, wv, mv = 0.f, vv = 0.f;
                 if (MIXED)
                     gv = widen4(ld<NT>(as_global<const u32x2>(static_cast<const uint16_t *>(tabs.g[row + k]) + e0) + tid));
                 else
                     gv = ld<NT>(as_global<const f32x4>(static_cast<const float *>(tabs.g[row + k]) + e0) + tid);
                 wv = ld<NT>(as_global<const f32x4>(tabs.w[row + k] + e0) + tid);
-                if (OPT::kMomentum && !a.first)
+                if (OPT::kMomentum && !a.first) {
                     mv = ld<NT>(as_global<const f32x4>(tabs.m[row + k] + e0) + tid);
-                elem4<OPT, true, true>(gv, wv, mv, unused, a, acc);
+                    if (OPT::kSecondMoment)
+                        vv = ld<NT>(as_global<const f32x4>(tabs.v[row + k] + e0) + tid);
+                }
+                elem4<OPT, true, true>(gv, wv, mv, vv, a, acc);
                 s0 += (double)wv.x;
                 s1 += (double)wv.y;
                 s2 += (double)wv.z;
                 s3 += (double)wv.w;
                 if (OPT::kMomentum)
                     st<NT>(as_global<f32x4>(tabs.m[row + k] + e0) + tid, mv);
+                if (OPT::kSecondMoment)
+                    st<NT>(as_global<f32x4>(tabs.v[row + k] + e0) + tid, vv);
             }
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
@@ -1204,12 +1221,17 @@ __global__ __launch_bounds__(64) void k_sync_step(const AggChunkRec *__restrict_
                         g = as_global<const float>(tabs.g[row + k])[e];
                     float w = as_global<const float>(tabs.w[row + k])[e];
                     float m = 0.f, v = 0.f;
-                    if (OPT::kMomentum && !a.first)
+                    if (OPT::kMomentum && !a.first) {
                         m = as_global<const float>(tabs.m[row + k])[e];
+                        if (OPT::kSecondMoment)
+                            v = as_global<const float>(tabs.v[row + k])[e];
+                    }
                     OPT::template elem<true, true>(g, w, m, v, a, acc);
                     ss[q] += (double)w;
                     if (OPT::kMomentum)
                         as_global<float>(tabs.m[row + k])[e] = m;
+                    if (OPT::kSecondMoment)
+                        as_global<float>(tabs.v[row + k])[e] = v;
                 }
             }
             const double x = wave_sum_to_last_lane(acc);
@@ -1382,7 +1404,7 @@ hipError_t launch_ga_o(bool mixed, const AggTable &t, const AggTables &tabs, int
 }
 
 template <class OPT, int KC, bool MIXED, bool NT>
-hipError_t launch_sync_t(const AggTable &t, const AggTables &tabs, int K, const SgdArgs &sgd, double *partials,
+hipError_t launch_sync_t(const AggTable &t, const AggTables &tabs, int K, const typename OPT::Args &sgd, double *partials,
                          hipStream_t s)
 {
     const int pow2 = (K & (K - 1)) == 0;
@@ -1392,7 +1414,7 @@ hipError_t launch_sync_t(const AggTable &t, const AggTables &tabs, int K, const 
 }
 
 template <class OPT, bool MIXED, bool NT>
-hipError_t launch_sync_k(const AggTable &t, const AggTables &tabs, int K, const SgdArgs &sgd, double *partials,
+hipError_t launch_sync_k(const AggTable &t, const AggTables &tabs, int K, const typename OPT::Args &sgd, double *partials,
                          hipStream_t s)
 {
 #define SELSYNC_SYNC_CALL(KC) launch_sync_t<OPT, KC, MIXED, NT>(t, tabs, K, sgd, partials, s)
@@ -1401,9 +1423,11 @@ hipError_t launch_sync_k(const AggTable &t, const AggTables &tabs, int K, const 
 }
 
 template <class OPT>
-hipError_t launch_sync_o(bool mixed, const AggTable &t, const AggTables &tabs, int K, const SgdArgs &sgd,
+hipError_t launch_sync_o(bool mixed, const AggTable &t, const AggTables &tabs, int K, const typename OPT::Args &sgd,
                          double *partials, bool nontemporal, hipStream_t s)
 {
+    if (t.nslots <= 0)
+        return hipSuccess;
     if (mixed)
         return nontemporal ? launch_sync_k<OPT, true, true>(t, tabs, K, sgd, partials, s)
                            : launch_sync_k<OPT, true, false>(t, tabs, K, sgd, partials, s);
@@ -1488,6 +1512,12 @@ hipError_t launch_sync_step(bool mixed, bool has_momentum, const AggTable &t, co
     if (!has_momentum)
         return launch_sync_o<PlainSgdOpt>(mixed, t, tabs, K, sgd, partials, nontemporal, s);
     return launch_sync_o<SgdOpt>(mixed, t, tabs, K, sgd, partials, nontemporal, s);
+}
+
+hipError_t launch_sync_step_adam(bool mixed, const AggTable &t, const AggTables &tabs, int K, const AdamArgs &a,
+                                 double *partials, bool nontemporal, hipStream_t s)
+{
+    return launch_sync_o<AdamOpt>(mixed, t, tabs, K, a, partials, nontemporal, s);
 }
 
 hipError_t launch_partition_order(int64_t D, int64_t N, int64_t n, int scheme, int64_t count, int64_t *out,

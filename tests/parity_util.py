@@ -264,6 +264,25 @@ class LockStep:
                                                                          "second moment[%d][%d]" % (k, i)))
         return dec, rec
 
+    def step_bsp_adam(self, slot: int, lr: float, b1: float, b2: float, eps: float, wd: float, gs: float = 1.0):
+        """One fully synchronous iteration with Adam as the update (unconditional aggregation) on both sides."""
+        t = self.steps_done + 1
+        dec = self.ctx.step_bsp_adam(self.plans[slot], lr, b1, b2, eps, wd, gs, step=t, blocking=True)
+        g = self.h_grads[slot]
+        rec = self.oracle.track(g, gs)
+        for k in range(self.K):
+            O.adam_update(self.h_w[k], self.h_m[k], self.h_v[k], g[k], lr, b1, b2, eps, wd, t, gs,
+                          None if not self.mixed else self.h_c[k])
+        self._check_decision(dec, rec)
+        self._oracle_average()
+        self.steps_done += 1
+        self.compare(after_sync=True)
+        for k in range(self.K):
+            for i in range(len(self.numel)):
+                self.worst_ulp = max(self.worst_ulp, assert_update_close(to_host(self.d_v[k][i]), self.h_v[k][i],
+                                                                         "second moment[%d][%d]" % (k, i)))
+        return dec, rec
+
     def step_ga(self, slot: int, lr: float, mu: float, wd: float, gs: float = 1.0, fused: bool = True,
                 nesterov: bool = False):
         """One iteration under gradient aggregation (Sec. III-C) on both sides."""

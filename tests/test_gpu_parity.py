@@ -727,6 +727,56 @@ def test_one_pass_synchronous_step_on_momentum_free_plans(B, mixed):
     ls.close()
 
 
+@pytest.mark.parametrize("K", [1, 3, 4, 8])
+@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("misalign,misalign_g", [(0, 0), (1, 1), (2, 3)])
+def test_one_pass_synchronous_step_with_adam_matches_oracle(B, K, mixed, misalign, misalign_g):
+    numel = [70001, 5, 4096, 0, 1023, 255]
+    ls = PU.LockStep(B, numel, K, delta=0.15, window=5, alpha=0.5, mixed=mixed, misalign=misalign,
+                     misalign_g=misalign_g, seed=84, tuning=dict(nontemporal=K % 2))
+    r = rng(840 + K)
+    for slot in range(3):
+        grads = []
+        for k in range(K):
+            gk = [(r.standard_normal(n) * 1e-2 * (1 + 2 * slot) * (1 + 0.1 * k)).astype(np.float32) for n in numel]
+            grads.append([W.round_to_bf16_bits(a) for a in gk] if mixed else gk)
+        ls.bind_grads(slot, grads)
+    ls.enable_adam()
+    flagged = 0
+    for t in range(6):
+        dec, rec = ls.step_bsp_adam([0, 1, 2, 2, 0, 1][t], 1e-3, 0.9, 0.999, 1e-8, [0.0, 1e-2][t % 2], [1.0, 0.7][t % 2])
+        flagged += rec.sync
+        for tt in range(len(numel)):
+            assert PU.to_host(ls.d_glob[tt]).tobytes() == ls.h_glob[tt].tobytes()
+    assert 0 < flagged < 6 and ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+    ls.close()
+
+
+def test_adam_step_at_threshold_zero_takes_the_one_pass_kernel_with_identical_results(B):
+    numel = [100003, 257, 65536]
+    K = 4
+    runs = []
+    for fused in (True, False):
+        ls = PU.LockStep(B, numel, K, delta=0.0, alpha=0.5, window=5, seed=85)
+        rr = rng(850)
+        for slot in range(2):
+            ls.bind_grads(slot, [[(rr.standard_normal(n) * (1 + slot) * 1e-2).astype(np.float32) for n in numel]
+                                 for _ in range(K)])
+        ls.enable_adam()
+        ls.ctx.profile_enable(True, 64)
+        decs = [ls.step_adam(t % 2, 1e-3, 0.9, 0.999, 1e-8, 1e-2, 1.0, fused=fused)[0] for t in range(5)]
+        launches = [ls.ctx.profile_summary(kind)[0] for kind in range(3)]
+        assert launches == ([5, 5, 0] if fused else [10, 5, 5])
+        state = [[PU.to_host(x).tobytes() for x in ls.d_w[k] + ls.d_m[k] + ls.d_v[k]] for k in range(K)]
+        runs.append((decs, state, [PU.to_host(x).tobytes() for x in ls.d_glob]))
+        assert ls.oracle.steps_sync == 5 and ls.worst_ulp == 0
+        ls.close()
+    (d1, s1, g1), (d2, s2, g2) = runs
+    assert s1 == s2 and g1 == g2
+    for a, b in zip(d1, d2):
+        assert a.sync == b.sync == 1 and [x.hex() for x in a.norm_sq] == [x.hex() for x in b.norm_sq]
+
+
 @pytest.mark.parametrize("mixed", [False, True])
 def test_step_at_threshold_zero_takes_the_one_pass_kernel_with_identical_results(B, mixed):
     """selsync_step under delta = 0 runs the one-pass kernel; the three-call sequence runs the update pass
