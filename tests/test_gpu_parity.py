@@ -560,7 +560,8 @@ def test_mode0_follows_the_device_decision_after_the_threshold_changes(B):
     ls.close()
 
 
-@pytest.mark.parametrize("variant,K,mixed", [("pa", 4, False), ("ga", 4, False), ("ga", 3, True), ("pa", 3, True)])
+@pytest.mark.parametrize("variant,K,mixed", [("pa", 4, False), ("ga", 4, False), ("ga", 3, True), ("pa", 3, True),
+                                             ("ga_adam", 4, False), ("ga_adam", 3, True), ("pa_adam", 4, True)])
 def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant, K, mixed):
     """A step recorded into a HIP graph under delta = 0 (when the library expects every step to
     synchronise) and replayed after selsync_set_delta(0.3) must take the decisions of delta = 0.3:
@@ -571,16 +572,25 @@ def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant, 
     g0 = [[(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel] for _ in range(K)]
     ls.bind_grads(0, [[W.round_to_bf16_bits(a) for a in gk] for gk in g0] if mixed else g0)
     scales = [1.0, 1.0, 4.0, 1.0, 1.0, 0.25, 1.0]           # powers of two: exact in bf16 as well
-    step = ls.step if variant == "pa" else ls.step_ga
-    step(0, 0.05, 0.9, 1e-4, scales[0])                     # eager, delta = 0: synchronises
+    adam = variant.endswith("_adam")
+    AD = (1e-3, 0.9, 0.999, 1e-8, 1e-2)                      # lr, betas, eps, weight decay of the Adam variants
+    if adam:
+        ls.enable_adam()
+        (ls.step_adam if variant == "pa_adam" else ls.step_ga_adam)(0, *AD, scales[0])
+    else:
+        (ls.step if variant == "pa" else ls.step_ga)(0, 0.05, 0.9, 1e-4, scales[0])   # eager, delta = 0: synchronises
     assert ls.oracle.steps_sync == 1
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         if variant == "pa":
             ls.ctx.step(ls.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=0)
-        else:
+        elif variant == "ga":
             ls.ctx.step_ga(ls.plans[0], 0.05, 0.9, 1e-4, 1.0, first_step=0)
+        elif variant == "pa_adam":                           # the bias-correction step is recorded with the launch:
+            ls.ctx.step_adam(ls.plans[0], *AD, 1.0, step=2)  # every replay is "step 2", on both sides
+        else:
+            ls.ctx.step_ga_adam(ls.plans[0], *AD, 1.0, step=2)
     ls.ctx.set_delta(0.3)
     ls.oracle.delta = 0.3
     syncs = 0
@@ -605,11 +615,23 @@ def test_graph_captured_at_threshold_zero_follows_a_later_threshold(B, variant, 
                              None if not mixed else ls.h_c[k])
             if sync:
                 O.average_params(ls.h_w, ls.h_glob, ls.h_c, ls.h_gc)
-        else:
+        elif variant == "ga":
             O.ga_update(ls.h_grads[0], ls.h_w, ls.h_m, 0.05, 0.9, 1e-4, 1.0, False, bool(sync), ls.h_c)
+        elif variant == "pa_adam":
+            for k in range(K):
+                O.adam_update(ls.h_w[k], ls.h_m[k], ls.h_v[k], ls.h_grads[0][k], *AD, 2, 1.0,
+                              None if not mixed else ls.h_c[k])
+            if sync:
+                O.average_params(ls.h_w, ls.h_glob, ls.h_c, ls.h_gc)
+        else:
+            O.ga_update_adam(ls.h_grads[0], ls.h_w, ls.h_m, ls.h_v, *AD, 2, 1.0, bool(sync), ls.h_c)
         ls.steps_done += 1
         ls.compare()
-        if variant == "pa" and sync:
+        if adam:
+            for k in range(K):
+                for i in range(len(numel)):
+                    assert PU.to_host(ls.d_v[k][i]).tobytes() == ls.h_v[k][i].tobytes()
+        if variant.startswith("pa") and sync:
             for t2 in range(len(numel)):
                 assert PU.to_host(ls.d_glob[t2]).tobytes() == ls.h_glob[t2].tobytes()
         syncs += sync
