@@ -91,7 +91,7 @@ def parse_args():
                          "(selsync_step_adam, 28 B per parameter); plain: momentum-free SGD on plans without momentum buffers "
                          "(12 B per parameter); nesterov: selsync_step with the Nesterov step direction")
     ap.add_argument("--window", type=int, default=0, help="EWMA window (default: the workload's, 25)")
-    ap.add_argument("--reps", type=int, default=1,
+    ap.add_argument("--reps", type=int, default=5,
                     help="after the timed region, time this many minus one further regions of --steps steps each and "
                          "report median / min / max of all of them beside the headline figures")
     ap.add_argument("--workers", type=int, default=0, help="replicas K held on the GPU (default: the workload's)")
