@@ -106,7 +106,7 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel (1 GiB read + 1 GiB written, 3 times) so "
                          "that FETCH_SIZE / WRITE_SIZE counters can be scaled by a kernel of known traffic")
-    ap.add_argument("--cpu-steps", type=int, default=8, help="oracle local steps timed for the CPU baseline")
+    ap.add_argument("--cpu-steps", type=int, default=16, help="oracle local steps timed for the CPU baseline")
     ap.add_argument("--no-survey", action="store_true",
                     help="skip the per-kernel survey after the timed region (other_kernels becomes null)")
     ap.add_argument("--survey-max-steps", type=int, default=30,

@@ -91,6 +91,14 @@ def test_null_arguments_are_errors_not_crashes(B):
     assert B.selsync_get_stats(None, None, None) == B.SELSYNC_ERR_INVALID_ARG
     assert B.selsync_read_decision(None, None, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
     assert B.selsync_profile_enable(None, 1, 10) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_step_bsp(None, None, None, None, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_step_bsp_adam(None, None, None, None, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_step_ga(None, None, None, None, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_ga_update_adam(None, None, None, 0, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_step_ga_adam(None, None, None, None, 0, None, None, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    # the allocation-free entry point validates on the host before it touches the GPU
+    assert B.selsync_grad_norm_sq_noalloc(None, 1, 1.0, None, None) == B.SELSYNC_ERR_INVALID_ARG
+    assert B.selsync_status_string(B.SELSYNC_ERR_TOO_LARGE) == b"SELSYNC_ERR_TOO_LARGE"
 
 
 def chunk_preview(B, numel, chunk, lead=None):
