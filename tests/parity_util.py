@@ -89,6 +89,14 @@ class LockStep:
         # Replicas are independent and every call is the unchanged single-threaded oracle routine, so
         # no sum changes its order; it only shortens full-size multi-hundred-step runs.
         self.pool = ThreadPoolExecutor(oracle_threads) if oracle_threads > 1 else None
+        # runs of whole tensors of about equal size, one per spare oracle thread of a worker
+        runs, numel = max(1, oracle_threads // K), [int(n) for n in shapes_numel]
+        cuts, acc, total = [0], 0, sum(numel)
+        for t, n in enumerate(numel):
+            acc += n
+            if len(cuts) < runs and acc * runs >= total * len(cuts) and t + 1 < len(numel):
+                cuts.append(t + 1)
+        self._tensor_runs = list(zip(cuts, cuts[1:] + [len(numel)]))
         self.momentum_free = momentum_free       # no momentum buffers on either side (plain SGD)
         self.numel = list(shapes_numel)
         if init_params is None:
@@ -192,19 +200,21 @@ class LockStep:
         """Oracle side of Alg. 1 lines 8-13 for all K workers: norms, trackers, local updates."""
         g = self.h_grads[slot]
 
-        def update(k):
-            O.sgd_update(self.h_w[k], None if self.momentum_free else self.h_m[k], g[k], lr, mu, wd, gs, first,
-                         None if not self.mixed else self.h_c[k], nesterov=nesterov)
+        def update(k, lo=0, hi=None):
+            O.sgd_update(self.h_w[k][lo:hi], None if self.momentum_free else self.h_m[k][lo:hi], g[k][lo:hi], lr, mu,
+                         wd, gs, first, None if not self.mixed else self.h_c[k][lo:hi], nesterov=nesterov)
 
         if self.pool is None:
             rec = self.oracle.track(g, gs)
             for k in range(self.K):
                 update(k)
         else:
-            # norms first (they read the gradients only), handed to the trackers in worker order
+            # norms first (they read the gradients only; each worker's sum stays one sequential pass), handed to
+            # the trackers in worker order; the update is elementwise, so spare threads take runs of whole tensors
             xs = list(self.pool.map(lambda k: O.norm_sq(g[k], gs), range(self.K)))
             rec = self.oracle.track_norms(xs)
-            list(self.pool.map(update, range(self.K)))
+            list(self.pool.map(lambda job: update(*job), [(k, lo, hi) for k in range(self.K)
+                                                          for lo, hi in self._tensor_runs]))
         return rec
 
     def _oracle_average(self):
@@ -380,7 +390,7 @@ class LockStep:
 
 def run_workload(B, wl: W.Workload, steps: Optional[int] = None, compare_every: int = 1, fused: bool = True,
                  tuning: Optional[dict] = None, pool: Optional[int] = None, oracle_threads: int = 1,
-                 progress_every: int = 0) -> LockStep:
+                 progress_every: int = 0, progress=print) -> LockStep:
     """Run a whole seeded workload in lock step and return the runner (with counters).  Decisions,
     norms and Delta are compared every step; tensors every `compare_every` steps (0: never on request),
     at every synchronising step and after the last step."""
@@ -398,8 +408,8 @@ def run_workload(B, wl: W.Workload, steps: Optional[int] = None, compare_every: 
         dec, rec = ls.step(t % pool, wl.lr, wl.momentum, wl.weight_decay, sig[t], fused=fused,
                            compare_tensors=cmp_now)
         if progress_every and (t + 1) % progress_every == 0:
-            print("  %s step %d/%d: %d sync so far, min |Delta - delta| %.3g (%.0f s)" % (
-                wl.name, t + 1, steps, ls.oracle.steps_sync, ls.min_margin, time.time() - t0), flush=True)
+            progress("  %s step %d/%d: %d sync so far, min |Delta - delta| %.3g (%.0f s)" % (
+                wl.name, t + 1, steps, ls.oracle.steps_sync, ls.min_margin, time.time() - t0))
     st = ls.ctx.stats()
     assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
     assert st["lssr"] == ls.oracle.lssr

@@ -1,6 +1,9 @@
-"""Full-size parity: the VGG11-shaped workload (132,863,336 fp32 parameters, K = 4) in
-the launch configuration bench.py times (library defaults), three steps ending in a
-synchronisation, every tensor compared with the CPU oracle element by element."""
+"""Full-size parity in the launch configuration bench.py times (library defaults): the VGG11-shaped
+workload (132,863,336 fp32 parameters, K = 4) and the three other stated configurations at their stated
+sizes, worker counts and step counts, compared with the CPU oracle element by element.
+
+The whole-schedule tests take one to two minutes each, nearly all of it in the oracle: they print a
+progress line past pytest's capture every few dozen steps, so that a watcher sees the run is alive."""
 import time
 
 import numpy as np
@@ -12,6 +15,14 @@ torch = pytest.importorskip("torch")
 
 from paper_2307_07950_amd import workloads as W                 # noqa: E402
 from tests import parity_util as PU                             # noqa: E402
+
+
+@pytest.fixture
+def progress(capsys):
+    def emit(line):
+        with capsys.disabled():
+            print(line, flush=True)
+    return emit
 
 
 def test_vgg11_like_full_size_three_steps_with_sync():
@@ -41,7 +52,7 @@ def test_vgg11_like_full_size_three_steps_with_sync():
     ls.close()
 
 
-def test_vgg11_like_full_size_all_200_steps():
+def test_vgg11_like_full_size_all_200_steps(progress):
     """The 133M-parameter configuration exactly as stated -- full size, K = 4, all 200 steps, library
     defaults (the launch configuration bench.py times): decisions, norms and Delta compared with the
     oracle after every step, every tensor of every replica at each synchronising step and at the end."""
@@ -50,13 +61,36 @@ def test_vgg11_like_full_size_all_200_steps():
     from paper_2307_07950_amd import binding as B
     wl = W.get("c4")
     assert (wl.num_params, wl.num_workers, wl.steps) == (132_863_336, 4, 200)
-    ls = PU.run_workload(B, wl, compare_every=0, oracle_threads=wl.num_workers, progress_every=20)
+    ls = PU.run_workload(B, wl, compare_every=0, oracle_threads=16, progress_every=50, progress=progress)
     print("%s: steps=%d sync=%d lssr=%.3f min|Delta-delta|=%.3g worst norm rel=%.2g worst ulp=%d forced=%d" % (
         wl.name, ls.steps_done, ls.oracle.steps_sync, ls.oracle.lssr, ls.min_margin, ls.worst_norm_rel,
         ls.worst_ulp, ls.forced), flush=True)
     assert ls.steps_done == 200 and ls.oracle.steps_sync >= 7
     assert ls.forced == 0 and ls.min_margin > 1e-3
     assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-10
+    ls.close()
+
+
+@pytest.mark.parametrize("name,params,workers,steps", [("c2", 44_541_480, 8, 200), ("c3", 61_100_840, 8, 200),
+                                                       ("c5", 61_212_158, 8, 500)])
+def test_other_workloads_full_size_all_steps(name, params, workers, steps, progress):
+    """The ResNet-, AlexNet- and Transformer-shaped configurations exactly as stated: full size, K = 8, all 200 / 200 /
+    500 steps, library defaults.  Decisions, norms and Delta are compared with the oracle after every step, every tensor
+    at each synchronising step and at the end (the AlexNet- and Transformer-shaped schedules have a constant gradient
+    scale and never reach their thresholds: for them the chain of 200 / 500 local updates is what is checked)."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2307_07950_amd import binding as B
+    wl = W.get(name)
+    assert (wl.num_params, wl.num_workers, wl.steps) == (params, workers, steps)
+    ls = PU.run_workload(B, wl, compare_every=0, oracle_threads=16, progress_every=100, progress=progress)
+    print("%s: steps=%d sync=%d lssr=%.3f min|Delta-delta|=%.3g worst norm rel=%.2g worst ulp=%d forced=%d" % (
+        wl.name, ls.steps_done, ls.oracle.steps_sync, ls.oracle.lssr, ls.min_margin, ls.worst_norm_rel,
+        ls.worst_ulp, ls.forced), flush=True)
+    assert ls.steps_done == steps and ls.forced == 0 and ls.min_margin > 1e-3
+    assert ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-9
+    if name == "c2":
+        assert ls.oracle.steps_sync >= 1
     ls.close()
 
 
