@@ -336,12 +336,16 @@ def main():
     kern = [ctx.profile_summary(kind) for kind in range(3)]
     ctx.profile_enable(False)
     rep_ms = [elapsed / args.steps * 1e3]
+    rep_sync, seen = [s1["steps_sync"] - s0["steps_sync"]], s1["steps_sync"]
     for rep in range(1, max(1, args.reps)):
         torch.cuda.synchronize()
         r0 = time.perf_counter()
         run(args.warmup + rep * args.steps, args.steps)
         torch.cuda.synchronize()
         rep_ms.append((time.perf_counter() - r0) / args.steps * 1e3)
+        now = ctx.stats()["steps_sync"]
+        rep_sync.append(now - seen)
+        seen = now
 
     # Per-kernel survey: the same schedule continued, every kernel bracketed by events and the stream drained
     # after every step, until a synchronising step has happened -- so that the line carries the aggregation
@@ -510,7 +514,13 @@ def main():
         }
     if len(rep_ms) > 1:
         srt = sorted(rep_ms)
-        result["repeats"] = {"ms_per_step": rep_ms, "median": srt[len(srt) // 2], "min": srt[0], "max": srt[-1]}
+        result["repeats"] = {"ms_per_step": rep_ms, "median": srt[len(srt) // 2], "min": srt[0], "max": srt[-1],
+                             "sync_steps": rep_sync,
+                             "all_regions": {"steps": args.steps * len(rep_ms), "sync_steps": sum(rep_sync),
+                                             "lssr": 1.0 - sum(rep_sync) / float(args.steps * len(rep_ms)),
+                                             "steps_per_s": 1e3 * len(rep_ms) / sum(rep_ms)},
+                             "note": "region 0 is `value`; the later regions continue the workload's schedule, so "
+                                     "each holds the synchronising steps that fall into it"}
     if args.variant == "pa" and result.get("roofline"):
         # context for the roofline fraction: what a plain library copy kernel (1 GiB read + 1 GiB written)
         # sustains on this very box, measured after the timed region
