@@ -392,6 +392,9 @@ int32_t selsync_step_ga_adam(selsync_ctx *ctx, selsync_plan *plan, const selsync
  * All calls on one GPU share the array: calls that may overlap in time on one GPU (different
  * streams, different threads) race and must be serialised by the caller.  Nothing in the array
  * needs clearing between calls (a call writes every slot it reads).
+ * The first call on a GPU looks up the array's device address, and, as the first launch of any
+ * kernel of a library does, makes the runtime load the library's device image there: a caller that
+ * must not trigger that inside a capture or a timed loop makes one call beforehand.
  */
 int32_t selsync_grad_norm_sq_noalloc(const selsync_tensor_list *grads, int32_t num_workers, float grad_scale,
                                      double *norm_sq_out, void *stream);

@@ -90,6 +90,36 @@ def test_unaligned_tensors_zero_and_constant_gradients(B):
     assert out1.item() == 0.0
 
 
+def test_can_be_recorded_into_a_hip_graph_and_replayed(B):
+    """Callers under graph capture are who the entry point is for: record it once, replay it several times with
+    eager work and synchronisations in between, and compare every replay with an eager call on the same data."""
+    K, numel = 3, [70001, 33, 4099, 0]
+    gen = torch.Generator(device="cuda").manual_seed(904)
+    grads = [[torch.randn(n, device="cuda", generator=gen) * 0.01 for n in numel] for _ in range(K)]
+    out_g = torch.full((K,), -1.0, dtype=torch.float64, device="cuda")
+    out_e = torch.full((K,), -1.0, dtype=torch.float64, device="cuda")
+    B.grad_norm_sq_noalloc(grads, out_e, 0.5)          # first call on this GPU outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.grad_norm_sq_noalloc(grads, out_g, 0.5)
+    torch.cuda.synchronize()
+    assert out_g.cpu().tolist() == [-1.0] * K          # the capture itself runs nothing
+    for rep in range(4):
+        for k in range(K):                             # eager work between replays: new gradient values in place
+            for x in grads[k]:
+                x.mul_(1.0 + 0.25 * (rep + k))
+        g.replay()
+        torch.cuda.synchronize()
+        B.grad_norm_sq_noalloc(grads, out_e, 0.5)
+        torch.cuda.synchronize()
+        assert [x.hex() for x in out_g.cpu().tolist()] == [x.hex() for x in out_e.cpu().tolist()]
+        want = [O.norm_sq([PU.to_host(x) for x in grads[k]], 0.5) for k in range(K)]
+        for k in range(K):
+            assert out_g[k].item() == pytest.approx(want[k], rel=1e-12)
+    del g
+
+
 def test_limits_and_argument_errors(B):
     out = torch.zeros(65, dtype=torch.float64, device="cuda")
     g = [torch.zeros(16, device="cuda")]
