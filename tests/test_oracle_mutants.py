@@ -45,6 +45,20 @@ MUT = [
  ("ga leaves stale bf16 copies", "copies[k][t][...] = f32_to_bf16(params[k][t])\n\n\ndef ga_update_adam", "pass\n\n\ndef ga_update_adam", PY),
  ("ga adam applies own gradient", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)", "adam_update(params[k], m[k], v[k], grads[k], lr, beta1, beta2, eps, weight_decay, step, grad_scale)", PY),
  ("ga adam scales the mean again", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, grad_scale)", PY),
+ # Adam as the local update (C source)
+ ("adam second moment not squared", "float t5 = t4 * gd;\n        float vn = t3 + t5;\n        float mh = mn / bc1;\n        float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16", "float t5 = t4;\n        float vn = t3 + t5;\n        float mh = mn / bc1;\n        float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16"),
+ ("adam no bias correction of v", "float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16", "float vh = vn;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16"),
+ ("adam eps under the root", "float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16", "float den = sqrtf(vh + eps);\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16"),
+ ("adam first step keeps stale buffers", "float mo = first ? 0.0f : m[j];\n        float vo = first ? 0.0f : v[j];\n        float t1 = b1 * mo;\n        float t2 = omb1 * gd;\n        float mn = t1 + t2;\n        float t3 = b2 * vo;\n        float t4 = omb2 * gd;\n        float t5 = t4 * gd;\n        float vn = t3 + t5;\n        float mh = mn / bc1;\n        float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16", "float mo = m[j];\n        float vo = v[j];\n        float t1 = b1 * mo;\n        float t2 = omb1 * gd;\n        float mn = t1 + t2;\n        float t3 = b2 * vo;\n        float t4 = omb2 * gd;\n        float t5 = t4 * gd;\n        float vn = t3 + t5;\n        float mh = mn / bc1;\n        float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16"),
+ # tracker window and conventions (C source)
+ ("tracker keeps one value too many", "if (t->len == t->window) {\n        memmove(t->hist, t->hist + 1, (size_t)(t->window - 1) * sizeof(double));\n        t->len -= 1;\n    }\n    t->hist[t->len++] = x;", "t->hist[t->len < t->window ? t->len++ : t->window - 1] = x;"),
+ ("tracker first step compares with zero", "if (!t->has_prev) {\n        delta = 0.0;\n    } else if", "if (0) {\n        delta = 0.0;\n    } else if"),
+ # partitioner and counters (oracle/selsync_oracle.py)
+ ("seldp rotates the other way", "order.extend(chunks[(worker + j) % num_workers])", "order.extend(chunks[(worker - j) % num_workers])", PY),
+ ("seldp does not rotate", "order.extend(chunks[(worker + j) % num_workers])", "order.extend(chunks[j % num_workers])", PY),
+ ("chunks give the extra sample to the last workers", "size = base + (1 if c < rem else 0)", "size = base + (1 if c >= num_workers - rem else 0)", PY),
+ ("lssr counts synchronising steps", "return self.steps_local / tot if tot else float(\"nan\")", "return self.steps_sync / tot if tot else float(\"nan\")", PY),
+ ("all workers must agree to synchronise", "sync = int(any(fs))", "sync = int(all(fs))", PY),
  ("ga local step averages anyway", "    if not sync:\n        for k in range(K):\n            sgd_update(", "    if False:\n        for k in range(K):\n            sgd_update(", PY),
 ]
 

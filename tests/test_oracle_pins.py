@@ -912,6 +912,14 @@ def test_partitioning_properties(D, N):
             assert len({owner[orders[n][pos]] for n in range(N)}) == N
 
 
+@pytest.mark.parametrize("D,N", [(100, 4), (103, 4), (7, 3), (5, 8), (0, 3), (1001, 16), (17, 1)])
+def test_chunks_are_numpys_array_split(D, N):
+    # the paper speaks of equal-sized chunks only; when N does not divide D the first D mod N chunks hold one
+    # sample more -- the convention of numpy.array_split, re-called here as the independent routine
+    want = [a.tolist() for a in np.array_split(np.arange(D), N)]
+    assert O.partition_chunks(D, N) == want
+
+
 # =============================================================== end to end, independent re-derivation
 
 def test_c1_decision_sequence_matches_independent_numpy_pandas_run():
