@@ -45,6 +45,13 @@ MUT = [
  ("ga leaves stale bf16 copies", "copies[k][t][...] = f32_to_bf16(params[k][t])\n\n\ndef ga_update_adam", "pass\n\n\ndef ga_update_adam", PY),
  ("ga adam applies own gradient", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)", "adam_update(params[k], m[k], v[k], grads[k], lr, beta1, beta2, eps, weight_decay, step, grad_scale)", PY),
  ("ga adam scales the mean again", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, 1.0)", "adam_update(params[k], m[k], v[k], gbar, lr, beta1, beta2, eps, weight_decay, step, grad_scale)", PY),
+ # mixed precision (C source)
+ ("bf16 widening shifts by 15", "uint32_t u = ((uint32_t)h) << 16;", "uint32_t u = ((uint32_t)h) << 15;"),
+ ("mixed sgd copy taken before the step", "master[j] = master[j] - stepv;\n        copy[j] = selsync_oracle_f32_to_bf16(master[j]);\n    }\n}\n\n/*\n * Momentum-free", "copy[j] = selsync_oracle_f32_to_bf16(master[j]);\n        master[j] = master[j] - stepv;\n    }\n}\n\n/*\n * Momentum-free"),
+ ("mixed sgd steps the rounded copy", "float dec = wd * master[j];\n        float d = gh + dec;\n        float mom;\n        if (first) {\n            mom = d;\n        } else {\n            float mm = mu * m[j];\n            mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        master[j] = master[j] - stepv;", "float dec = wd * master[j];\n        float d = gh + dec;\n        float mom;\n        if (first) {\n            mom = d;\n        } else {\n            float mm = mu * m[j];\n            mom = mm + d;\n        }\n        float stepv = lr * mom;\n        m[j] = mom;\n        master[j] = selsync_oracle_bf16_to_f32(copy[j]) - stepv;"),
+ ("mixed norm of the unscaled gradient", "float gh = grad_scale * selsync_oracle_bf16_to_f32(g[j]);\n        acc +=", "float gh = selsync_oracle_bf16_to_f32(g[j]);\n        acc +="),
+ ("mixed average leaves worker copies stale", "masters[k][j] = mean;\n            copies[k][j] = h;", "masters[k][j] = mean;"),
+ ("mixed average rounds the masters too", "global_master[j] = mean;\n        global_copy[j] = h;", "mean = selsync_oracle_bf16_to_f32(h);\n        global_master[j] = mean;\n        global_copy[j] = h;"),
  # Adam as the local update (C source)
  ("adam second moment not squared", "float t5 = t4 * gd;\n        float vn = t3 + t5;\n        float mh = mn / bc1;\n        float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16", "float t5 = t4;\n        float vn = t3 + t5;\n        float mh = mn / bc1;\n        float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16"),
  ("adam no bias correction of v", "float vh = vn / bc2;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16", "float vh = vn;\n        float num = lr * mh;\n        float den = sqrtf(vh) + eps;\n        float q = num / den;\n        m[j] = mn;\n        v[j] = vn;\n        w[j] = w[j] - q;\n    }\n}\n\nvoid selsync_oracle_adam_bf16"),
