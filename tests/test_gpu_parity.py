@@ -1058,6 +1058,28 @@ def test_more_workers_than_one_tracker_round(B, K, mixed):
     ls.close()
 
 
+def test_the_largest_worker_count_a_context_accepts(B):
+    # 1024 workers is the limit of selsync_create: 64 tracker rounds, run-time K in every K-way kernel
+    K = 1024
+    with pytest.raises(B.SelSyncError):
+        B.SelSync(K + 1, 0.2)
+    numel = [300, 0, 5]
+    ls = PU.LockStep(B, numel, K, delta=0.2, window=4, seed=61)
+    r = rng(190)
+    for slot in range(2):
+        ls.bind_grads(slot, [[(r.standard_normal(n) * 1e-2 * (1 + 3 * slot) * (1.0 + 0.001 * k)).astype(np.float32)
+                              for n in numel] for k in range(K)])
+    syncs = 0
+    for t in range(4):
+        dec, rec = ls.step([0, 0, 1, 1][t], 0.05, 0.9, 1e-4, 1.0, fused=(t % 2 == 0))
+        syncs += rec.sync
+        assert len(dec.norm_sq) == K and dec.flags == rec.flags
+    dec, rec = ls.step_ga(0, 0.05, 0.9, 1e-4, 1.0)
+    dec, rec = ls.step_bsp(1, 0.05, 0.9, 1e-4, 1.0)
+    assert 0 < syncs < 4 and ls.worst_ulp == 0 and ls.worst_norm_rel < 1e-12
+    ls.close()
+
+
 # ================================================================= tensors anywhere in an arena
 
 @pytest.mark.parametrize("off_w,off_g", [(37, 37), (37, 41), (100, 4), (255, 255), (260, 0), (64, 192), (129, 2)])
