@@ -380,7 +380,7 @@ def test_fused_step_is_bit_identical_to_three_calls(B):
         assert [x.hex() for x in a.delta] == [x.hex() for x in b.delta]
 
 
-@pytest.mark.parametrize("window,alpha", [(1, 0.16), (25, 0.04), (25, 1.0), (200, 0.16), (3, 0.5)])
+@pytest.mark.parametrize("window,alpha", [(1, 0.16), (25, 0.04), (25, 1.0), (200, 0.16), (3, 0.5), (2048, 0.01)])
 def test_tracker_matches_oracle_for_windows_and_alphas(B, window, alpha):
     numel = [3000]
     K = 2
@@ -395,6 +395,20 @@ def test_tracker_matches_oracle_for_windows_and_alphas(B, window, alpha):
     assert ls.oracle.steps_sync > 0 and ls.oracle.steps_local > 0
     st = ls.ctx.stats()
     assert st["max_delta"] == pytest.approx(ls.oracle.max_delta, rel=1e-9)
+    ls.close()
+
+
+def test_the_largest_window_a_context_accepts(B):
+    # 65536 is the limit of selsync_create; the window never fills here, the state only has to be laid out for it
+    with pytest.raises(B.SelSyncError):
+        B.SelSync(2, 0.3, window=65537)
+    ls = PU.LockStep(B, [3000], 2, delta=0.05, window=65536, alpha=0.3, seed=15)
+    ls.bind_grads(0, [[rng(65 + k).standard_normal(3000).astype(np.float32)] for k in range(2)])
+    for t, gs in enumerate([1.0, 1.0, 1.5, 1.5, 0.7, 0.7, 0.7, 2.0]):
+        ls.step(0, 0.01, 0.9, 0.0, gs)
+    assert ls.oracle.steps_sync > 0 and ls.oracle.steps_local > 0
+    blob = ls.ctx.get_state()                          # the checkpoint carries the whole (mostly empty) window
+    assert len(blob) > 2 * 65536 * 8
     ls.close()
 
 
