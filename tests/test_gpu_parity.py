@@ -709,6 +709,45 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed(B):
     graphed.close()
 
 
+# ================================================================= caller-owned streams
+
+def test_two_contexts_on_two_caller_streams_do_not_interfere(B):
+    """Everything is ordered on the caller's stream and a context shares nothing with another one: two
+    contexts (different K, shapes, precisions) step at the same time on two non-default streams, nothing
+    blocks between the enqueues, and each matches the oracle step by step."""
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    numel_a, numel_b = [3_000_001, 70001, 0, 33], [2_000_003, 4096, 5]
+    a = PU.LockStep(B, numel_a, 3, delta=0.2, window=5, alpha=0.5, seed=31)
+    b = PU.LockStep(B, numel_b, 2, delta=0.1, window=4, alpha=0.5, mixed=True, seed=32)
+    r = rng(310)
+    a.bind_grads(0, [[(r.standard_normal(n) * 1e-2).astype(np.float32) for n in numel_a] for _ in range(3)])
+    b.bind_grads(0, [[W.round_to_bf16_bits((r.standard_normal(n) * 1e-2).astype(np.float32)) for n in numel_b]
+                     for _ in range(2)])
+    torch.cuda.synchronize()                   # the uploads ran on the default stream
+    gs_a = [1.0, 1.0, 2.5, 2.5, 2.5, 0.5, 0.5]
+    gs_b = [1.0, 3.0, 3.0, 1.0, 1.0, 1.0, 2.0]
+    for t in range(7):
+        with torch.cuda.stream(s1):
+            a.ctx.step(a.plans[0], 0.05, 0.9, 1e-4, gs_a[t], first_step=int(t == 0))       # not blocking
+        with torch.cuda.stream(s2):
+            b.ctx.step(b.plans[0], 0.02, 0.8, 0.0, gs_b[t], first_step=int(t == 0))
+        s1.synchronize()
+        s2.synchronize()
+        for ls, (lr, mu, wd), gs in ((a, (0.05, 0.9, 1e-4), gs_a[t]), (b, (0.02, 0.8, 0.0), gs_b[t])):
+            dec = ls.ctx.read_decision()
+            rec = ls._oracle_track_and_update(0, lr, mu, wd, gs, t == 0, False)
+            sync = ls._check_decision(dec, rec)
+            if sync:
+                ls._oracle_average()
+            ls.steps_done += 1
+            ls.compare(after_sync=bool(sync))
+    for ls in (a, b):
+        assert ls.oracle.steps_sync > 0 and ls.oracle.steps_local > 0 and ls.worst_ulp == 0 and ls.forced == 0
+        st = ls.ctx.stats()
+        assert st["steps_sync"] == ls.oracle.steps_sync and st["steps_local"] == ls.oracle.steps_local
+        ls.close()
+
+
 # ================================================================= fully synchronous step in one pass
 
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 8, 17])
