@@ -209,12 +209,14 @@ class LockStep:
             for k in range(self.K):
                 update(k)
         else:
-            # norms first (they read the gradients only; each worker's sum stays one sequential pass), handed to
-            # the trackers in worker order; the update is elementwise, so spare threads take runs of whole tensors
-            xs = list(self.pool.map(lambda k: O.norm_sq(g[k], gs), range(self.K)))
-            rec = self.oracle.track_norms(xs)
-            list(self.pool.map(lambda job: update(*job), [(k, lo, hi) for k in range(self.K)
-                                                          for lo, hi in self._tensor_runs]))
+            # The norms only read the gradients and the update of Alg. 1 line 9 does not wait for the decision,
+            # so both are handed to the pool at once.  Each worker's norm stays one sequential pass (handed to
+            # the trackers in worker order); the update is elementwise, so it is cut into runs of whole tensors.
+            norms = [self.pool.submit(O.norm_sq, g[k], gs) for k in range(self.K)]
+            updates = [self.pool.submit(update, k, lo, hi) for k in range(self.K) for lo, hi in self._tensor_runs]
+            rec = self.oracle.track_norms([f.result() for f in norms])
+            for f in updates:
+                f.result()
         return rec
 
     def _oracle_average(self):
